@@ -1,0 +1,236 @@
+/*
+ * computron.h — C ABI of the MI355X model-swapping library.
+ *
+ * One GPU's share of "model parallel swapping" (Computron, arXiv 2306.13835):
+ * the fp16 parameters of one tensor-parallel rank of an OPT decoder live in
+ * page-locked host memory (Section 3.2, last paragraph), are swapped into a
+ * device arena when the model is requested and swapped out again when a
+ * least-recently-used replacement policy needs the room (Section 3, demand
+ * paging; Section 4, LRU).  Loads, offloads and inference run on three
+ * separate streams (Section 3.2).  Beyond the paper, a load is split layer by
+ * layer and every layer signals an event, so the forward pass of the same
+ * model may start as soon as its first layers have landed.
+ *
+ * Conventions
+ *   - Every function returns 0 (CTN_OK) or a negative CTN_E_* code; nothing
+ *     throws across the boundary.  After CTN_E_HIP, ctn_last_hip_error()
+ *     returns the HIP status that caused it.
+ *   - "host" pointers are ordinary process addresses; "device" pointers are
+ *     HIP device addresses.  Each argument says which it is.
+ *   - The library never allocates or frees device memory: the arena, the
+ *     workspace and the streams belong to the caller and must outlive the
+ *     context.  It owns only host-side descriptors and its events.
+ *   - A context is not thread safe; use one host thread per context.
+ */
+#ifndef COMPUTRON_H
+#define COMPUTRON_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+#pragma GCC visibility push(default) /* the entry points below are the library's only exports */
+
+typedef struct ctn_ctx ctn_ctx;
+typedef int32_t ctn_model;
+
+enum {
+  CTN_OK = 0,
+  CTN_E_INVAL = -1,   /* bad argument: null, inconsistent description, size/shape mismatch, misalignment */
+  CTN_E_TOO_BIG = -2, /* shard larger than the budget or the arena */
+  CTN_E_NOMODEL = -3, /* unknown model handle */
+  CTN_E_BUSY = -4,    /* no room can be made (nothing evictable) */
+  CTN_E_HIP = -5,     /* a HIP call failed; see ctn_last_hip_error() */
+  CTN_E_SHAPE = -6,   /* batch/seq outside what the model or the workspace allows */
+  CTN_E_NOMEM = -7    /* host allocation failed / workspace too small for the library's tables */
+};
+
+enum { CTN_XFER_DMA = 0, CTN_XFER_KERNEL = 1 };
+
+/* One rank's share of an OPT decoder.  heads, ffn and vocab are those of the
+ * whole model; the rank owns heads/tp heads, ffn/tp hidden units, vocab/tp
+ * token rows.  Requirements: hidden % heads == 0, head size 64 or 128,
+ * heads % tp == 0, ffn % tp == 0, vocab % tp == 0, (hidden/tp) % 8 == 0,
+ * (ffn/tp) % 8 == 0, 0 <= rank < tp, max_pos >= 1. */
+typedef struct {
+  int32_t layers, hidden, ffn, heads, vocab, max_pos, tp, rank;
+} ctn_model_desc;
+
+/* One parameter tensor, fp16, C-contiguous.  host_ptr (host, also readable
+ * and writable by the device: memory from ctn_host_alloc or any other
+ * hipHostMalloc'ed mapping) stays the caller's and must stay valid until the
+ * context is destroyed.  nbytes must equal 2*prod(shape) and be a multiple
+ * of 16; host_ptr must be 16-byte aligned. */
+typedef struct {
+  void* host_ptr;
+  uint64_t nbytes;
+  int32_t ndim;      /* 1 or 2 */
+  int64_t shape[2];  /* shape[1] ignored when ndim == 1 */
+} ctn_param;
+
+typedef struct {
+  uint64_t hbm_budget_bytes; /* cap on the parameter bytes resident at once (arena bytes only) */
+  void* arena_dev;           /* device; 256-byte aligned; holds resident shards */
+  uint64_t arena_bytes;
+  void* workspace_dev;       /* device; 256-byte aligned; activations + the library's tables */
+  uint64_t workspace_bytes;
+  void* stream_compute;      /* hipStream_t; inference kernels */
+  void* stream_h2d;          /* hipStream_t; swap-in  */
+  void* stream_d2h;          /* hipStream_t; swap-out */
+  int32_t transfer_mode;     /* CTN_XFER_DMA: one hipMemcpyAsync per tensor (the paper's per-tensor
+                                messages, Section 5.1); CTN_XFER_KERNEL: one copy kernel per layer */
+  int32_t pipeline;          /* 0: inference waits for the whole shard (the paper's rule, Section 3.2);
+                                1: inference waits layer by layer */
+  int32_t copy_blocks;       /* workgroups of a copy kernel; 0 = library default */
+  int32_t reserved;
+} ctn_config;
+
+typedef struct {
+  uint64_t bytes_h2d, bytes_d2h;       /* parameter bytes moved so far */
+  uint64_t n_swap_in, n_swap_out;      /* completed enqueue operations */
+  uint64_t n_hit, n_miss;              /* uses that found / did not find the model resident */
+  uint64_t n_infer;
+  uint64_t resident_bytes, peak_resident_bytes;
+  uint64_t budget_bytes;
+} ctn_stats;
+
+/* Residency event, in the order decisions were taken (Section 3: replacement
+ * on demand).  kind: 0 hit, 1 miss (victims swapped out first), 2 explicit
+ * swap-out.  victims are model handles, least recently used first. */
+typedef struct {
+  int32_t kind;
+  int32_t model;
+  int32_t n_victims;
+  int32_t victims[13];
+} ctn_event;
+
+/* ---- life cycle ---------------------------------------------------------- */
+
+/* Creates a context on the current HIP device.  cfg (host) is copied. */
+int ctn_create(const ctn_config* cfg, ctn_ctx** out);
+/* Synchronises the three streams, destroys events; frees no caller memory. */
+int ctn_destroy(ctn_ctx* ctx);
+
+/* Page-locked, device-mapped host memory for parameters (Section 3.2: the
+ * host copy stays pinned so no staging copy is needed).  *out is a host
+ * pointer that kernels may also dereference.  Freed by ctn_host_free only. */
+int ctn_host_alloc(uint64_t nbytes, void** out);
+int ctn_host_free(void* p);
+
+/* Registers one rank's parameter list (Section 3.1: every worker manages its
+ * shard of every co-located model).  params (host array of n entries) lists
+ * the tensors in forward order:
+ *   embed_tokens[vocab/tp, hidden], embed_positions[max_pos+2, hidden],
+ *   per layer: ln1.w ln1.b q.w[hidden/tp, hidden] q.b k.w k.b v.w v.b
+ *              o.w[hidden, hidden/tp] o.b[hidden] ln2.w ln2.b
+ *              fc1.w[ffn/tp, hidden] fc1.b fc2.w[hidden, ffn/tp] fc2.b[hidden],
+ *   final_ln.w, final_ln.b                       (n == 16*layers + 4).
+ * Weight matrices are [out, in] row major.  hbm_budget_bytes is the manager
+ * wide budget: 0 keeps the context's value, any other value must equal it.
+ * The model starts swapped out.  Errors: CTN_E_INVAL, CTN_E_TOO_BIG. */
+int ctn_register_model(ctn_ctx* ctx, const ctn_model_desc* desc, const ctn_param* params,
+                       size_t n, uint64_t hbm_budget_bytes, ctn_model* out);
+
+/* ---- swapping (Section 3.2: load / offload entries, asynchronous) --------- */
+
+/* Counts as a use.  If the model is not resident, swaps out least recently
+ * used models until it fits, then enqueues its load on the h2d stream, layer
+ * block by layer block in forward order, one event per block.  Returns
+ * without waiting.  Resident model: success, nothing moved. */
+int ctn_swap_in(ctn_ctx* ctx, ctn_model m);
+/* Enqueues the copy of every tensor back to its host buffer on the d2h
+ * stream (after the model's last inference, on the device), then releases its
+ * arena range.  Non-resident model: success, nothing moved. */
+int ctn_swap_out(ctn_ctx* ctx, ctn_model m);
+/* Blocks the host until the model's pending load or offload has finished. */
+int ctn_wait(ctn_ctx* ctx, ctn_model m);
+/* Blocks the host until all three streams are idle. */
+int ctn_sync(ctn_ctx* ctx);
+
+/* ---- inference ------------------------------------------------------------ */
+
+/* Forward pass of the rank's shard on token ids (host, int32 [batch, seq],
+ * values in [0, vocab)): logits fp32 [batch, seq, vocab/tp].  Row-parallel
+ * products are this rank's partial sums (the cross-rank reduction is the
+ * identity on one GPU).  Counts as a use; a non-resident model is swapped in
+ * first (demand paging, Section 3).  logits_out is a device pointer when
+ * out_is_device != 0 (the call returns with the work enqueued on the compute
+ * stream), else pinned or ordinary host memory (the call returns after the
+ * logits have arrived).  Errors: CTN_E_SHAPE when seq > max_pos or the
+ * workspace cannot hold batch*seq tokens (see ctn_workspace_bytes). */
+int ctn_infer(ctn_ctx* ctx, ctn_model m, const int32_t* token_ids_host, int32_t batch, int32_t seq,
+              void* logits_out, int32_t out_is_device);
+
+/* Workspace bytes a context needs for models of this description at up to
+ * max_tokens = batch*seq tokens per inference and n_models registrations. */
+uint64_t ctn_workspace_bytes(const ctn_model_desc* desc, int64_t max_tokens, int32_t n_models);
+/* Arena bytes one shard of this description occupies (tensors padded to 256 B). */
+uint64_t ctn_arena_bytes(const ctn_model_desc* desc);
+
+/* ---- introspection -------------------------------------------------------- */
+
+int ctn_is_resident(ctn_ctx* ctx, ctn_model m, int32_t* out);
+int ctn_get_stats(ctn_ctx* ctx, ctn_stats* out);
+/* Copies up to cap events starting at index first into out (host); *n_out
+ * receives the number copied, *total the number recorded so far. */
+int ctn_get_events(ctn_ctx* ctx, uint64_t first, ctn_event* out, uint64_t cap, uint64_t* n_out,
+                   uint64_t* total);
+/* Device-timeline duration (ms) of the model's last completed load and
+ * offload, and the start-to-event time of each of its layer blocks
+ * (block_ms: host array of cap floats or NULL; blocks = layers + 1:
+ * embeddings with the final LayerNorm, then each layer).  Blocks until they have finished. */
+int ctn_last_swap_ms(ctn_ctx* ctx, ctn_model m, float* in_ms, float* out_ms, float* block_ms,
+                     int32_t cap, int32_t* n_blocks);
+/* Reads the device copy of tensor `index` of a resident model into dst (host,
+ * at least that tensor's nbytes); waits for the model's load first.  Tests. */
+int ctn_debug_read_param(ctn_ctx* ctx, ctn_model m, int32_t index, void* dst_host, uint64_t cap);
+/* Changes transfer mode / pipelining / copy-kernel width between operations. */
+int ctn_set_mode(ctn_ctx* ctx, int32_t transfer_mode, int32_t pipeline, int32_t copy_blocks);
+int ctn_last_hip_error(ctn_ctx* ctx);
+const char* ctn_strerror(int code);
+
+/* Host only, no device needed: replays a sequence of uses (trace, host array
+ * of n model indices below n_models) through the same replacement policy the
+ * context uses (Section 3 demand paging with Section 4's LRU, byte budget)
+ * and writes one event per use to out (host, n entries). */
+int ctn_residency_replay(uint64_t budget_bytes, const uint64_t* sizes, int32_t n_models,
+                         const int32_t* trace, uint64_t n, ctn_event* out);
+
+/* ---- single operations (each enqueues on `stream`, a hipStream_t; all data
+ *      pointers are device pointers unless stated) --------------------------- */
+
+enum { CTN_EPI_BIAS_F16 = 0,       /* out fp16 [M,N]  = A W^T + bias            */
+       CTN_EPI_BIAS_RELU_F16 = 1,  /* out fp16 [M,N]  = max(0, A W^T + bias)    */
+       CTN_EPI_BIAS_RESID_F32 = 2, /* out fp32 [M,N] += A W^T + bias (in place) */
+       CTN_EPI_F32 = 3 };          /* out fp32 [M,N]  = A W^T (bias ignored)    */
+
+/* Copy kernel over one byte range (16-byte multiple, 16-byte aligned ends).
+ * src/dst may each be device memory or device-mapped pinned host memory: the
+ * same kernel serves swap-in and swap-out (Section 3.2).  blocks = workgroups. */
+int ctn_op_copy(void* dst, const void* src, uint64_t nbytes, int32_t blocks, void* stream);
+/* hipMemcpyAsync of one range (the DMA engine path), for link-peak measurements. */
+int ctn_op_dma(void* dst, const void* src, uint64_t nbytes, void* stream);
+/* x fp32 [M,hidden] = token row (zero if id outside [rank*vocab_local,
+ * (rank+1)*vocab_local)) + position row (m mod seq) + 2.  ids int32 [M]. */
+int ctn_op_embed(const int32_t* ids, const void* tok_f16, const void* pos_f16, float* x, int32_t M,
+                 int32_t seq, int32_t hidden, int32_t vocab_local, int32_t rank, void* stream);
+/* out fp16 [rows,hidden] = LayerNorm(x fp32; gain, bias fp16), biased variance, eps 1e-5. */
+int ctn_op_layernorm(const float* x, const void* gain_f16, const void* bias_f16, void* out_f16,
+                     int32_t rows, int32_t hidden, void* stream);
+/* C = A[M,K] (fp16) times W[N,K]^T (fp16), fp32 accumulation on the matrix
+ * cores, then the chosen epilogue.  K % 8 == 0. */
+int ctn_op_gemm(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,
+                int32_t N, int32_t K, int32_t epilogue, void* stream);
+/* Causal self-attention of every (batch, head): qkv fp16 [batch*seq, 3*heads*d]
+ * holds q | k | v side by side; out fp16 [batch*seq, heads*d]
+ * = softmax_causal((q d^-1/2) k^T) v.  d is 64 or 128. */
+int ctn_op_attention(const void* qkv_f16, void* out_f16, int32_t batch, int32_t seq, int32_t heads,
+                     int32_t head_dim, void* stream);
+
+#pragma GCC visibility pop
+#ifdef __cplusplus
+}
+#endif
+#endif

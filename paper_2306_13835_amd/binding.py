@@ -1,0 +1,315 @@
+"""ctypes binding with the same names as include/computron.h."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcomputron_mi355.so")
+
+XFER_DMA, XFER_KERNEL = 0, 1
+EPI_BIAS_F16, EPI_BIAS_RELU_F16, EPI_BIAS_RESID_F32, EPI_F32 = 0, 1, 2, 3
+
+DECLARED_SYMBOLS = [
+    "ctn_create", "ctn_destroy", "ctn_host_alloc", "ctn_host_free", "ctn_register_model",
+    "ctn_swap_in", "ctn_swap_out", "ctn_wait", "ctn_sync", "ctn_infer", "ctn_workspace_bytes",
+    "ctn_arena_bytes", "ctn_is_resident", "ctn_get_stats", "ctn_get_events", "ctn_last_swap_ms",
+    "ctn_debug_read_param", "ctn_set_mode", "ctn_last_hip_error", "ctn_strerror",
+    "ctn_residency_replay", "ctn_op_copy", "ctn_op_dma", "ctn_op_embed", "ctn_op_layernorm",
+    "ctn_op_gemm", "ctn_op_attention",
+]
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("layers", "hidden", "ffn", "heads", "vocab", "max_pos", "tp", "rank")]
+
+
+class Param(C.Structure):
+    _fields_ = [("host_ptr", C.c_void_p), ("nbytes", C.c_uint64), ("ndim", C.c_int32),
+                ("shape", C.c_int64 * 2)]
+
+
+class Config(C.Structure):
+    _fields_ = [("hbm_budget_bytes", C.c_uint64), ("arena_dev", C.c_void_p), ("arena_bytes", C.c_uint64),
+                ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_uint64),
+                ("stream_compute", C.c_void_p), ("stream_h2d", C.c_void_p), ("stream_d2h", C.c_void_p),
+                ("transfer_mode", C.c_int32), ("pipeline", C.c_int32), ("copy_blocks", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+class Stats(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("bytes_h2d", "bytes_d2h", "n_swap_in", "n_swap_out", "n_hit",
+                                          "n_miss", "n_infer", "resident_bytes", "peak_resident_bytes",
+                                          "budget_bytes")]
+
+
+class Event(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("model", C.c_int32), ("n_victims", C.c_int32),
+                ("victims", C.c_int32 * 13)]
+
+
+class CtnError(RuntimeError):
+    def __init__(self, code: int, what: str, hip: int = 0):
+        self.code, self.hip = code, hip
+        msg = lib().ctn_strerror(code).decode()
+        super().__init__(f"{what}: {msg} ({code})" + (f", hip error {hip}" if hip else ""))
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the built library; raises if it is missing (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2306_13835_amd.build`")
+    L = C.CDLL(LIB_PATH)
+    vp, u64, i32, i64 = C.c_void_p, C.c_uint64, C.c_int32, C.c_int64
+    P = C.POINTER
+    sig = {
+        "ctn_create": (C.c_int, [P(Config), P(vp)]),
+        "ctn_destroy": (C.c_int, [vp]),
+        "ctn_host_alloc": (C.c_int, [u64, P(vp)]),
+        "ctn_host_free": (C.c_int, [vp]),
+        "ctn_register_model": (C.c_int, [vp, P(ModelDesc), P(Param), C.c_size_t, u64, P(i32)]),
+        "ctn_swap_in": (C.c_int, [vp, i32]),
+        "ctn_swap_out": (C.c_int, [vp, i32]),
+        "ctn_wait": (C.c_int, [vp, i32]),
+        "ctn_sync": (C.c_int, [vp]),
+        "ctn_infer": (C.c_int, [vp, i32, vp, i32, i32, vp, i32]),
+        "ctn_workspace_bytes": (u64, [P(ModelDesc), i64, i32]),
+        "ctn_arena_bytes": (u64, [P(ModelDesc)]),
+        "ctn_is_resident": (C.c_int, [vp, i32, P(i32)]),
+        "ctn_get_stats": (C.c_int, [vp, P(Stats)]),
+        "ctn_get_events": (C.c_int, [vp, u64, P(Event), u64, P(u64), P(u64)]),
+        "ctn_last_swap_ms": (C.c_int, [vp, i32, P(C.c_float), P(C.c_float), P(C.c_float), i32, P(i32)]),
+        "ctn_debug_read_param": (C.c_int, [vp, i32, i32, vp, u64]),
+        "ctn_set_mode": (C.c_int, [vp, i32, i32, i32]),
+        "ctn_last_hip_error": (C.c_int, [vp]),
+        "ctn_strerror": (C.c_char_p, [C.c_int]),
+        "ctn_residency_replay": (C.c_int, [u64, P(u64), i32, P(i32), u64, P(Event)]),
+        "ctn_op_copy": (C.c_int, [vp, vp, u64, i32, vp]),
+        "ctn_op_dma": (C.c_int, [vp, vp, u64, vp]),
+        "ctn_op_embed": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]),
+        "ctn_op_layernorm": (C.c_int, [vp, vp, vp, vp, i32, i32, vp]),
+        "ctn_op_gemm": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, vp]),
+        "ctn_op_attention": (C.c_int, [vp, vp, i32, i32, i32, i32, vp]),
+    }
+    for name, (res, args) in sig.items():
+        f = getattr(L, name)
+        f.restype, f.argtypes = res, args
+    _lib = L
+    return L
+
+
+def _desc(d) -> ModelDesc:
+    return ModelDesc(d.layers, d.hidden, d.ffn, d.heads, d.vocab, d.max_pos, d.tp, d.rank)
+
+
+def workspace_bytes(desc, max_tokens: int, n_models: int = 1) -> int:
+    return int(lib().ctn_workspace_bytes(C.byref(_desc(desc)), max_tokens, n_models))
+
+
+def arena_bytes(desc) -> int:
+    return int(lib().ctn_arena_bytes(C.byref(_desc(desc))))
+
+
+def _events_to_list(evs, n) -> List[Tuple[str, int, Tuple[int, ...]]]:
+    kinds = ("hit", "miss", "out")
+    return [(kinds[e.kind], e.model, tuple(e.victims[i] for i in range(min(e.n_victims, 13))))
+            for e in evs[:n]]
+
+
+def residency_replay(budget: int, sizes: Sequence[int], trace: Sequence[int]):
+    n = len(trace)
+    sz = (C.c_uint64 * len(sizes))(*[int(s) for s in sizes])
+    tr = (C.c_int32 * max(n, 1))(*[int(t) for t in trace])
+    out = (Event * max(n, 1))()
+    rc = lib().ctn_residency_replay(int(budget), sz, len(sizes), tr, n, out)
+    if rc:
+        raise CtnError(rc, "ctn_residency_replay")
+    return _events_to_list(out, n)
+
+
+class HostPool:
+    """Pinned, device-mapped host memory from ctn_host_alloc, handed out as numpy arrays."""
+
+    def __init__(self, nbytes: int):
+        self.nbytes = int(nbytes)
+        p = C.c_void_p()
+        rc = lib().ctn_host_alloc(self.nbytes, C.byref(p))
+        if rc:
+            raise CtnError(rc, f"ctn_host_alloc({nbytes})")
+        self.ptr = p.value
+        self._buf = (C.c_uint8 * self.nbytes).from_address(self.ptr)
+        self.bytes = np.frombuffer(self._buf, dtype=np.uint8)
+        self._cur = 0
+
+    def take(self, shape, dtype=np.float16, align: int = 256) -> np.ndarray:
+        n = int(np.prod(shape)) * np.dtype(dtype).itemsize
+        lo = (self._cur + align - 1) // align * align
+        if lo + n > self.nbytes:
+            raise MemoryError("HostPool exhausted")
+        self._cur = lo + n
+        return self.bytes[lo:lo + n].view(dtype).reshape(shape)
+
+    def close(self):
+        if self.ptr:
+            self.bytes = None
+            self._buf = None
+            lib().ctn_host_free(self.ptr)
+            self.ptr = None
+
+
+def _addr(a) -> int:
+    if a is None:
+        return 0
+    if isinstance(a, int):
+        return a
+    if isinstance(a, np.ndarray):
+        return a.ctypes.data
+    return int(a.data_ptr())      # torch tensor
+
+
+class Context:
+    """One ctn_ctx.  `arena`/`workspace` are torch CUDA tensors (uint8), streams are
+    torch.cuda.Stream objects; torch only provides the memory and the streams."""
+
+    def __init__(self, budget: int, arena, workspace, stream_compute, stream_h2d, stream_d2h,
+                 transfer_mode: int = XFER_KERNEL, pipeline: bool = True, copy_blocks: int = 0):
+        self._keep = (arena, workspace, stream_compute, stream_h2d, stream_d2h)
+        cfg = Config(int(budget), arena.data_ptr(), arena.numel() * arena.element_size(),
+                     workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                     stream_compute.cuda_stream, stream_h2d.cuda_stream, stream_d2h.cuda_stream,
+                     transfer_mode, int(bool(pipeline)), copy_blocks, 0)
+        h = C.c_void_p()
+        rc = lib().ctn_create(C.byref(cfg), C.byref(h))
+        if rc:
+            raise CtnError(rc, "ctn_create")
+        self.h = h
+        self._params = []
+
+    def _check(self, rc: int, what: str):
+        if rc:
+            raise CtnError(rc, what, lib().ctn_last_hip_error(self.h) if rc == -5 else 0)
+
+    def close(self):
+        if self.h:
+            rc = lib().ctn_destroy(self.h)
+            self.h = None
+            if rc:
+                raise CtnError(rc, "ctn_destroy")
+
+    def register_model(self, desc, tensors: Sequence[np.ndarray], budget: int = 0) -> int:
+        arr = (Param * len(tensors))()
+        for i, t in enumerate(tensors):
+            arr[i].host_ptr = t.ctypes.data
+            arr[i].nbytes = t.nbytes
+            arr[i].ndim = t.ndim
+            arr[i].shape[0] = t.shape[0]
+            arr[i].shape[1] = t.shape[1] if t.ndim > 1 else 0
+        out = C.c_int32(-1)
+        self._check(lib().ctn_register_model(self.h, C.byref(_desc(desc)), arr, len(tensors), int(budget),
+                                             C.byref(out)), "ctn_register_model")
+        self._params.append(list(tensors))
+        return out.value
+
+    def swap_in(self, m: int):
+        self._check(lib().ctn_swap_in(self.h, m), "ctn_swap_in")
+
+    def swap_out(self, m: int):
+        self._check(lib().ctn_swap_out(self.h, m), "ctn_swap_out")
+
+    def wait(self, m: int):
+        self._check(lib().ctn_wait(self.h, m), "ctn_wait")
+
+    def sync(self):
+        self._check(lib().ctn_sync(self.h), "ctn_sync")
+
+    def infer(self, m: int, ids: np.ndarray, out=None):
+        """ids int32 [batch, seq] (host).  `out`: None -> new numpy fp32 array (blocking);
+        a numpy array -> filled (blocking); a torch CUDA tensor -> enqueued only."""
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        b, s = ids.shape
+        is_dev = out is not None and not isinstance(out, np.ndarray)
+        if out is None:
+            vl = self._params[m][0].shape[0]
+            out = np.empty((b, s, vl), dtype=np.float32)
+        self._check(lib().ctn_infer(self.h, m, ids.ctypes.data, b, s, _addr(out), int(is_dev)), "ctn_infer")
+        return out
+
+    def is_resident(self, m: int) -> bool:
+        o = C.c_int32()
+        self._check(lib().ctn_is_resident(self.h, m, C.byref(o)), "ctn_is_resident")
+        return bool(o.value)
+
+    def stats(self) -> dict:
+        s = Stats()
+        self._check(lib().ctn_get_stats(self.h, C.byref(s)), "ctn_get_stats")
+        return {n: int(getattr(s, n)) for n, _ in Stats._fields_}
+
+    def events(self, first: int = 0):
+        n, total = C.c_uint64(), C.c_uint64()
+        self._check(lib().ctn_get_events(self.h, 0, None, 0, C.byref(n), C.byref(total)), "ctn_get_events")
+        cap = max(int(total.value) - first, 0)
+        buf = (Event * max(cap, 1))()
+        self._check(lib().ctn_get_events(self.h, first, buf, cap, C.byref(n), C.byref(total)), "ctn_get_events")
+        return _events_to_list(buf, int(n.value))
+
+    def last_swap_ms(self, m: int):
+        nb = C.c_int32()
+        self._check(lib().ctn_last_swap_ms(self.h, m, None, None, None, 0, C.byref(nb)), "ctn_last_swap_ms")
+        blocks = (C.c_float * nb.value)()
+        i, o = C.c_float(), C.c_float()
+        self._check(lib().ctn_last_swap_ms(self.h, m, C.byref(i), C.byref(o), blocks, nb.value, C.byref(nb)),
+                    "ctn_last_swap_ms")
+        return i.value, o.value, list(blocks)
+
+    def debug_read_param(self, m: int, index: int) -> np.ndarray:
+        t = self._params[m][index]
+        dst = np.empty(t.shape, dtype=t.dtype)
+        self._check(lib().ctn_debug_read_param(self.h, m, index, dst.ctypes.data, dst.nbytes),
+                    "ctn_debug_read_param")
+        return dst
+
+    def set_mode(self, transfer_mode: int, pipeline: bool, copy_blocks: int = 0):
+        self._check(lib().ctn_set_mode(self.h, transfer_mode, int(bool(pipeline)), copy_blocks), "ctn_set_mode")
+
+
+# ---- single operations (device pointers / torch tensors) ----------------------
+
+def _op(rc, what):
+    if rc:
+        raise CtnError(rc, what)
+
+
+def op_copy(dst, src, nbytes, blocks, stream):
+    _op(lib().ctn_op_copy(_addr(dst), _addr(src), nbytes, blocks, stream.cuda_stream), "ctn_op_copy")
+
+
+def op_dma(dst, src, nbytes, stream):
+    _op(lib().ctn_op_dma(_addr(dst), _addr(src), nbytes, stream.cuda_stream), "ctn_op_dma")
+
+
+def op_embed(ids, tok, pos, x, M, seq, hidden, vocab_local, rank, stream):
+    _op(lib().ctn_op_embed(_addr(ids), _addr(tok), _addr(pos), _addr(x), M, seq, hidden, vocab_local, rank,
+                           stream.cuda_stream), "ctn_op_embed")
+
+
+def op_layernorm(x, g, b, out, rows, hidden, stream):
+    _op(lib().ctn_op_layernorm(_addr(x), _addr(g), _addr(b), _addr(out), rows, hidden, stream.cuda_stream),
+        "ctn_op_layernorm")
+
+
+def op_gemm(A, W, bias, out, M, N, K, epilogue, stream):
+    _op(lib().ctn_op_gemm(_addr(A), _addr(W), _addr(bias), _addr(out), M, N, K, epilogue, stream.cuda_stream),
+        "ctn_op_gemm")
+
+
+def op_attention(qkv, out, batch, seq, heads, head_dim, stream):
+    _op(lib().ctn_op_attention(_addr(qkv), _addr(out), batch, seq, heads, head_dim, stream.cuda_stream),
+        "ctn_op_attention")

@@ -1,0 +1,168 @@
+// Causal self-attention of one tensor-parallel rank's heads, fused:
+//   out = softmax_causal((q d^-1/2) k^T) v        per (batch, head)
+// with scores, probabilities and the running maximum / sum kept in fp32
+// registers and never written to memory (one pass over the keys with a
+// running rescale).  The paper names the model only (OPT, Section 5.1); this
+// is the attention of the public OPT decoder on the heads this rank owns
+// (Section 3.1: tensor parallel workers).
+//
+// Mapping to the matrix cores (v_mfma_f32_32x32x16_f16): a wavefront owns 32
+// queries.  It forms the TRANSPOSED score tile  S^T[key, query] = K Q^T  so
+// that in the accumulator layout every lane holds one query column and 16
+// keys: the row-wise softmax statistics are then per-lane values plus one
+// exchange with lane ^ 32.  The probabilities, rounded to fp16, are fed back
+// unchanged as the B operand of  O^T[dim, query] = V^T P^T ; the contraction
+// index of that product is permuted the same way for both operands, so no
+// data movement is needed.  K and V^T tiles of 32 keys are staged in LDS and
+// shared by the 4 wavefronts (128 queries) of a workgroup.
+//
+// Share of the forward pass: ~1 % of the flops at the benchmark shapes.
+#include "kernels.h"
+
+namespace ctn {
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+constexpr int QB = 128;    // queries per workgroup (4 wavefronts x 32)
+constexpr int KT = 32;     // keys per tile
+constexpr int VT_ROW = KT + 4;
+
+template <int D>
+__global__ __launch_bounds__(256) void attention_kernel(const _Float16* __restrict__ qkv,
+                                                        _Float16* __restrict__ out, int seq, int heads) {
+  constexpr int KS = D / 16;        // MFMA steps over the head dimension
+  constexpr int DT = D / 32;        // 32-row tiles of O^T
+  constexpr int K_ROW = D + 8;
+  __shared__ __attribute__((aligned(16))) _Float16 Ks[KT][K_ROW];
+  __shared__ __attribute__((aligned(16))) _Float16 Vt[D][VT_ROW];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int HL = heads * D, ld = 3 * HL;
+  const int q0 = blockIdx.x * QB;
+  const int qw0 = q0 + wave * 32;
+  const int g = lane >> 5;
+  const int qi = qw0 + (lane & 31);               // this lane's query
+  const int qload = qi < seq ? qi : seq - 1;      // clamp: rows past the end are computed but not stored
+  const _Float16* base = qkv + static_cast<int64_t>(b) * seq * ld + head * D;
+
+  half8 qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+    qf[ks] = *reinterpret_cast<const half8*>(base + static_cast<int64_t>(qload) * ld + ks * 16 + g * 8);
+
+  float16v o[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float scale = (D == 64) ? 0.125f : 0.08838834764831845f;   // d^-1/2
+
+  const int q_last_wg = (q0 + QB - 1 < seq - 1) ? q0 + QB - 1 : seq - 1;
+  const int n_tiles = q_last_wg / KT + 1;          // key tiles up to the workgroup's diagonal
+  const int my_tiles = (qw0 + 31) / KT + 1;        // ... up to this wavefront's diagonal
+
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    const int k0 = kt * KT;
+    __syncthreads();                                // previous tile fully consumed
+    for (int c = tid; c < KT * (D / 8); c += 256) {
+      const int key = c / (D / 8), part = c % (D / 8);
+      half8 kv = {0, 0, 0, 0, 0, 0, 0, 0}, vv = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (k0 + key < seq) {
+        const _Float16* row = base + static_cast<int64_t>(k0 + key) * ld + part * 8;
+        kv = *reinterpret_cast<const half8*>(row + HL);
+        vv = *reinterpret_cast<const half8*>(row + 2 * HL);
+      }
+      *reinterpret_cast<half8*>(&Ks[key][part * 8]) = kv;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) Vt[part * 8 + e][key] = vv[e];
+    }
+    __syncthreads();
+    if (kt >= my_tiles) continue;                   // above this wavefront's diagonal (uniform per wavefront)
+
+    // S^T tile: rows = keys (A operand from LDS), columns = queries (B operand in registers)
+    float16v s;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s[e] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const half8 kf = *reinterpret_cast<const half8*>(&Ks[lane & 31][ks * 16 + g * 8]);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[ks], s, 0, 0, 0);
+    }
+    // accumulator element e of this lane is key  k0 + 8*(e/4) + 4*g + e%4
+    float m_tile = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int key = k0 + 8 * (e >> 2) + 4 * g + (e & 3);
+      s[e] = (key <= qi && key < seq) ? s[e] * scale : -INFINITY;
+      m_tile = fmaxf(m_tile, s[e]);
+    }
+    m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
+    const float m_new = fmaxf(m_run, m_tile);       // finite from the first tile on: key 0 is never masked
+    const float alpha = __expf(m_run - m_new);
+    float psum = 0.f;
+    half8 pf[2];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const float p = __expf(s[e] - m_new);
+      psum += p;
+      pf[e >> 3][e & 7] = static_cast<_Float16>(p);
+    }
+    psum += __shfl_xor(psum, 32, 64);
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+
+    // O^T += V^T P^T.  Contraction slot (step t, group g, element e) stands for
+    // key 16t + 8*(e/4) + 4g + e%4 on both operands.
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const _Float16* vrow = &Vt[dt * 32 + (lane & 31)][16 * t + 4 * g];
+        const half4 lo = *reinterpret_cast<const half4*>(vrow);
+        const half4 hi = *reinterpret_cast<const half4*>(vrow + 8);
+        const half8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[t], o[dt], 0, 0, 0);
+      }
+    }
+  }
+
+  if (qi < seq) {
+    const float inv = 1.0f / l_run;
+    _Float16* orow = out + (static_cast<int64_t>(b) * seq + qi) * HL + head * D;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        half4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = static_cast<_Float16>(o[dt][4 * r + e] * inv);
+        *reinterpret_cast<half4*>(orow + dt * 32 + 8 * r + 4 * g) = v;
+      }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_attention(const _Float16* qkv, _Float16* out, int batch, int seq, int heads, int head_dim,
+                            hipStream_t s) {
+  if (batch <= 0 || seq <= 0 || heads <= 0) return hipSuccess;
+  if (heads > 65535 || batch > 65535) return hipErrorInvalidValue;
+  const dim3 grid((seq + QB - 1) / QB, heads, batch), block(256);
+  if (head_dim == 64)
+    hipLaunchKernelGGL(attention_kernel<64>, grid, block, 0, s, qkv, out, seq, heads);
+  else if (head_dim == 128)
+    hipLaunchKernelGGL(attention_kernel<128>, grid, block, 0, s, qkv, out, seq, heads);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+}  // namespace ctn

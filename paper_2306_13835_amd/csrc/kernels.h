@@ -1,0 +1,37 @@
+// Internal launch interface of the HIP kernels (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace ctn {
+
+// ---- copy (swap-in / swap-out) ---------------------------------------------
+constexpr int kCopyMaxSegs = 16;
+struct CopySeg {
+  const void* src;
+  void* dst;
+  uint64_t n16;  // number of 16-byte units
+};
+struct CopyTable {
+  int32_t n;
+  uint32_t chunk_prefix[kCopyMaxSegs + 1];  // chunks before segment i
+  CopySeg seg[kCopyMaxSegs];
+};
+// Fills chunk_prefix from seg[].n16; returns false if the table is too large.
+bool copy_table_finish(CopyTable& t);
+hipError_t launch_copy_table(const CopyTable& t, int blocks, hipStream_t s);
+int default_copy_blocks();
+
+// ---- elementwise -------------------------------------------------------------
+hipError_t launch_embed(const int32_t* ids, const _Float16* tok, const _Float16* pos, float* x, int M,
+                        int seq, int hidden, int vocab_local, int rank, hipStream_t s);
+hipError_t launch_layernorm(const float* x, const _Float16* g, const _Float16* b, _Float16* out, int rows,
+                            int hidden, hipStream_t s);
+
+// ---- dense products ------------------------------------------------------------
+hipError_t launch_gemm(const _Float16* A, const _Float16* W, const _Float16* bias, void* out, int M, int N,
+                       int K, int epilogue, hipStream_t s);
+hipError_t launch_attention(const _Float16* qkv, _Float16* out, int batch, int seq, int heads, int head_dim,
+                            hipStream_t s);
+
+}  // namespace ctn

@@ -1,0 +1,134 @@
+// Where the tensors of one rank's OPT shard sit inside its arena range.
+//
+// The parameter list (Section 3.1: a worker holds its shard of every model)
+// arrives as 16*L+4 separate host tensors in forward order.  On the device
+// they are packed into transfer blocks that follow the forward pass, so a
+// load can signal "block b has landed" (Section 3.2 loads whole models; the
+// block split is this library's refinement):
+//   block 0      : embed_tokens, embed_positions, final_ln.w, final_ln.b
+//   block 1 + l  : the 16 tensors of decoder layer l
+// Inside a layer q.w|k.w|v.w and q.b|k.b|v.b are stored back to back so the
+// three column-parallel projections run as one product.  Every group starts
+// on a 256-byte boundary.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "computron.h"
+
+namespace ctn {
+
+constexpr uint64_t kAlign = 256;
+constexpr int kLayerTensors = 16;
+constexpr int kPosOffset = 2;  // OPT keeps position rows shifted by two
+
+inline uint64_t align_up(uint64_t x, uint64_t a = kAlign) { return (x + a - 1) / a * a; }
+
+// Index of a tensor inside a layer's 16, in list order.
+enum LayerTensor {
+  LN1_W = 0, LN1_B, Q_W, Q_B, K_W, K_B, V_W, V_B, O_W, O_B, LN2_W, LN2_B, FC1_W, FC1_B, FC2_W, FC2_B
+};
+
+struct ShardLayout {
+  ctn_model_desc d{};
+  int n_tensors = 0;
+  int n_blocks = 0;
+  uint64_t param_bytes = 0;               // sum of tensor sizes (what the budget counts)
+  uint64_t arena_bytes = 0;               // padded size of the arena range
+  std::vector<uint64_t> offset;           // per tensor (list order): byte offset in the range
+  std::vector<uint64_t> nbytes;           // per tensor
+  std::vector<int> block_of;              // per tensor
+  std::vector<std::vector<int>> block_tensors;  // per block: tensor indices in arena order
+  std::vector<uint64_t> block_bytes;      // per block: parameter bytes
+
+  int hl() const { return d.hidden / d.tp; }
+  int fl() const { return d.ffn / d.tp; }
+  int vl() const { return d.vocab / d.tp; }
+  int local_heads() const { return d.heads / d.tp; }
+  int head_dim() const { return d.hidden / d.heads; }
+  int layer_tensor(int layer, int which) const { return 2 + kLayerTensors * layer + which; }
+};
+
+inline bool desc_valid(const ctn_model_desc& d) {
+  if (d.layers < 0 || d.hidden <= 0 || d.ffn <= 0 || d.heads <= 0 || d.vocab <= 0 || d.max_pos < 1 ||
+      d.tp < 1 || d.rank < 0 || d.rank >= d.tp)
+    return false;
+  if (d.hidden % d.heads || d.heads % d.tp || d.ffn % d.tp || d.vocab % d.tp) return false;
+  int hd = d.hidden / d.heads;
+  if (hd != 64 && hd != 128) return false;
+  if ((d.hidden / d.tp) % 8 || (d.ffn / d.tp) % 8 || d.hidden % 8) return false;
+  return true;
+}
+
+// Expected shape of tensor i of the list ({rows, cols}; cols == 0 for vectors).
+inline void expected_shape(const ctn_model_desc& d, int i, int64_t& rows, int64_t& cols) {
+  const int64_t h = d.hidden, hl = d.hidden / d.tp, fl = d.ffn / d.tp;
+  const int n = kLayerTensors * d.layers + 4;
+  if (i == 0) { rows = d.vocab / d.tp; cols = h; return; }
+  if (i == 1) { rows = d.max_pos + kPosOffset; cols = h; return; }
+  if (i >= n - 2) { rows = h; cols = 0; return; }
+  switch ((i - 2) % kLayerTensors) {
+    case Q_W: case K_W: case V_W: rows = hl; cols = h; return;
+    case Q_B: case K_B: case V_B: rows = hl; cols = 0; return;
+    case O_W: rows = h; cols = hl; return;
+    case FC1_W: rows = fl; cols = h; return;
+    case FC1_B: rows = fl; cols = 0; return;
+    case FC2_W: rows = h; cols = fl; return;
+    default: rows = h; cols = 0; return;  // LayerNorm vectors, o.b, fc2.b
+  }
+}
+
+inline ShardLayout make_layout(const ctn_model_desc& d) {
+  ShardLayout L;
+  L.d = d;
+  L.n_tensors = kLayerTensors * d.layers + 4;
+  L.n_blocks = d.layers + 1;
+  L.offset.assign(L.n_tensors, 0);
+  L.nbytes.assign(L.n_tensors, 0);
+  L.block_of.assign(L.n_tensors, 0);
+  L.block_tensors.assign(L.n_blocks, {});
+  L.block_bytes.assign(L.n_blocks, 0);
+  for (int i = 0; i < L.n_tensors; ++i) {
+    int64_t r, c;
+    expected_shape(d, i, r, c);
+    L.nbytes[i] = 2ull * static_cast<uint64_t>(r) * static_cast<uint64_t>(c ? c : 1);
+    L.param_bytes += L.nbytes[i];
+  }
+  uint64_t cur = 0;
+  auto place = [&](int block, int t, bool packed_after_previous) {
+    if (!packed_after_previous) cur = align_up(cur);
+    L.offset[t] = cur;
+    cur += L.nbytes[t];
+    L.block_of[t] = block;
+    L.block_tensors[block].push_back(t);
+    L.block_bytes[block] += L.nbytes[t];
+  };
+  place(0, 0, false);
+  place(0, 1, false);
+  place(0, L.n_tensors - 2, false);
+  place(0, L.n_tensors - 1, false);
+  for (int l = 0; l < d.layers; ++l) {
+    const int b = 1 + l;
+    auto T = [&](int w) { return L.layer_tensor(l, w); };
+    place(b, T(LN1_W), false);
+    place(b, T(LN1_B), false);
+    place(b, T(Q_W), false);
+    place(b, T(K_W), true);
+    place(b, T(V_W), true);
+    place(b, T(Q_B), false);
+    place(b, T(K_B), true);
+    place(b, T(V_B), true);
+    place(b, T(O_W), false);
+    place(b, T(O_B), false);
+    place(b, T(LN2_W), false);
+    place(b, T(LN2_B), false);
+    place(b, T(FC1_W), false);
+    place(b, T(FC1_B), false);
+    place(b, T(FC2_W), false);
+    place(b, T(FC2_B), false);
+  }
+  L.arena_bytes = align_up(cur);
+  return L;
+}
+
+}  // namespace ctn

@@ -1,0 +1,620 @@
+// Host runtime behind the C ABI: contexts, model registration, asynchronous
+// swap-in / swap-out on dedicated streams with one event per transfer block,
+// LRU residency under a byte budget, and the layer-by-layer forward pass that
+// waits only for the blocks it is about to read.
+//
+// Paper: Section 3 (demand paging of whole models), Section 3.2 (load and
+// offload entries run on two extra streams next to the compute stream; a
+// batch may only run on loaded parameters; host copies stay pinned),
+// Section 4 (LRU), Section 5.1 (per-tensor messages and their alpha cost).
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <vector>
+
+#include "computron.h"
+#include "kernels.h"
+#include "layout.hpp"
+#include "residency.hpp"
+
+using namespace ctn;
+
+namespace {
+
+struct PendingRelease {   // arena range given back by a swap-out that may still be copying
+  uint64_t off, len;
+  hipEvent_t done;        // borrowed from the model that was swapped out
+};
+
+struct Model {
+  ShardLayout lay;
+  std::vector<void*> host;           // per tensor, list order (host address)
+  std::vector<void*> host_dev;       // the same memory as the device sees it
+  bool resident = false;
+  uint64_t arena_off = 0;
+  std::vector<hipEvent_t> ev_block;  // recorded on the h2d stream after each block
+  hipEvent_t ev_in_start = nullptr, ev_out_start = nullptr, ev_out_done = nullptr, ev_last_use = nullptr;
+  bool used_since_load = false;      // ev_last_use recorded since the last swap-in
+  bool load_recorded = false, out_recorded = false;
+  bool pending_in = false, pending_out = false;
+};
+
+struct Activations {   // carved from the workspace for one inference of M tokens
+  int32_t* ids;
+  float* x;
+  _Float16 *a, *qkv, *attn, *u;
+  float* logits;
+  uint64_t bytes;
+};
+
+}  // namespace
+
+struct ctn_ctx {
+  ctn_config cfg{};
+  hipStream_t s_compute = nullptr, s_h2d = nullptr, s_d2h = nullptr;
+  Residency res{0};
+  RangeAllocator arena;
+  std::vector<std::unique_ptr<Model>> models;
+  std::vector<PendingRelease> pending;
+  std::vector<ctn_event> events;
+  ctn_stats stats{};
+  int last_hip = 0;
+};
+
+namespace {
+
+#define CTN_HIP(ctx, expr)                        \
+  do {                                            \
+    hipError_t e_ = (expr);                       \
+    if (e_ != hipSuccess) {                       \
+      if (ctx) (ctx)->last_hip = (int)e_;         \
+      return CTN_E_HIP;                           \
+    }                                             \
+  } while (0)
+
+Model* get_model(ctn_ctx* c, ctn_model m) {
+  if (!c || m < 0 || m >= (ctn_model)c->models.size()) return nullptr;
+  return c->models[m].get();
+}
+
+void log_event(ctn_ctx* c, int kind, int model, const std::vector<int>& victims) {
+  ctn_event e{};
+  e.kind = kind;
+  e.model = model;
+  e.n_victims = (int32_t)victims.size();
+  for (size_t i = 0; i < victims.size() && i < 13; ++i) e.victims[i] = victims[i];
+  c->events.push_back(e);
+}
+
+uint64_t activation_bytes(const ctn_model_desc& d, int64_t M, bool with_logits, Activations* out,
+                          char* base) {
+  const uint64_t h = d.hidden, hl = d.hidden / d.tp, fl = d.ffn / d.tp, vl = d.vocab / d.tp;
+  uint64_t cur = 0;
+  auto take = [&](uint64_t n) {
+    uint64_t o = cur;
+    cur = align_up(cur + n);
+    return o;
+  };
+  const uint64_t o_ids = take(4ull * M), o_x = take(4ull * M * h), o_a = take(2ull * M * h),
+                 o_qkv = take(2ull * M * 3 * hl), o_attn = take(2ull * M * hl), o_u = take(2ull * M * fl),
+                 o_log = with_logits ? take(4ull * M * vl) : 0;
+  if (out && base) {
+    out->ids = reinterpret_cast<int32_t*>(base + o_ids);
+    out->x = reinterpret_cast<float*>(base + o_x);
+    out->a = reinterpret_cast<_Float16*>(base + o_a);
+    out->qkv = reinterpret_cast<_Float16*>(base + o_qkv);
+    out->attn = reinterpret_cast<_Float16*>(base + o_attn);
+    out->u = reinterpret_cast<_Float16*>(base + o_u);
+    out->logits = with_logits ? reinterpret_cast<float*>(base + o_log) : nullptr;
+    out->bytes = cur;
+  }
+  return cur;
+}
+
+// Enqueue the copy of model m back to its host tensors and give its range back.
+int do_swap_out(ctn_ctx* c, int mi) {
+  Model* m = c->models[mi].get();
+  if (!m->resident) return CTN_OK;
+  char* arena = static_cast<char*>(c->cfg.arena_dev) + m->arena_off;
+  // The offload must see the complete device copy and must not overtake an
+  // inference that is still reading it.
+  CTN_HIP(c, hipStreamWaitEvent(c->s_d2h, m->ev_block.back(), 0));
+  if (m->used_since_load) CTN_HIP(c, hipStreamWaitEvent(c->s_d2h, m->ev_last_use, 0));
+  CTN_HIP(c, hipEventRecord(m->ev_out_start, c->s_d2h));
+  const ShardLayout& L = m->lay;
+  for (int b = 0; b < L.n_blocks; ++b) {
+    if (c->cfg.transfer_mode == CTN_XFER_KERNEL) {
+      CopyTable t{};
+      for (int ti : L.block_tensors[b]) {
+        t.seg[t.n].src = arena + L.offset[ti];
+        t.seg[t.n].dst = m->host_dev[ti];
+        t.seg[t.n].n16 = L.nbytes[ti] / 16;
+        ++t.n;
+      }
+      if (!copy_table_finish(t)) return CTN_E_INVAL;
+      CTN_HIP(c, launch_copy_table(t, c->cfg.copy_blocks, c->s_d2h));
+    } else {
+      for (int ti : L.block_tensors[b])
+        CTN_HIP(c, hipMemcpyAsync(m->host[ti], arena + L.offset[ti], L.nbytes[ti], hipMemcpyDeviceToHost,
+                                  c->s_d2h));
+    }
+  }
+  CTN_HIP(c, hipEventRecord(m->ev_out_done, c->s_d2h));
+  m->out_recorded = true;
+  m->pending_out = true;
+  m->resident = false;
+  c->arena.release(m->arena_off, L.arena_bytes);
+  c->pending.push_back({m->arena_off, L.arena_bytes, m->ev_out_done});
+  c->res.mark_evicted(mi);
+  c->stats.bytes_d2h += L.param_bytes;
+  c->stats.n_swap_out += 1;
+  return CTN_OK;
+}
+
+// Make model mi resident (a use).  On a miss: evict least recently used
+// models while the budget (or the arena) has no room, then enqueue the load.
+int ensure_resident(ctn_ctx* c, int mi) {
+  Model* m = c->models[mi].get();
+  std::vector<int> victims;
+  if (m->resident) {
+    c->res.touch(mi);
+    c->stats.n_hit += 1;
+    log_event(c, 0, mi, victims);
+    return CTN_OK;
+  }
+  const ShardLayout& L = m->lay;
+  if (L.param_bytes > c->res.budget() || L.arena_bytes > c->cfg.arena_bytes) return CTN_E_TOO_BIG;
+  while (c->res.over_budget_with(mi)) {
+    int v = c->res.oldest(mi);
+    if (v < 0) return CTN_E_BUSY;
+    int rc = do_swap_out(c, v);
+    if (rc) return rc;
+    victims.push_back(v);
+  }
+  uint64_t off = c->arena.alloc(L.arena_bytes);
+  while (off == UINT64_MAX) {   // budget has room but no hole is wide enough: keep evicting
+    int v = c->res.oldest(mi);
+    if (v < 0) return CTN_E_BUSY;
+    int rc = do_swap_out(c, v);
+    if (rc) return rc;
+    victims.push_back(v);
+    off = c->arena.alloc(L.arena_bytes);
+  }
+  m->arena_off = off;
+  // A load into a range that an offload is still reading must wait for it;
+  // loads into other ranges overlap with the offload (Section 3.2 / 5.1).
+  for (size_t i = 0; i < c->pending.size();) {
+    PendingRelease& p = c->pending[i];
+    const hipError_t q = hipEventQuery(p.done);
+    if (q == hipSuccess) {
+      c->pending.erase(c->pending.begin() + i);
+      continue;
+    }
+    (void)hipGetLastError();   // "not ready" is an answer, not a failure to report later
+    if (p.off < off + L.arena_bytes && off < p.off + p.len) CTN_HIP(c, hipStreamWaitEvent(c->s_h2d, p.done, 0));
+    ++i;
+  }
+  // The load reads the host tensors this model's own offload may still be writing.
+  if (m->pending_out) CTN_HIP(c, hipStreamWaitEvent(c->s_h2d, m->ev_out_done, 0));
+  char* arena = static_cast<char*>(c->cfg.arena_dev) + off;
+  CTN_HIP(c, hipEventRecord(m->ev_in_start, c->s_h2d));
+  for (int b = 0; b < L.n_blocks; ++b) {
+    if (c->cfg.transfer_mode == CTN_XFER_KERNEL) {
+      CopyTable t{};
+      for (int ti : L.block_tensors[b]) {
+        t.seg[t.n].src = m->host_dev[ti];
+        t.seg[t.n].dst = arena + L.offset[ti];
+        t.seg[t.n].n16 = L.nbytes[ti] / 16;
+        ++t.n;
+      }
+      if (!copy_table_finish(t)) return CTN_E_INVAL;
+      CTN_HIP(c, launch_copy_table(t, c->cfg.copy_blocks, c->s_h2d));
+    } else {
+      for (int ti : L.block_tensors[b])
+        CTN_HIP(c, hipMemcpyAsync(arena + L.offset[ti], m->host[ti], L.nbytes[ti], hipMemcpyHostToDevice,
+                                  c->s_h2d));
+    }
+    CTN_HIP(c, hipEventRecord(m->ev_block[b], c->s_h2d));
+  }
+  m->resident = true;
+  m->load_recorded = true;
+  m->pending_in = true;
+  m->used_since_load = false;
+  c->res.mark_resident(mi);
+  c->stats.bytes_h2d += L.param_bytes;
+  c->stats.n_swap_in += 1;
+  c->stats.n_miss += 1;
+  c->stats.resident_bytes = c->res.resident_bytes();
+  c->stats.peak_resident_bytes = c->res.peak_bytes();
+  log_event(c, 1, mi, victims);
+  return CTN_OK;
+}
+
+template <typename T>
+T* dev_tensor(ctn_ctx* c, Model* m, int ti) {
+  return reinterpret_cast<T*>(static_cast<char*>(c->cfg.arena_dev) + m->arena_off + m->lay.offset[ti]);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ctn_create(const ctn_config* cfg, ctn_ctx** out) {
+  if (!cfg || !out) return CTN_E_INVAL;
+  if (!cfg->arena_dev || !cfg->workspace_dev || !cfg->stream_compute || !cfg->stream_h2d || !cfg->stream_d2h)
+    return CTN_E_INVAL;
+  if (reinterpret_cast<uintptr_t>(cfg->arena_dev) % kAlign || reinterpret_cast<uintptr_t>(cfg->workspace_dev) % kAlign)
+    return CTN_E_INVAL;
+  if (cfg->hbm_budget_bytes == 0 || cfg->arena_bytes == 0) return CTN_E_INVAL;
+  if (cfg->transfer_mode != CTN_XFER_DMA && cfg->transfer_mode != CTN_XFER_KERNEL) return CTN_E_INVAL;
+  if (cfg->stream_h2d == cfg->stream_compute || cfg->stream_d2h == cfg->stream_compute ||
+      cfg->stream_h2d == cfg->stream_d2h)
+    return CTN_E_INVAL;
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev < 1) return CTN_E_HIP;   // no silent fallback
+  ctn_ctx* c = new (std::nothrow) ctn_ctx();
+  if (!c) return CTN_E_NOMEM;
+  c->cfg = *cfg;
+  c->s_compute = static_cast<hipStream_t>(cfg->stream_compute);
+  c->s_h2d = static_cast<hipStream_t>(cfg->stream_h2d);
+  c->s_d2h = static_cast<hipStream_t>(cfg->stream_d2h);
+  c->res = Residency(cfg->hbm_budget_bytes);
+  c->arena.reset(cfg->arena_bytes / kAlign * kAlign);
+  c->stats.budget_bytes = cfg->hbm_budget_bytes;
+  *out = c;
+  return CTN_OK;
+}
+
+int ctn_sync(ctn_ctx* c) {
+  if (!c) return CTN_E_INVAL;
+  CTN_HIP(c, hipStreamSynchronize(c->s_h2d));
+  CTN_HIP(c, hipStreamSynchronize(c->s_d2h));
+  CTN_HIP(c, hipStreamSynchronize(c->s_compute));
+  for (auto& m : c->models) m->pending_in = m->pending_out = false;
+  c->pending.clear();
+  return CTN_OK;
+}
+
+int ctn_destroy(ctn_ctx* c) {
+  if (!c) return CTN_E_INVAL;
+  int rc = ctn_sync(c);
+  for (auto& m : c->models) {
+    for (hipEvent_t e : m->ev_block) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {m->ev_in_start, m->ev_out_start, m->ev_out_done, m->ev_last_use})
+      if (e) (void)hipEventDestroy(e);
+  }
+  delete c;
+  return rc;
+}
+
+int ctn_host_alloc(uint64_t nbytes, void** out) {
+  if (!out || nbytes == 0) return CTN_E_INVAL;
+  void* p = nullptr;
+  hipError_t e = hipHostMalloc(&p, nbytes, hipHostMallocMapped | hipHostMallocPortable);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return e == hipErrorOutOfMemory ? CTN_E_NOMEM : CTN_E_HIP;
+  }
+  *out = p;
+  return CTN_OK;
+}
+
+int ctn_host_free(void* p) {
+  if (!p) return CTN_OK;
+  return hipHostFree(p) == hipSuccess ? CTN_OK : CTN_E_HIP;
+}
+
+int ctn_register_model(ctn_ctx* c, const ctn_model_desc* desc, const ctn_param* params, size_t n,
+                       uint64_t hbm_budget_bytes, ctn_model* out) {
+  if (!c || !desc || !params || !out) return CTN_E_INVAL;
+  if (hbm_budget_bytes != 0 && hbm_budget_bytes != c->res.budget()) return CTN_E_INVAL;
+  if (!desc_valid(*desc)) return CTN_E_INVAL;
+  auto m = std::make_unique<Model>();
+  m->lay = make_layout(*desc);
+  const ShardLayout& L = m->lay;
+  if (n != (size_t)L.n_tensors) return CTN_E_INVAL;
+  for (int i = 0; i < L.n_tensors; ++i) {
+    const ctn_param& p = params[i];
+    int64_t r, cc;
+    expected_shape(*desc, i, r, cc);
+    if (!p.host_ptr || reinterpret_cast<uintptr_t>(p.host_ptr) % 16 || p.nbytes % 16) return CTN_E_INVAL;
+    if (p.nbytes != L.nbytes[i]) return CTN_E_INVAL;
+    if (cc == 0) {
+      if (p.ndim != 1 || p.shape[0] != r) return CTN_E_INVAL;
+    } else {
+      if (p.ndim != 2 || p.shape[0] != r || p.shape[1] != cc) return CTN_E_INVAL;
+    }
+    m->host.push_back(p.host_ptr);
+  }
+  if (L.param_bytes > c->res.budget() || L.arena_bytes > c->cfg.arena_bytes) return CTN_E_TOO_BIG;
+  // the device must be able to dereference the host tensors (zero-copy path)
+  for (int i = 0; i < L.n_tensors; ++i) {
+    void* dp = nullptr;
+    hipError_t e = hipHostGetDevicePointer(&dp, m->host[i], 0);
+    if (e != hipSuccess || !dp) {
+      (void)hipGetLastError();
+      c->last_hip = (int)e;
+      return CTN_E_INVAL;
+    }
+    m->host_dev.push_back(dp);
+  }
+  m->ev_block.resize(L.n_blocks);
+  for (auto& e : m->ev_block) CTN_HIP(c, hipEventCreate(&e));
+  CTN_HIP(c, hipEventCreate(&m->ev_in_start));
+  CTN_HIP(c, hipEventCreate(&m->ev_out_start));
+  CTN_HIP(c, hipEventCreate(&m->ev_out_done));
+  CTN_HIP(c, hipEventCreateWithFlags(&m->ev_last_use, hipEventDisableTiming));
+  int idx = c->res.add_model(L.param_bytes);
+  c->models.push_back(std::move(m));
+  *out = idx;
+  return CTN_OK;
+}
+
+int ctn_swap_in(ctn_ctx* c, ctn_model mi) {
+  if (!get_model(c, mi)) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
+  return ensure_resident(c, mi);
+}
+
+int ctn_swap_out(ctn_ctx* c, ctn_model mi) {
+  Model* m = get_model(c, mi);
+  if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
+  std::vector<int> victims;
+  if (m->resident) victims.push_back(mi);
+  int rc = do_swap_out(c, mi);
+  if (rc) return rc;
+  c->stats.resident_bytes = c->res.resident_bytes();
+  log_event(c, 2, mi, victims);
+  return CTN_OK;
+}
+
+int ctn_wait(ctn_ctx* c, ctn_model mi) {
+  Model* m = get_model(c, mi);
+  if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
+  if (m->pending_out) {
+    CTN_HIP(c, hipEventSynchronize(m->ev_out_done));
+    m->pending_out = false;
+  }
+  if (m->pending_in) {
+    CTN_HIP(c, hipEventSynchronize(m->ev_block.back()));
+    m->pending_in = false;
+  }
+  return CTN_OK;
+}
+
+uint64_t ctn_workspace_bytes(const ctn_model_desc* desc, int64_t max_tokens, int32_t n_models) {
+  (void)n_models;
+  if (!desc || !desc_valid(*desc) || max_tokens <= 0) return 0;
+  return activation_bytes(*desc, max_tokens, true, nullptr, nullptr);
+}
+
+uint64_t ctn_arena_bytes(const ctn_model_desc* desc) {
+  if (!desc || !desc_valid(*desc)) return 0;
+  return make_layout(*desc).arena_bytes;
+}
+
+int ctn_infer(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int32_t batch, int32_t seq, void* logits_out,
+              int32_t out_is_device) {
+  Model* m = get_model(c, mi);
+  if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
+  if (!ids_host || !logits_out) return CTN_E_INVAL;
+  const ShardLayout& L = m->lay;
+  const ctn_model_desc& d = L.d;
+  if (batch <= 0 || seq <= 0 || seq > d.max_pos || (int64_t)batch * seq > (1 << 24)) return CTN_E_SHAPE;
+  const int M = batch * seq;
+  const bool own_logits = !out_is_device;
+  Activations act{};
+  if (activation_bytes(d, M, own_logits, &act, static_cast<char*>(c->cfg.workspace_dev)) > c->cfg.workspace_bytes)
+    return CTN_E_SHAPE;
+  for (int i = 0; i < M; ++i)
+    if (ids_host[i] < 0 || ids_host[i] >= d.vocab) return CTN_E_INVAL;
+
+  int rc = ensure_resident(c, mi);
+  if (rc) return rc;
+  c->stats.n_infer += 1;
+
+  hipStream_t s = c->s_compute;
+  const int h = d.hidden, hl = L.hl(), fl = L.fl(), vl = L.vl();
+  CTN_HIP(c, hipMemcpyAsync(act.ids, ids_host, 4ull * M, hipMemcpyHostToDevice, s));
+  float* logits = out_is_device ? static_cast<float*>(logits_out) : act.logits;
+
+  // The paper's rule (Section 3.2): a batch runs only on a fully loaded
+  // model.  With pipelining the same rule is applied per transfer block.
+  if (!c->cfg.pipeline) CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block.back(), 0));
+  else CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block[0], 0));
+
+  const _Float16* tok = dev_tensor<_Float16>(c, m, 0);
+  CTN_HIP(c, launch_embed(act.ids, tok, dev_tensor<_Float16>(c, m, 1), act.x, M, seq, h, vl, d.rank, s));
+  for (int l = 0; l < d.layers; ++l) {
+    if (c->cfg.pipeline) CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block[1 + l], 0));
+    auto T = [&](int w) { return dev_tensor<_Float16>(c, m, L.layer_tensor(l, w)); };
+    CTN_HIP(c, launch_layernorm(act.x, T(LN1_W), T(LN1_B), act.a, M, h, s));
+    // q | k | v weights and biases are adjacent in the arena: one product
+    CTN_HIP(c, launch_gemm(act.a, T(Q_W), T(Q_B), act.qkv, M, 3 * hl, h, CTN_EPI_BIAS_F16, s));
+    CTN_HIP(c, launch_attention(act.qkv, act.attn, batch, seq, L.local_heads(), L.head_dim(), s));
+    // row parallel: this rank's partial sum joins the residual stream (the
+    // cross-rank reduction is the identity on one GPU), bias added once
+    CTN_HIP(c, launch_gemm(act.attn, T(O_W), T(O_B), act.x, M, h, hl, CTN_EPI_BIAS_RESID_F32, s));
+    CTN_HIP(c, launch_layernorm(act.x, T(LN2_W), T(LN2_B), act.a, M, h, s));
+    CTN_HIP(c, launch_gemm(act.a, T(FC1_W), T(FC1_B), act.u, M, fl, h, CTN_EPI_BIAS_RELU_F16, s));
+    CTN_HIP(c, launch_gemm(act.u, T(FC2_W), T(FC2_B), act.x, M, h, fl, CTN_EPI_BIAS_RESID_F32, s));
+  }
+  CTN_HIP(c, launch_layernorm(act.x, dev_tensor<_Float16>(c, m, L.n_tensors - 2),
+                              dev_tensor<_Float16>(c, m, L.n_tensors - 1), act.a, M, h, s));
+  CTN_HIP(c, launch_gemm(act.a, tok, nullptr, logits, M, vl, h, CTN_EPI_F32, s));   // tied head, vocabulary slice
+  CTN_HIP(c, hipEventRecord(m->ev_last_use, s));
+  m->used_since_load = true;
+  if (!out_is_device) {
+    CTN_HIP(c, hipMemcpyAsync(logits_out, logits, 4ull * M * vl, hipMemcpyDeviceToHost, s));
+    CTN_HIP(c, hipStreamSynchronize(s));
+  }
+  return CTN_OK;
+}
+
+int ctn_is_resident(ctn_ctx* c, ctn_model mi, int32_t* out) {
+  Model* m = get_model(c, mi);
+  if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
+  if (!out) return CTN_E_INVAL;
+  *out = m->resident ? 1 : 0;
+  return CTN_OK;
+}
+
+int ctn_get_stats(ctn_ctx* c, ctn_stats* out) {
+  if (!c || !out) return CTN_E_INVAL;
+  c->stats.resident_bytes = c->res.resident_bytes();
+  c->stats.peak_resident_bytes = c->res.peak_bytes();
+  *out = c->stats;
+  return CTN_OK;
+}
+
+int ctn_get_events(ctn_ctx* c, uint64_t first, ctn_event* out, uint64_t cap, uint64_t* n_out, uint64_t* total) {
+  if (!c || !n_out || !total || (cap && !out)) return CTN_E_INVAL;
+  *total = c->events.size();
+  uint64_t n = 0;
+  for (uint64_t i = first; i < c->events.size() && n < cap; ++i) out[n++] = c->events[i];
+  *n_out = n;
+  return CTN_OK;
+}
+
+int ctn_last_swap_ms(ctn_ctx* c, ctn_model mi, float* in_ms, float* out_ms, float* block_ms, int32_t cap,
+                     int32_t* n_blocks) {
+  Model* m = get_model(c, mi);
+  if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
+  int rc = ctn_wait(c, mi);
+  if (rc) return rc;
+  if (n_blocks) *n_blocks = m->lay.n_blocks;
+  if (in_ms) {
+    *in_ms = -1.f;
+    if (m->load_recorded) CTN_HIP(c, hipEventElapsedTime(in_ms, m->ev_in_start, m->ev_block.back()));
+  }
+  if (out_ms) {
+    *out_ms = -1.f;
+    if (m->out_recorded) {
+      CTN_HIP(c, hipEventSynchronize(m->ev_out_done));
+      CTN_HIP(c, hipEventElapsedTime(out_ms, m->ev_out_start, m->ev_out_done));
+    }
+  }
+  if (block_ms && m->load_recorded)
+    for (int b = 0; b < m->lay.n_blocks && b < cap; ++b)
+      CTN_HIP(c, hipEventElapsedTime(&block_ms[b], m->ev_in_start, m->ev_block[b]));
+  return CTN_OK;
+}
+
+int ctn_debug_read_param(ctn_ctx* c, ctn_model mi, int32_t index, void* dst, uint64_t cap) {
+  Model* m = get_model(c, mi);
+  if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
+  if (!dst || index < 0 || index >= m->lay.n_tensors || !m->resident) return CTN_E_INVAL;
+  if (cap < m->lay.nbytes[index]) return CTN_E_INVAL;
+  int rc = ctn_wait(c, mi);
+  if (rc) return rc;
+  CTN_HIP(c, hipMemcpy(dst, dev_tensor<char>(c, m, index), m->lay.nbytes[index], hipMemcpyDeviceToHost));
+  return CTN_OK;
+}
+
+int ctn_set_mode(ctn_ctx* c, int32_t transfer_mode, int32_t pipeline, int32_t copy_blocks) {
+  if (!c) return CTN_E_INVAL;
+  if (transfer_mode != CTN_XFER_DMA && transfer_mode != CTN_XFER_KERNEL) return CTN_E_INVAL;
+  if (copy_blocks < 0 || copy_blocks > 4096) return CTN_E_INVAL;
+  c->cfg.transfer_mode = transfer_mode;
+  c->cfg.pipeline = pipeline ? 1 : 0;
+  c->cfg.copy_blocks = copy_blocks;
+  return CTN_OK;
+}
+
+int ctn_last_hip_error(ctn_ctx* c) { return c ? c->last_hip : 0; }
+
+const char* ctn_strerror(int code) {
+  switch (code) {
+    case CTN_OK: return "ok";
+    case CTN_E_INVAL: return "invalid argument";
+    case CTN_E_TOO_BIG: return "shard larger than the budget or the arena";
+    case CTN_E_NOMODEL: return "unknown model";
+    case CTN_E_BUSY: return "no room can be made";
+    case CTN_E_HIP: return "HIP call failed";
+    case CTN_E_SHAPE: return "batch/sequence outside what the model or workspace allows";
+    case CTN_E_NOMEM: return "out of memory";
+    default: return "unknown error";
+  }
+}
+
+int ctn_residency_replay(uint64_t budget, const uint64_t* sizes, int32_t n_models, const int32_t* trace,
+                         uint64_t n, ctn_event* out) {
+  if (!sizes || n_models <= 0 || (n && (!trace || !out))) return CTN_E_INVAL;
+  Residency res(budget);
+  for (int i = 0; i < n_models; ++i) res.add_model(sizes[i]);
+  for (uint64_t i = 0; i < n; ++i) {
+    const int m = trace[i];
+    if (m < 0 || m >= n_models) return CTN_E_NOMODEL;
+    ctn_event e{};
+    e.model = m;
+    if (res.resident(m)) {
+      res.touch(m);
+      e.kind = 0;
+    } else {
+      if (res.size(m) > budget) return CTN_E_TOO_BIG;
+      e.kind = 1;
+      while (res.over_budget_with(m)) {
+        int v = res.oldest(m);
+        if (v < 0) return CTN_E_BUSY;
+        res.mark_evicted(v);
+        if (e.n_victims < 13) e.victims[e.n_victims] = v;
+        e.n_victims += 1;
+      }
+      res.mark_resident(m);
+    }
+    out[i] = e;
+  }
+  return CTN_OK;
+}
+
+// ---- single operations -------------------------------------------------------
+
+static int op_rc(hipError_t e) { return e == hipSuccess ? CTN_OK : (e == hipErrorInvalidValue ? CTN_E_INVAL : CTN_E_HIP); }
+
+int ctn_op_copy(void* dst, const void* src, uint64_t nbytes, int32_t blocks, void* stream) {
+  if (!dst || !src || nbytes % 16 || reinterpret_cast<uintptr_t>(dst) % 16 || reinterpret_cast<uintptr_t>(src) % 16)
+    return CTN_E_INVAL;
+  CopyTable t{};
+  t.n = 1;
+  t.seg[0] = {src, dst, nbytes / 16};
+  if (!copy_table_finish(t)) return CTN_E_INVAL;
+  return op_rc(launch_copy_table(t, blocks, static_cast<hipStream_t>(stream)));
+}
+
+int ctn_op_dma(void* dst, const void* src, uint64_t nbytes, void* stream) {
+  if (!dst || !src) return CTN_E_INVAL;
+  return op_rc(hipMemcpyAsync(dst, src, nbytes, hipMemcpyDefault, static_cast<hipStream_t>(stream)));
+}
+
+int ctn_op_embed(const int32_t* ids, const void* tok, const void* pos, float* x, int32_t M, int32_t seq,
+                 int32_t hidden, int32_t vocab_local, int32_t rank, void* stream) {
+  if (!ids || !tok || !pos || !x || M < 0) return CTN_E_INVAL;
+  return op_rc(launch_embed(ids, static_cast<const _Float16*>(tok), static_cast<const _Float16*>(pos), x, M, seq,
+                            hidden, vocab_local, rank, static_cast<hipStream_t>(stream)));
+}
+
+int ctn_op_layernorm(const float* x, const void* g, const void* b, void* out, int32_t rows, int32_t hidden,
+                     void* stream) {
+  if (!x || !g || !b || !out || rows < 0) return CTN_E_INVAL;
+  return op_rc(launch_layernorm(x, static_cast<const _Float16*>(g), static_cast<const _Float16*>(b),
+                                static_cast<_Float16*>(out), rows, hidden, static_cast<hipStream_t>(stream)));
+}
+
+int ctn_op_gemm(const void* A, const void* W, const void* bias, void* out, int32_t M, int32_t N, int32_t K,
+                int32_t epilogue, void* stream) {
+  if (!A || !W || !out || M < 0 || N < 0) return CTN_E_INVAL;
+  return op_rc(launch_gemm(static_cast<const _Float16*>(A), static_cast<const _Float16*>(W),
+                           static_cast<const _Float16*>(bias), out, M, N, K, epilogue,
+                           static_cast<hipStream_t>(stream)));
+}
+
+int ctn_op_attention(const void* qkv, void* out, int32_t batch, int32_t seq, int32_t heads, int32_t head_dim,
+                     void* stream) {
+  if (!qkv || !out || batch < 0 || seq < 0 || heads < 0) return CTN_E_INVAL;
+  return op_rc(launch_attention(static_cast<const _Float16*>(qkv), static_cast<_Float16*>(out), batch, seq, heads,
+                                head_dim, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,51 @@
+"""Shared plumbing for the GPU tests: torch provides device memory and streams only."""
+import numpy as np
+import torch
+
+import paper_2306_13835_amd as P
+from paper_2306_13835_amd import binding as B
+from synth import fill_shard, param_list, shard_bytes
+
+
+class Rig:
+    """A context with its arena, workspace, streams and pinned host pool."""
+
+    def __init__(self, descs, budget=None, max_tokens=64, arena_bytes=None, mode=P.XFER_KERNEL,
+                 pipeline=True, host_bytes=None):
+        self.dev = torch.device("cuda:0")
+        torch.cuda.set_device(0)
+        self.s_compute, self.s_h2d, self.s_d2h = (torch.cuda.Stream() for _ in range(3))
+        need = [P.arena_bytes(d) for d in descs]
+        arena_bytes = arena_bytes or sum(need)
+        budget = budget or sum(shard_bytes(d) for d in descs)
+        ws = max(P.workspace_bytes(d, max_tokens) for d in descs)
+        self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device=self.dev)
+        self.workspace = torch.empty(ws, dtype=torch.uint8, device=self.dev)
+        torch.cuda.synchronize()
+        self.ctx = P.Context(budget, self.arena, self.workspace, self.s_compute, self.s_h2d, self.s_d2h,
+                             transfer_mode=mode, pipeline=pipeline)
+        host_bytes = host_bytes or sum(shard_bytes(d) + 256 * len(param_list(d)) for d in descs) + 4096
+        self.pool = P.HostPool(host_bytes)
+        self.descs = list(descs)
+        self.models, self.tensors = [], []
+
+    def add(self, desc, seed):
+        t = fill_shard(desc, seed, alloc=lambda shape: self.pool.take(shape))
+        m = self.ctx.register_model(desc, t)
+        self.models.append(m)
+        self.tensors.append(t)
+        return m
+
+    def close(self):
+        self.ctx.close()
+        self.tensors = []
+        self.pool.close()
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def errors(got: np.ndarray, want: np.ndarray):
+    diff = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    return diff.max(), diff.mean() / np.abs(want).mean()

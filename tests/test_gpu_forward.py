@@ -1,0 +1,168 @@
+"""Shard forward pass through ctn_infer against the fp32 CPU oracle.
+
+Acceptance bar: max |g - o| <= 2e-2 and mean|g - o| / mean|o| <= 1e-3 on the logits.
+"""
+import time
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+import paper_2306_13835_amd as P
+from oracle import opt_shard as O
+from oracle.swap import as_bytes
+from synth import CONFIGS, ShardDesc, token_ids, shard_bytes
+from gpu_util import Rig, errors
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_REL = 2e-2, 1e-3
+
+
+def oracle_logits(rig, m, desc, ids):
+    return O.forward(rig.tensors[m], ids, layers=desc.layers, heads=desc.heads, tp=desc.tp, rank=desc.rank,
+                     dtype=np.float32)
+
+
+def assert_close(got, want, what=""):
+    mx, rel = errors(got, want)
+    print(f"{what} max-abs {mx:.3e} mean-rel {rel:.3e}", flush=True)
+    assert np.isfinite(got).all()
+    assert mx <= MAX_ABS and rel <= MEAN_REL, (what, mx, rel)
+
+
+TINY = [
+    (ShardDesc(2, 128, 512, 2, vocab=512, max_pos=40), 2, 5),
+    (ShardDesc(3, 256, 1024, 4, vocab=1000, max_pos=300, tp=2, rank=0), 1, 1),
+    (ShardDesc(3, 256, 1024, 4, vocab=1000, max_pos=300, tp=2, rank=1), 3, 37),
+    (ShardDesc(2, 512, 2048, 4, vocab=1024, max_pos=300, tp=4, rank=2), 2, 130),   # head size 128, ragged tiles
+    (ShardDesc(2, 640, 2560, 10, vocab=1000, max_pos=300), 1, 264),
+]
+
+
+@pytest.mark.parametrize("desc,batch,seq", TINY)
+def test_small_shards_every_mode(desc, batch, seq):
+    rig = Rig([desc], max_tokens=batch * seq)
+    try:
+        m = rig.add(desc, seed=77)
+        ids = token_ids(9, batch, seq, desc.vocab)
+        want = oracle_logits(rig, m, desc, ids)
+        outs = []
+        for mode in (P.XFER_KERNEL, P.XFER_DMA):
+            for pipe in (True, False):
+                rig.ctx.set_mode(mode, pipe)
+                rig.arena.fill_(0x7E)                 # NaN pattern: reading a block before it lands shows up
+                torch.cuda.synchronize()
+                got = rig.ctx.infer(m, ids)           # demand paging: the model is not resident
+                assert got.shape == (batch, seq, desc.vocab // desc.tp)
+                assert_close(got, want, f"{desc} mode {mode} pipe {pipe}")
+                outs.append(got.copy())
+                again = rig.ctx.infer(m, ids)         # resident now: a hit, bit-identical result
+                assert np.array_equal(again, got)
+                rig.ctx.swap_out(m)
+                rig.ctx.wait(m)
+        for o in outs[1:]:
+            assert np.array_equal(o, outs[0])
+        st = rig.ctx.stats()
+        assert st["n_miss"] == 4 and st["n_hit"] == 4 and st["n_infer"] == 8
+    finally:
+        rig.close()
+
+
+def test_device_output_and_shape_errors():
+    desc, batch, seq = TINY[0]
+    rig = Rig([desc], max_tokens=batch * seq)
+    try:
+        m = rig.add(desc, seed=3)
+        ids = token_ids(1, batch, seq, desc.vocab)
+        out = torch.empty(batch, seq, desc.vocab, dtype=torch.float32, device="cuda")
+        rig.ctx.infer(m, ids, out=out)
+        rig.ctx.sync()
+        assert np.array_equal(out.cpu().numpy(), rig.ctx.infer(m, ids))
+        with pytest.raises(P.CtnError) as e:
+            rig.ctx.infer(m, token_ids(1, 1, 41, desc.vocab))          # beyond max_pos
+        assert e.value.code == -6
+        with pytest.raises(P.CtnError) as e:
+            rig.ctx.infer(m, token_ids(1, 4, 40, desc.vocab))          # workspace too small
+        assert e.value.code == -6
+        bad = ids.copy(); bad[0, 0] = desc.vocab
+        with pytest.raises(P.CtnError) as e:
+            rig.ctx.infer(m, bad)
+        assert e.value.code == -1
+    finally:
+        rig.close()
+
+
+def test_infer_under_eviction_pressure_matches_oracle():
+    """Three models, room for two: every request may trigger swap-out + swap-in."""
+    desc = ShardDesc(2, 256, 1024, 4, vocab=1000, max_pos=64)
+    size = shard_bytes(desc)
+    rig = Rig([desc] * 3, budget=2 * size, arena_bytes=2 * P.arena_bytes(desc), max_tokens=16)
+    try:
+        ms = [rig.add(desc, seed=40 + i) for i in range(3)]
+        orig = [[t.copy() for t in rig.tensors[m]] for m in ms]
+        ids = [token_ids(60 + i, 2, 8, desc.vocab) for i in range(3)]
+        want = [oracle_logits(rig, m, desc, ids[m]) for m in ms]
+        for m in (0, 1, 2, 0, 2, 1, 1, 0):
+            got = rig.ctx.infer(m, ids[m])
+            assert_close(got, want[m], f"model {m}")
+            assert rig.ctx.stats()["resident_bytes"] <= 2 * size
+        rig.ctx.sync()
+        for m in ms:
+            for t, o in zip(rig.tensors[m], orig[m]):
+                assert np.array_equal(as_bytes(t), as_bytes(o))
+    finally:
+        rig.close()
+
+
+def test_opt125m_swap_in_forward_swap_out_verify():
+    c = CONFIGS["opt125m_tp1"]
+    desc = c["desc"]
+    rig = Rig([desc], max_tokens=c["batch"] * c["seq"])
+    try:
+        m = rig.add(desc, seed=c["wseed"])
+        orig_sum = [int(as_bytes(t).astype(np.uint64).sum()) for t in rig.tensors[m]]
+        ids = token_ids(c["idseed"], c["batch"], c["seq"], desc.vocab)
+        rig.ctx.swap_in(m); rig.ctx.wait(m)
+        got = rig.ctx.infer(m, ids)
+        assert_close(got, oracle_logits(rig, m, desc, ids), "opt125m")
+        for t in rig.tensors[m][:6]:
+            as_bytes(t)[:] = 0
+        rig.ctx.swap_out(m); rig.ctx.wait(m)
+        assert [int(as_bytes(t).astype(np.uint64).sum()) for t in rig.tensors[m]] == orig_sum
+    finally:
+        rig.close()
+
+
+@pytest.mark.parametrize("name,rows", [("opt1.3b_tp1", [0, 5]), ("opt6.7b_tp2", [3]), ("opt13b_tp4", [7])])
+def test_full_size_shards_sampled_batch_rows(name, rows):
+    """Full benchmark shapes, pipelined demand-paged inference exactly as bench.py runs it;
+    the oracle evaluates a sample of the batch rows (rows do not interact)."""
+    c = CONFIGS[name]
+    desc, batch, seq = c["desc"], c["batch"], c["seq"]
+    rig = Rig([desc], max_tokens=batch * seq)
+    try:
+        t0 = time.time()
+        m = rig.add(desc, seed=c["wseed"])
+        print(f"{name}: weights in {time.time() - t0:.1f}s", flush=True)
+        ids = token_ids(c["idseed"], batch, seq, desc.vocab)
+        rig.arena.fill_(0x7E)
+        torch.cuda.synchronize()
+        out = torch.empty(batch, seq, desc.vocab // desc.tp, dtype=torch.float32, device="cuda")
+        rig.ctx.infer(m, ids, out=out)               # not resident: layer-pipelined swap-in + forward
+        rig.ctx.sync()
+        got = out.cpu().numpy()
+        t0 = time.time()
+        want = oracle_logits(rig, m, desc, ids[rows])
+        print(f"{name}: oracle rows {rows} in {time.time() - t0:.1f}s", flush=True)
+        assert_close(got[rows], want, name)
+        assert np.isfinite(got).all()
+        # spot-check the device copy of a few tensors, then a real swap-out
+        for i in (0, 1, 4, len(rig.tensors[m]) - 3):
+            assert np.array_equal(rig.ctx.debug_read_param(m, i), rig.tensors[m][i])
+        keep = rig.tensors[m][4].copy()
+        rig.tensors[m][4][:] = 0
+        rig.ctx.swap_out(m); rig.ctx.wait(m)
+        assert np.array_equal(rig.tensors[m][4], keep)
+    finally:
+        rig.close()

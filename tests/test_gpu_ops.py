@@ -1,0 +1,136 @@
+"""Parity of each HIP kernel, called through the C ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+import paper_2306_13835_amd as P
+from paper_2306_13835_amd import binding as B
+from oracle import opt_shard as O
+from gpu_util import dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def stream():
+    torch.cuda.set_device(0)
+    return torch.cuda.Stream()
+
+
+def f16(rng, shape, scale=1.0):
+    return (rng.standard_normal(shape) * scale).astype(np.float16)
+
+
+@pytest.mark.parametrize("nbytes", [16, 2560, 32 * 1024, 32 * 1024 + 16, 5 * 1024 * 1024 + 48])
+@pytest.mark.parametrize("blocks", [1, 7, 64])
+def test_copy_kernel_both_directions(stream, nbytes, blocks):
+    pool = P.HostPool(2 * nbytes + 1024)
+    try:
+        src = pool.take((nbytes,), np.uint8)
+        back = pool.take((nbytes,), np.uint8)
+        rng = np.random.default_rng(nbytes)
+        src[:] = rng.integers(0, 256, nbytes, dtype=np.uint8)
+        back[:] = 0
+        d = torch.full((nbytes + 512,), 0x7E, dtype=torch.uint8, device="cuda")
+        B.op_copy(d.data_ptr() + 256, src, nbytes, blocks, stream)       # host -> device
+        stream.synchronize()
+        got = d.cpu().numpy()
+        assert np.array_equal(got[256:256 + nbytes], src)
+        assert (got[:256] == 0x7E).all() and (got[256 + nbytes:] == 0x7E).all()   # nothing outside the range
+        B.op_copy(back, d.data_ptr() + 256, nbytes, blocks, stream)      # device -> host
+        stream.synchronize()
+        assert np.array_equal(back, src)
+    finally:
+        pool.close()
+
+
+def test_copy_rejects_misaligned(stream):
+    d = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(P.CtnError):
+        B.op_copy(d.data_ptr(), d.data_ptr() + 512, 24, 1, stream)
+    with pytest.raises(P.CtnError):
+        B.op_copy(d.data_ptr() + 8, d.data_ptr() + 512, 32, 1, stream)
+
+
+@pytest.mark.parametrize("hidden,rank,tp", [(768, 0, 1), (4096, 1, 2), (5120, 3, 4), (128, 0, 2)])
+def test_embed(stream, hidden, rank, tp):
+    rng = np.random.default_rng(hidden + rank)
+    vocab, seq, batch = 512, 7, 3
+    vl = vocab // tp
+    tok, pos = f16(rng, (vl, hidden)), f16(rng, (seq + 2, hidden))
+    ids = rng.integers(0, vocab, (batch, seq)).astype(np.int32)
+    ids[0, 0], ids[0, 1] = rank * vl, (rank + 1) * vl - 1          # slice edges
+    want = O.embed(ids, tok, pos, rank, np.float32).reshape(batch * seq, hidden)
+    x = torch.empty(batch * seq, hidden, dtype=torch.float32, device="cuda")
+    B.op_embed(dev(ids), dev(tok), dev(pos), x, batch * seq, seq, hidden, vl, rank, stream)
+    stream.synchronize()
+    assert np.array_equal(x.cpu().numpy(), want)                    # one fp32 add: exact
+
+
+@pytest.mark.parametrize("rows,hidden", [(1, 768), (8, 768), (5, 2048), (133, 4096), (64, 5120), (3, 128), (9, 8192)])
+def test_layernorm(stream, rows, hidden):
+    rng = np.random.default_rng(rows * hidden)
+    x = (rng.standard_normal((rows, hidden)) * 3 + 0.5).astype(np.float32)
+    g, b = (1 + 0.1 * rng.standard_normal(hidden)).astype(np.float16), f16(rng, hidden, 0.1)
+    want = O.layer_norm(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64))
+    out = torch.empty(rows, hidden, dtype=torch.float16, device="cuda")
+    B.op_layernorm(dev(x), dev(g), dev(b), out, rows, hidden, stream)
+    stream.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    # fp32 arithmetic then one rounding to fp16: within one fp16 ulp of the exact value
+    assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.maximum(np.abs(want), 2.0 ** -14) + 1e-6)
+
+
+GEMM_SHAPES = [(8, 2304, 768), (1, 128, 64), (33, 200, 72), (64, 6144, 4096), (130, 257, 136),
+               (1024, 4096, 2048), (300, 50272 // 4, 512), (2048, 1280, 5120)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+@pytest.mark.parametrize("epi", [P.EPI_BIAS_F16, P.EPI_BIAS_RELU_F16, P.EPI_BIAS_RESID_F32, P.EPI_F32])
+def test_gemm(stream, M, N, K, epi):
+    rng = np.random.default_rng(M * 31 + N * 7 + K + epi)
+    A, W, bias = f16(rng, (M, K)), f16(rng, (N, K), 0.05), f16(rng, N, 0.5)
+    res = rng.standard_normal((M, N)).astype(np.float32)
+    acc = A.astype(np.float64) @ W.astype(np.float64).T     # the definition, in fp64 on the CPU
+    if epi == P.EPI_BIAS_F16:
+        want, out = acc + bias.astype(np.float64), torch.empty(M, N, dtype=torch.float16, device="cuda")
+    elif epi == P.EPI_BIAS_RELU_F16:
+        want, out = np.maximum(acc + bias.astype(np.float64), 0), torch.empty(M, N, dtype=torch.float16, device="cuda")
+    elif epi == P.EPI_BIAS_RESID_F32:
+        want, out = res + acc + bias.astype(np.float64), dev(res)
+    else:
+        want, out = acc, torch.empty(M, N, dtype=torch.float32, device="cuda")
+    guard = torch.full((4096,), 7.0, dtype=torch.float32, device="cuda")   # detect stray writes after `out`
+    B.op_gemm(dev(A), dev(W), dev(bias), out, M, N, K, epi, stream)
+    stream.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    scale = np.sqrt(K) * 0.05
+    if out.dtype == torch.float16:
+        assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.abs(want) + 1e-4 * scale + 1e-7)
+    else:
+        assert np.abs(got - want).max() <= 2e-5 * scale * max(1.0, np.log2(K)) + 1e-6 * np.abs(want).max()
+    assert (guard == 7.0).all()
+
+
+def test_gemm_rejects_bad_k(stream):
+    a = torch.zeros(64, dtype=torch.float16, device="cuda")
+    with pytest.raises(P.CtnError):
+        B.op_gemm(a, a, a, a, 2, 2, 12, P.EPI_BIAS_F16, stream)
+
+
+@pytest.mark.parametrize("batch,seq,heads,d", [(1, 8, 12, 64), (2, 33, 3, 64), (4, 256, 16, 128), (1, 64, 16, 128),
+                                               (2, 129, 2, 128), (16, 128, 10, 128), (1, 300, 2, 64)])
+def test_attention(stream, batch, seq, heads, d):
+    rng = np.random.default_rng(batch * seq + heads + d)
+    hl = heads * d
+    qkv = f16(rng, (batch * seq, 3 * hl), 1.5)
+    q, k, v = (qkv[:, i * hl:(i + 1) * hl].astype(np.float64).reshape(batch, seq, hl) for i in range(3))
+    want = O.attention(q, k, v, heads).reshape(batch * seq, hl)
+    out = torch.full((batch * seq, hl), float("nan"), dtype=torch.float16, device="cuda")
+    B.op_attention(dev(qkv), out, batch, seq, heads, d, stream)
+    stream.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    # probabilities are rounded to fp16 before the second product, outputs to fp16
+    assert np.abs(got - want).max() <= 4e-3 * max(1.0, np.abs(want).max())
+    assert np.abs(got - want).mean() <= 4e-4 * np.abs(want).mean() + 1e-5

@@ -1,0 +1,163 @@
+"""Swap-in / swap-out through the C ABI: byte identity, residency policy, error paths."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+import paper_2306_13835_amd as P
+from oracle.lru import LruResidency
+from oracle.swap import DeviceImage, as_bytes
+from synth import ShardDesc, shard_bytes, param_list, CONFIGS
+from gpu_util import Rig
+
+pytestmark = pytest.mark.gpu
+
+SMALL = ShardDesc(3, 256, 1024, 4, vocab=1000, max_pos=62)            # ~5.6 MB, biases of 512 B
+SMALL_TP = ShardDesc(2, 640, 2560, 10, vocab=1000, max_pos=30, tp=2, rank=1)   # odd sizes: 640 B, 2560 B biases
+
+
+def check_device_copy(rig, m, desc):
+    """Every tensor read back from the arena equals the oracle's device image."""
+    img = DeviceImage([t.nbytes for t in rig.tensors[m]])
+    img.swap_in(rig.tensors[m])
+    for i in range(len(rig.tensors[m])):
+        got = rig.ctx.debug_read_param(m, i)
+        assert np.array_equal(as_bytes(got), img.tensors[i]), f"tensor {i}"
+
+
+@pytest.mark.parametrize("mode", [P.XFER_KERNEL, P.XFER_DMA])
+@pytest.mark.parametrize("desc", [SMALL, SMALL_TP])
+def test_round_trip_scribble_and_poison(mode, desc):
+    rig = Rig([desc], mode=mode)
+    try:
+        m = rig.add(desc, seed=5)
+        orig = [t.copy() for t in rig.tensors[m]]
+        rig.arena.fill_(0x7E)                         # fp16 NaN pattern everywhere
+        torch.cuda.synchronize()
+        rig.ctx.swap_in(m)
+        rig.ctx.wait(m)
+        assert rig.ctx.is_resident(m)
+        check_device_copy(rig, m, desc)
+        for t in rig.tensors[m]:                      # scribble: swap-out must really copy back
+            as_bytes(t)[:] = 0xA5
+        rig.ctx.swap_out(m)
+        rig.ctx.wait(m)
+        assert not rig.ctx.is_resident(m)
+        for t, o in zip(rig.tensors[m], orig):
+            assert np.array_equal(as_bytes(t), as_bytes(o))
+        st = rig.ctx.stats()
+        assert st["bytes_h2d"] == st["bytes_d2h"] == shard_bytes(desc)
+        assert st["resident_bytes"] == 0 and st["peak_resident_bytes"] == shard_bytes(desc)
+        in_ms, out_ms, blocks = rig.ctx.last_swap_ms(m)
+        assert in_ms > 0 and out_ms > 0 and len(blocks) == desc.layers + 1
+        assert all(b2 >= b1 for b1, b2 in zip(blocks, blocks[1:]))
+    finally:
+        rig.close()
+
+
+def test_dma_and_kernel_paths_leave_identical_arenas():
+    rig = Rig([SMALL])
+    try:
+        m = rig.add(SMALL, seed=9)
+        images = []
+        for mode in (P.XFER_KERNEL, P.XFER_DMA):
+            rig.ctx.set_mode(mode, True)
+            rig.arena.zero_()
+            torch.cuda.synchronize()
+            rig.ctx.swap_in(m)
+            rig.ctx.wait(m)
+            images.append(rig.arena.cpu().numpy().copy())
+            rig.ctx.swap_out(m)
+            rig.ctx.wait(m)
+        assert np.array_equal(images[0], images[1])
+    finally:
+        rig.close()
+
+
+def test_many_cycles_any_order_keeps_host_bits():
+    descs = [SMALL, SMALL_TP, SMALL]
+    rig = Rig(descs, budget=shard_bytes(SMALL) + shard_bytes(SMALL_TP) + 100)
+    try:
+        ms = [rig.add(d, seed=20 + i) for i, d in enumerate(descs)]
+        orig = [[t.copy() for t in rig.tensors[m]] for m in ms]
+        rng = np.random.default_rng(0)
+        for step in range(40):
+            m = int(rng.integers(0, 3))
+            if rng.random() < 0.3:
+                rig.ctx.swap_out(m)
+            else:
+                rig.ctx.set_mode(int(rng.integers(0, 2)), True)
+                rig.ctx.swap_in(m)
+                if rng.random() < 0.5:
+                    rig.ctx.wait(m)
+                    check_device_copy(rig, m, descs[m])
+            st = rig.ctx.stats()
+            assert st["resident_bytes"] <= st["budget_bytes"]
+        rig.ctx.sync()
+        for m in ms:
+            for t, o in zip(rig.tensors[m], orig[m]):
+                assert np.array_equal(as_bytes(t), as_bytes(o))
+        assert rig.ctx.stats()["peak_resident_bytes"] <= rig.ctx.stats()["budget_bytes"]
+    finally:
+        rig.close()
+
+
+def test_event_log_equals_oracle_lru():
+    descs = [SMALL] * 5
+    size = shard_bytes(SMALL)
+    rig = Rig(descs, budget=2 * size + 10, arena_bytes=2 * P.arena_bytes(SMALL))
+    try:
+        ms = [rig.add(d, seed=30 + i) for i, d in enumerate(descs)]
+        ref = LruResidency(2 * size + 10, [size] * 5)
+        rng = np.random.default_rng(3)
+        for step in range(60):
+            m = int(rng.integers(0, 5))
+            if rng.random() < 0.15:
+                rig.ctx.swap_out(m)
+                ref.swap_out(m)
+            else:
+                rig.ctx.swap_in(m)
+                ref.touch(m)
+            assert [rig.ctx.is_resident(k) for k in ms] == [ref.is_resident(k) for k in ms]
+        rig.ctx.sync()
+        assert rig.ctx.events() == ref.events
+        st = rig.ctx.stats()
+        assert st["n_hit"] == sum(e[0] == "hit" for e in ref.events)
+        assert st["n_miss"] == sum(e[0] == "miss" for e in ref.events)
+        assert st["peak_resident_bytes"] == ref.peak_resident
+    finally:
+        rig.close()
+
+
+def test_register_errors_and_idempotence():
+    rig = Rig([SMALL], budget=shard_bytes(SMALL))
+    try:
+        m = rig.add(SMALL, seed=1)
+        t = rig.tensors[m]
+        # pageable memory is not device accessible
+        with pytest.raises(P.CtnError) as e:
+            rig.ctx.register_model(SMALL, [np.array(x) for x in t])
+        assert e.value.code == -1
+        # wrong tensor count / wrong shape / wrong budget
+        with pytest.raises(P.CtnError):
+            rig.ctx.register_model(SMALL, t[:-1])
+        bad = list(t)
+        bad[4], bad[5] = t[5], t[4]
+        with pytest.raises(P.CtnError):
+            rig.ctx.register_model(SMALL, bad)
+        with pytest.raises(P.CtnError):
+            rig.ctx.register_model(SMALL, t, budget=123)
+        # a shard larger than the budget
+        big = ShardDesc(4, 256, 1024, 4, vocab=1000, max_pos=62)
+        with pytest.raises(P.CtnError) as e:
+            rig.ctx.register_model(big, t[:-2] + t[2:18] + t[-2:])
+        assert e.value.code == -2
+        # unknown handle; idempotent swaps
+        with pytest.raises(P.CtnError) as e:
+            rig.ctx.swap_in(7)
+        assert e.value.code == -3
+        rig.ctx.swap_out(m)                                   # not resident: no-op
+        rig.ctx.swap_in(m); rig.ctx.swap_in(m)
+        rig.ctx.wait(m)
+        assert rig.ctx.stats()["n_swap_in"] == 1 and rig.ctx.stats()["n_hit"] == 1
+    finally:
+        rig.close()
