@@ -47,7 +47,7 @@ enum {
   CTN_E_NOMEM = -7    /* host allocation failed / workspace too small for the library's tables */
 };
 
-enum { CTN_XFER_DMA = 0, CTN_XFER_KERNEL = 1 };
+enum { CTN_XFER_DMA = 0, CTN_XFER_KERNEL = 1, CTN_XFER_AUTO = 2 };
 
 /* One rank's share of an OPT decoder.  heads, ffn and vocab are those of the
  * whole model; the rank owns heads/tp heads, ffn/tp hidden units, vocab/tp
@@ -79,12 +79,22 @@ typedef struct {
   void* stream_compute;      /* hipStream_t; inference kernels */
   void* stream_h2d;          /* hipStream_t; swap-in  */
   void* stream_d2h;          /* hipStream_t; swap-out */
+                             /* All three NULL: the library creates and owns three streams, each on
+                                its own hardware queue and confined to its own compute units
+                                (copy_cus per transfer direction, the rest for inference), so copy
+                                wavefronts waiting on the host link never share a compute unit with
+                                the forward pass.  Otherwise all three must be given, distinct. */
   int32_t transfer_mode;     /* CTN_XFER_DMA: one hipMemcpyAsync per tensor (the paper's per-tensor
-                                messages, Section 5.1); CTN_XFER_KERNEL: one copy kernel per layer */
+                                messages, Section 5.1); CTN_XFER_KERNEL: one copy kernel per layer
+                                block; CTN_XFER_AUTO: a load uses the copy kernel when no offload
+                                is in flight and the DMA engines otherwise (kernel-issued host
+                                reads lose about 40 % of their rate against concurrent writes to
+                                the host, the DMA engines' reads do not); offloads use DMA */
   int32_t pipeline;          /* 0: inference waits for the whole shard (the paper's rule, Section 3.2);
                                 1: inference waits layer by layer */
   int32_t copy_blocks;       /* workgroups of a copy kernel; 0 = library default */
-  int32_t reserved;
+  int32_t copy_cus;          /* library-owned streams only: compute units reserved per transfer
+                                direction, at least 8 (one per XCD); 0 = library default */
 } ctn_config;
 
 typedef struct {
@@ -186,8 +196,11 @@ int ctn_last_swap_ms(ctn_ctx* ctx, ctn_model m, float* in_ms, float* out_ms, flo
 /* Reads the device copy of tensor `index` of a resident model into dst (host,
  * at least that tensor's nbytes); waits for the model's load first.  Tests. */
 int ctn_debug_read_param(ctn_ctx* ctx, ctn_model m, int32_t index, void* dst_host, uint64_t cap);
+/* The three streams in use (hipStream_t), the library's own or the caller's. */
+int ctn_get_streams(ctn_ctx* ctx, void** compute, void** h2d, void** d2h);
 /* Changes transfer mode / pipelining / copy-kernel width between operations. */
 int ctn_set_mode(ctn_ctx* ctx, int32_t transfer_mode, int32_t pipeline, int32_t copy_blocks);
+/* HIP status behind the last CTN_E_HIP of this context (ctx == NULL: of calls that take no context). */
 int ctn_last_hip_error(ctn_ctx* ctx);
 const char* ctn_strerror(int code);
 

@@ -9,14 +9,14 @@ import numpy as np
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcomputron_mi355.so")
 
-XFER_DMA, XFER_KERNEL = 0, 1
+XFER_DMA, XFER_KERNEL, XFER_AUTO = 0, 1, 2
 EPI_BIAS_F16, EPI_BIAS_RELU_F16, EPI_BIAS_RESID_F32, EPI_F32 = 0, 1, 2, 3
 
 DECLARED_SYMBOLS = [
     "ctn_create", "ctn_destroy", "ctn_host_alloc", "ctn_host_free", "ctn_register_model",
     "ctn_swap_in", "ctn_swap_out", "ctn_wait", "ctn_sync", "ctn_infer", "ctn_workspace_bytes",
     "ctn_arena_bytes", "ctn_is_resident", "ctn_get_stats", "ctn_get_events", "ctn_last_swap_ms",
-    "ctn_debug_read_param", "ctn_set_mode", "ctn_last_hip_error", "ctn_strerror",
+    "ctn_debug_read_param", "ctn_get_streams", "ctn_set_mode", "ctn_last_hip_error", "ctn_strerror",
     "ctn_residency_replay", "ctn_op_copy", "ctn_op_dma", "ctn_op_embed", "ctn_op_layernorm",
     "ctn_op_gemm", "ctn_op_attention",
 ]
@@ -36,7 +36,7 @@ class Config(C.Structure):
                 ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_uint64),
                 ("stream_compute", C.c_void_p), ("stream_h2d", C.c_void_p), ("stream_d2h", C.c_void_p),
                 ("transfer_mode", C.c_int32), ("pipeline", C.c_int32), ("copy_blocks", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("copy_cus", C.c_int32)]
 
 
 class Stats(C.Structure):
@@ -67,6 +67,10 @@ def lib() -> C.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2306_13835_amd.build`")
+    # The streams and device buffers handed to the library come from PyTorch, so both must use
+    # one HIP runtime instance: PyTorch's copy has to be in the process before the library binds
+    # to libamdhip64 (loading in the other order yields a second runtime that sees no device).
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, u64, i32, i64 = C.c_void_p, C.c_uint64, C.c_int32, C.c_int64
     P = C.POINTER
@@ -88,6 +92,7 @@ def lib() -> C.CDLL:
         "ctn_get_events": (C.c_int, [vp, u64, P(Event), u64, P(u64), P(u64)]),
         "ctn_last_swap_ms": (C.c_int, [vp, i32, P(C.c_float), P(C.c_float), P(C.c_float), i32, P(i32)]),
         "ctn_debug_read_param": (C.c_int, [vp, i32, i32, vp, u64]),
+        "ctn_get_streams": (C.c_int, [vp, P(vp), P(vp), P(vp)]),
         "ctn_set_mode": (C.c_int, [vp, i32, i32, i32]),
         "ctn_last_hip_error": (C.c_int, [vp]),
         "ctn_strerror": (C.c_char_p, [C.c_int]),
@@ -143,7 +148,7 @@ class HostPool:
         p = C.c_void_p()
         rc = lib().ctn_host_alloc(self.nbytes, C.byref(p))
         if rc:
-            raise CtnError(rc, f"ctn_host_alloc({nbytes})")
+            raise CtnError(rc, f"ctn_host_alloc({nbytes})", lib().ctn_last_hip_error(None))
         self.ptr = p.value
         self._buf = (C.c_uint8 * self.nbytes).from_address(self.ptr)
         self.bytes = np.frombuffer(self._buf, dtype=np.uint8)
@@ -179,17 +184,25 @@ class Context:
     """One ctn_ctx.  `arena`/`workspace` are torch CUDA tensors (uint8), streams are
     torch.cuda.Stream objects; torch only provides the memory and the streams."""
 
-    def __init__(self, budget: int, arena, workspace, stream_compute, stream_h2d, stream_d2h,
-                 transfer_mode: int = XFER_KERNEL, pipeline: bool = True, copy_blocks: int = 0):
+    def __init__(self, budget: int, arena, workspace, stream_compute=None, stream_h2d=None, stream_d2h=None,
+                 transfer_mode: int = XFER_KERNEL, pipeline: bool = True, copy_blocks: int = 0,
+                 copy_cus: int = 0):
+        """With no streams given the library creates its own three (CU-partitioned); they are
+        exposed as `stream_compute`, `stream_h2d`, `stream_d2h` (torch ExternalStream)."""
+        import torch
         self._keep = (arena, workspace, stream_compute, stream_h2d, stream_d2h)
+        sp = [s.cuda_stream if s is not None else None for s in (stream_compute, stream_h2d, stream_d2h)]
         cfg = Config(int(budget), arena.data_ptr(), arena.numel() * arena.element_size(),
                      workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                     stream_compute.cuda_stream, stream_h2d.cuda_stream, stream_d2h.cuda_stream,
-                     transfer_mode, int(bool(pipeline)), copy_blocks, 0)
+                     sp[0], sp[1], sp[2], transfer_mode, int(bool(pipeline)), copy_blocks, copy_cus)
         h = C.c_void_p()
         rc = lib().ctn_create(C.byref(cfg), C.byref(h))
         if rc:
-            raise CtnError(rc, "ctn_create")
+            raise CtnError(rc, "ctn_create", lib().ctn_last_hip_error(None))
+        a, b, c = C.c_void_p(), C.c_void_p(), C.c_void_p()
+        lib().ctn_get_streams(h, C.byref(a), C.byref(b), C.byref(c))
+        self.stream_compute, self.stream_h2d, self.stream_d2h = (
+            torch.cuda.ExternalStream(p.value) for p in (a, b, c))
         self.h = h
         self._params = []
 

@@ -20,6 +20,9 @@ constexpr uint32_t kChunk16 = kThreads * kUnroll;   // 16-byte units per chunk (
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// DIR only gives the two directions distinct kernel names in profiles
+// (0: host -> device, 1: device -> host, 2: anything else); the code is the same.
+template <int DIR>
 __global__ __launch_bounds__(kThreads) void copy_table_kernel(const CopyTable t) {
   const uint32_t total = t.chunk_prefix[t.n];
   for (uint32_t chunk = blockIdx.x; chunk < total; chunk += gridDim.x) {
@@ -64,14 +67,16 @@ bool copy_table_finish(CopyTable& t) {
   return true;
 }
 
-int default_copy_blocks() { return 64; }
+int default_copy_blocks() { return 32; }
 
-hipError_t launch_copy_table(const CopyTable& t, int blocks, hipStream_t s) {
+hipError_t launch_copy_table(const CopyTable& t, int blocks, hipStream_t s, int dir) {
   if (t.n <= 0 || t.chunk_prefix[t.n] == 0) return hipSuccess;
   if (blocks <= 0) blocks = default_copy_blocks();
   uint32_t total = t.chunk_prefix[t.n];
   if (static_cast<uint32_t>(blocks) > total) blocks = static_cast<int>(total);
-  hipLaunchKernelGGL(copy_table_kernel, dim3(blocks), dim3(kThreads), 0, s, t);
+  if (dir == kCopyH2D) hipLaunchKernelGGL(copy_table_kernel<0>, dim3(blocks), dim3(kThreads), 0, s, t);
+  else if (dir == kCopyD2H) hipLaunchKernelGGL(copy_table_kernel<1>, dim3(blocks), dim3(kThreads), 0, s, t);
+  else hipLaunchKernelGGL(copy_table_kernel<2>, dim3(blocks), dim3(kThreads), 0, s, t);
   return hipGetLastError();
 }
 

@@ -41,11 +41,20 @@ __device__ inline int xcd_remap(int id, int total) {
   return x * chunk + (x < rem ? x : rem) + slot;
 }
 
+// Up to three products that share A run as one launch ("parts"): part p
+// multiplies by W[p] (N rows), adds bias[p] and writes columns [p*N, (p+1)*N)
+// of an output with row stride ldc.  This is how q, k and v are projected
+// together although their weights are separate tensors.
+struct GemmArgs {
+  const _Float16* A;
+  const _Float16* W[3];
+  const _Float16* bias[3];
+  void* out;
+  int M, N, K, ldc, parts;
+};
+
 template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__(256) void gemm_nt_kernel(const _Float16* __restrict__ A,
-                                                      const _Float16* __restrict__ W,
-                                                      const _Float16* __restrict__ bias, void* __restrict__ out,
-                                                      int M, int N, int K) {
+__global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
   static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts per workgroup");
   static_assert(WM % 32 == 0 && WN % 32 == 0 && BM % 32 == 0 && BN % 32 == 0, "32x32 MFMA tiles");
   constexpr int TM = WM / 32, TN = WN / 32;     // MFMA tiles per wavefront
@@ -54,9 +63,17 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const _Float16* __restrict
   __shared__ __attribute__((aligned(16))) _Float16 As[2][BM][LDS_ROW];
   __shared__ __attribute__((aligned(16))) _Float16 Bs[2][BN][LDS_ROW];
 
+  const int M = g.M, N = g.N, K = g.K;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+  int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n * g.parts);
+  const int part = tile / (tiles_m * tiles_n);
+  tile -= part * tiles_m * tiles_n;
   const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;   // m fastest: W tile shared by neighbours
+  const _Float16* __restrict__ A = g.A;
+  const _Float16* __restrict__ W = part == 0 ? g.W[0] : (part == 1 ? g.W[1] : g.W[2]);
+  const _Float16* __restrict__ bias = part == 0 ? g.bias[0] : (part == 1 ? g.bias[1] : g.bias[2]);
+  void* __restrict__ out = g.out;
+  const int ldc = g.ldc, col0 = part * N;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave % (BM / WM)) * WM, wn0 = (wave / (BM / WM)) * WN;
@@ -138,7 +155,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const _Float16* __restrict
       for (int e = 0; e < 16; ++e) {
         const int m = m0 + wm0 + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
         if (m >= M) continue;
-        const int64_t o = static_cast<int64_t>(m) * N + n;
+        const int64_t o = static_cast<int64_t>(m) * ldc + col0 + n;
         const float v = acc[i][j][e] + bv;
         if (EPI == CTN_EPI_BIAS_F16) {
           static_cast<_Float16*>(out)[o] = static_cast<_Float16>(v);
@@ -155,12 +172,10 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const _Float16* __restrict
 }
 
 template <int BM, int BN, int WM, int WN>
-hipError_t launch_tiles(const _Float16* A, const _Float16* W, const _Float16* bias, void* out, int M, int N,
-                        int K, int epi, hipStream_t s) {
-  const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+hipError_t launch_tiles(const GemmArgs& g, int epi, hipStream_t s) {
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * g.parts;
   const dim3 grid(tiles), block(256);
-#define CTN_GEMM(E) \
-  hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, WM, WN, E>), grid, block, 0, s, A, W, bias, out, M, N, K)
+#define CTN_GEMM(E) hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, WM, WN, E>), grid, block, 0, s, g)
   switch (epi) {
     case CTN_EPI_BIAS_F16: CTN_GEMM(CTN_EPI_BIAS_F16); break;
     case CTN_EPI_BIAS_RELU_F16: CTN_GEMM(CTN_EPI_BIAS_RELU_F16); break;
@@ -174,14 +189,31 @@ hipError_t launch_tiles(const _Float16* A, const _Float16* W, const _Float16* bi
 
 }  // namespace
 
+static hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s) {
+  if (g.M <= 0 || g.N <= 0) return hipSuccess;
+  if (g.K <= 0 || g.K % 8 || g.parts < 1 || g.parts > 3) return hipErrorInvalidValue;
+  for (int p = 0; p < g.parts; ++p)
+    if (!g.W[p] || (epi != CTN_EPI_F32 && !g.bias[p])) return hipErrorInvalidValue;
+  if (g.M <= 32) return launch_tiles<32, 128, 32, 32>(g, epi, s);
+  if (g.M <= 64) return launch_tiles<64, 64, 32, 32>(g, epi, s);
+  return launch_tiles<128, 128, 64, 64>(g, epi, s);
+}
+
 hipError_t launch_gemm(const _Float16* A, const _Float16* W, const _Float16* bias, void* out, int M, int N,
                        int K, int epi, hipStream_t s) {
-  if (M <= 0 || N <= 0) return hipSuccess;
-  if (K <= 0 || K % 8) return hipErrorInvalidValue;
-  if (epi != CTN_EPI_F32 && bias == nullptr) return hipErrorInvalidValue;
-  if (M <= 32) return launch_tiles<32, 128, 32, 32>(A, W, bias, out, M, N, K, epi, s);
-  if (M <= 64) return launch_tiles<64, 64, 32, 32>(A, W, bias, out, M, N, K, epi, s);
-  return launch_tiles<128, 128, 64, 64>(A, W, bias, out, M, N, K, epi, s);
+  GemmArgs g{};
+  g.A = A; g.W[0] = W; g.bias[0] = bias; g.out = out;
+  g.M = M; g.N = N; g.K = K; g.ldc = N; g.parts = 1;
+  return dispatch(g, epi, s);
+}
+
+hipError_t launch_gemm3(const _Float16* A, const _Float16* const W[3], const _Float16* const bias[3], void* out,
+                        int M, int N, int K, int epi, hipStream_t s) {
+  GemmArgs g{};
+  g.A = A; g.out = out;
+  for (int p = 0; p < 3; ++p) { g.W[p] = W[p]; g.bias[p] = bias[p]; }
+  g.M = M; g.N = N; g.K = K; g.ldc = 3 * N; g.parts = 3;
+  return dispatch(g, epi, s);
 }
 
 }  // namespace ctn

@@ -19,7 +19,8 @@ struct CopyTable {
 };
 // Fills chunk_prefix from seg[].n16; returns false if the table is too large.
 bool copy_table_finish(CopyTable& t);
-hipError_t launch_copy_table(const CopyTable& t, int blocks, hipStream_t s);
+enum { kCopyH2D = 0, kCopyD2H = 1, kCopyOther = 2 };
+hipError_t launch_copy_table(const CopyTable& t, int blocks, hipStream_t s, int dir);
 int default_copy_blocks();
 
 // ---- elementwise -------------------------------------------------------------
@@ -31,6 +32,9 @@ hipError_t launch_layernorm(const float* x, const _Float16* g, const _Float16* b
 // ---- dense products ------------------------------------------------------------
 hipError_t launch_gemm(const _Float16* A, const _Float16* W, const _Float16* bias, void* out, int M, int N,
                        int K, int epilogue, hipStream_t s);
+// Three products sharing A in one launch: out[M, 3N] = [A W0^T + b0 | A W1^T + b1 | A W2^T + b2].
+hipError_t launch_gemm3(const _Float16* A, const _Float16* const W[3], const _Float16* const bias[3], void* out,
+                        int M, int N, int K, int epilogue, hipStream_t s);
 hipError_t launch_attention(const _Float16* qkv, _Float16* out, int batch, int seq, int heads, int head_dim,
                             hipStream_t s);
 

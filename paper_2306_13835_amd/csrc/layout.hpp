@@ -6,10 +6,10 @@
 // load can signal "block b has landed" (Section 3.2 loads whole models; the
 // block split is this library's refinement):
 //   block 0      : embed_tokens, embed_positions, final_ln.w, final_ln.b
-//   block 1 + l  : the 16 tensors of decoder layer l
-// Inside a layer q.w|k.w|v.w and q.b|k.b|v.b are stored back to back so the
-// three column-parallel projections run as one product.  Every group starts
-// on a 256-byte boundary.
+//   block 1 + l  : the 16 tensors of decoder layer l, in list order
+// Every tensor starts on a 256-byte boundary.  Keeping list order means that a
+// caller who stores a layer's tensors back to back on the host gets a device
+// image with the same spacing, so neighbouring tensors can travel as one copy.
 #pragma once
 #include <cstdint>
 #include <vector>
@@ -95,38 +95,20 @@ inline ShardLayout make_layout(const ctn_model_desc& d) {
     L.param_bytes += L.nbytes[i];
   }
   uint64_t cur = 0;
-  auto place = [&](int block, int t, bool packed_after_previous) {
-    if (!packed_after_previous) cur = align_up(cur);
+  auto place = [&](int block, int t) {
+    cur = align_up(cur);
     L.offset[t] = cur;
     cur += L.nbytes[t];
     L.block_of[t] = block;
     L.block_tensors[block].push_back(t);
     L.block_bytes[block] += L.nbytes[t];
   };
-  place(0, 0, false);
-  place(0, 1, false);
-  place(0, L.n_tensors - 2, false);
-  place(0, L.n_tensors - 1, false);
-  for (int l = 0; l < d.layers; ++l) {
-    const int b = 1 + l;
-    auto T = [&](int w) { return L.layer_tensor(l, w); };
-    place(b, T(LN1_W), false);
-    place(b, T(LN1_B), false);
-    place(b, T(Q_W), false);
-    place(b, T(K_W), true);
-    place(b, T(V_W), true);
-    place(b, T(Q_B), false);
-    place(b, T(K_B), true);
-    place(b, T(V_B), true);
-    place(b, T(O_W), false);
-    place(b, T(O_B), false);
-    place(b, T(LN2_W), false);
-    place(b, T(LN2_B), false);
-    place(b, T(FC1_W), false);
-    place(b, T(FC1_B), false);
-    place(b, T(FC2_W), false);
-    place(b, T(FC2_B), false);
-  }
+  place(0, 0);
+  place(0, 1);
+  place(0, L.n_tensors - 2);
+  place(0, L.n_tensors - 1);
+  for (int l = 0; l < d.layers; ++l)
+    for (int w = 0; w < kLayerTensors; ++w) place(1 + l, L.layer_tensor(l, w));
   L.arena_bytes = align_up(cur);
   return L;
 }

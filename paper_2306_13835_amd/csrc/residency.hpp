@@ -7,6 +7,7 @@
 // manager caps parameter bytes, which is the same thing for equal sizes.
 #pragma once
 #include <algorithm>
+#include <climits>
 #include <cstdint>
 #include <limits>
 #include <vector>
@@ -87,6 +88,45 @@ class RangeAllocator {
         return off;
       }
     return UINT64_MAX;
+  }
+  // Placement that waits least on ranges still being read by offloads.
+  // `busy` lists those ranges in the order their offloads complete (oldest
+  // first).  Every hole is tried at its start and slid just past each busy
+  // range; the cost of a placement is the position of the last busy range it
+  // overlaps (-1: none).  Lowest cost wins, then lowest offset.
+  uint64_t alloc_avoiding(uint64_t len, const std::vector<Range>& busy) {
+    int best_cost = INT32_MAX;
+    uint64_t best_off = UINT64_MAX;
+    auto consider = [&](const Range& hole, uint64_t off) {
+      if (off < hole.off || off + len < off || off + len > hole.off + hole.len) return;
+      int cost = -1;
+      for (size_t k = 0; k < busy.size(); ++k)
+        if (busy[k].off < off + len && off < busy[k].off + busy[k].len) cost = static_cast<int>(k);
+      if (cost < best_cost || (cost == best_cost && off < best_off)) {
+        best_cost = cost;
+        best_off = off;
+      }
+    };
+    for (const Range& hole : free_) {
+      consider(hole, hole.off);
+      for (const Range& b : busy) consider(hole, b.off + b.len);
+    }
+    if (best_off == UINT64_MAX) return UINT64_MAX;
+    alloc_at(best_off, len);
+    return best_off;
+  }
+  // Carves [off, off+len) out of the hole that contains it (caller guarantees it fits).
+  void alloc_at(uint64_t off, uint64_t len) {
+    for (size_t i = 0; i < free_.size(); ++i) {
+      const Range hole = free_[i];
+      if (off >= hole.off && off + len <= hole.off + hole.len) {
+        free_.erase(free_.begin() + i);
+        if (off + len < hole.off + hole.len)
+          free_.insert(free_.begin() + i, {off + len, hole.off + hole.len - (off + len)});
+        if (off > hole.off) free_.insert(free_.begin() + i, {hole.off, off - hole.off});
+        return;
+      }
+    }
   }
   void release(uint64_t off, uint64_t len) {
     auto it = std::lower_bound(free_.begin(), free_.end(), off,

@@ -27,14 +27,22 @@ namespace {
 struct PendingRelease {   // arena range given back by a swap-out that may still be copying
   uint64_t off, len;
   hipEvent_t done;        // borrowed from the model that was swapped out
+  int model;
 };
 
 struct Model {
   ShardLayout lay;
   std::vector<void*> host;           // per tensor, list order (host address)
   std::vector<void*> host_dev;       // the same memory as the device sees it
+  // Per transfer block: maximal runs of tensors that are back to back both on
+  // the host and in the arena image, so one copy can move a whole run.
+  struct Run { int first; uint64_t bytes; };   // first tensor (list index) and total bytes
+  std::vector<std::vector<Run>> runs;
   bool resident = false;
   uint64_t arena_off = 0;
+  uint64_t out_off = 0;              // range the current / last offload reads from
+  bool fragmented = true;            // many runs per block: the copy kernel beats per-run DMA when the link is quiet
+  bool offload_enqueued = true;      // false between the eviction decision and the offload's enqueue
   std::vector<hipEvent_t> ev_block;  // recorded on the h2d stream after each block
   hipEvent_t ev_in_start = nullptr, ev_out_start = nullptr, ev_out_done = nullptr, ev_last_use = nullptr;
   bool used_since_load = false;      // ev_last_use recorded since the last swap-in
@@ -55,16 +63,25 @@ struct Activations {   // carved from the workspace for one inference of M token
 struct ctn_ctx {
   ctn_config cfg{};
   hipStream_t s_compute = nullptr, s_h2d = nullptr, s_d2h = nullptr;
+  bool own_streams = false;
+  // Library-owned streams only: an unmasked compute stream for inferences that
+  // start while the link is quiet (all compute units, no copy wavefronts to avoid).
+  hipStream_t s_wide = nullptr;
+  hipStream_t last_compute = nullptr;
+  hipEvent_t ev_compute_done = nullptr;
   Residency res{0};
   RangeAllocator arena;
   std::vector<std::unique_ptr<Model>> models;
   std::vector<PendingRelease> pending;
+  std::vector<int> deferred;         // evicted models whose offload is not enqueued yet
   std::vector<ctn_event> events;
   ctn_stats stats{};
   int last_hip = 0;
 };
 
 namespace {
+
+int g_last_hip = 0;   // HIP status of the last failing call made without a context
 
 #define CTN_HIP(ctx, expr)                        \
   do {                                            \
@@ -114,11 +131,26 @@ uint64_t activation_bytes(const ctn_model_desc& d, int64_t M, bool with_logits, 
   return cur;
 }
 
-// Enqueue the copy of model m back to its host tensors and give its range back.
-int do_swap_out(ctn_ctx* c, int mi) {
+// Eviction happens in two steps so that, on a miss, the load of the requested
+// model and its forward pass can be enqueued before the (latency-insensitive)
+// offload of the victims: evict_logical() updates the bookkeeping and frees
+// the arena range; enqueue_offload() issues the copies back to the host
+// tensors and records the completion event the freed range waits on.
+void evict_logical(ctn_ctx* c, int mi) {
   Model* m = c->models[mi].get();
-  if (!m->resident) return CTN_OK;
-  char* arena = static_cast<char*>(c->cfg.arena_dev) + m->arena_off;
+  m->resident = false;
+  m->offload_enqueued = false;
+  m->out_off = m->arena_off;
+  c->arena.release(m->arena_off, m->lay.arena_bytes);
+  c->pending.push_back({m->arena_off, m->lay.arena_bytes, m->ev_out_done, mi});
+  c->res.mark_evicted(mi);
+  c->deferred.push_back(mi);
+}
+
+int enqueue_offload(ctn_ctx* c, int mi) {
+  Model* m = c->models[mi].get();
+  if (m->offload_enqueued) return CTN_OK;
+  char* arena = static_cast<char*>(c->cfg.arena_dev) + m->out_off;
   // The offload must see the complete device copy and must not overtake an
   // inference that is still reading it.
   CTN_HIP(c, hipStreamWaitEvent(c->s_d2h, m->ev_block.back(), 0));
@@ -128,34 +160,47 @@ int do_swap_out(ctn_ctx* c, int mi) {
   for (int b = 0; b < L.n_blocks; ++b) {
     if (c->cfg.transfer_mode == CTN_XFER_KERNEL) {
       CopyTable t{};
-      for (int ti : L.block_tensors[b]) {
-        t.seg[t.n].src = arena + L.offset[ti];
-        t.seg[t.n].dst = m->host_dev[ti];
-        t.seg[t.n].n16 = L.nbytes[ti] / 16;
+      for (const Model::Run& r : m->runs[b]) {
+        t.seg[t.n].src = arena + L.offset[r.first];
+        t.seg[t.n].dst = m->host_dev[r.first];
+        t.seg[t.n].n16 = r.bytes / 16;
         ++t.n;
       }
       if (!copy_table_finish(t)) return CTN_E_INVAL;
-      CTN_HIP(c, launch_copy_table(t, c->cfg.copy_blocks, c->s_d2h));
-    } else {
+      CTN_HIP(c, launch_copy_table(t, c->cfg.copy_blocks, c->s_d2h, kCopyD2H));
+    } else if (c->cfg.transfer_mode == CTN_XFER_DMA) {   // one message per tensor (Section 5.1)
       for (int ti : L.block_tensors[b])
         CTN_HIP(c, hipMemcpyAsync(m->host[ti], arena + L.offset[ti], L.nbytes[ti], hipMemcpyDeviceToHost,
+                                  c->s_d2h));
+    } else {                                             // one message per run of adjacent tensors
+      for (const Model::Run& r : m->runs[b])
+        CTN_HIP(c, hipMemcpyAsync(m->host[r.first], arena + L.offset[r.first], r.bytes, hipMemcpyDeviceToHost,
                                   c->s_d2h));
     }
   }
   CTN_HIP(c, hipEventRecord(m->ev_out_done, c->s_d2h));
+  m->offload_enqueued = true;
   m->out_recorded = true;
   m->pending_out = true;
-  m->resident = false;
-  c->arena.release(m->arena_off, L.arena_bytes);
-  c->pending.push_back({m->arena_off, L.arena_bytes, m->ev_out_done});
-  c->res.mark_evicted(mi);
   c->stats.bytes_d2h += L.param_bytes;
   c->stats.n_swap_out += 1;
   return CTN_OK;
 }
 
+// Issues every offload that was decided but not yet enqueued.
+int flush_deferred(ctn_ctx* c) {
+  for (int mi : c->deferred) {
+    int rc = enqueue_offload(c, mi);
+    if (rc) return rc;
+  }
+  c->deferred.clear();
+  return CTN_OK;
+}
+
 // Make model mi resident (a use).  On a miss: evict least recently used
 // models while the budget (or the arena) has no room, then enqueue the load.
+// Offloads of the victims stay deferred (see flush_deferred) unless the load
+// has to reuse a victim's range.
 int ensure_resident(ctn_ctx* c, int mi) {
   Model* m = c->models[mi].get();
   std::vector<int> victims;
@@ -167,54 +212,75 @@ int ensure_resident(ctn_ctx* c, int mi) {
   }
   const ShardLayout& L = m->lay;
   if (L.param_bytes > c->res.budget() || L.arena_bytes > c->cfg.arena_bytes) return CTN_E_TOO_BIG;
+  int rc = flush_deferred(c);
+  if (rc) return rc;
+  // Forget offloads that have finished; the others still read their old ranges.
+  for (size_t i = 0; i < c->pending.size();) {
+    if (hipEventQuery(c->pending[i].done) == hipSuccess) {
+      c->pending.erase(c->pending.begin() + i);
+    } else {
+      (void)hipGetLastError();   // "not ready" is an answer, not a failure to report later
+      ++i;
+    }
+  }
   while (c->res.over_budget_with(mi)) {
     int v = c->res.oldest(mi);
     if (v < 0) return CTN_E_BUSY;
-    int rc = do_swap_out(c, v);
-    if (rc) return rc;
+    evict_logical(c, v);
     victims.push_back(v);
   }
-  uint64_t off = c->arena.alloc(L.arena_bytes);
+  auto busy_ranges = [&]() {
+    std::vector<RangeAllocator::Range> b;
+    for (const PendingRelease& p : c->pending) b.push_back({p.off, p.len});
+    return b;
+  };
+  // Prefer a hole no offload is reading, so load and offload overlap on the
+  // two link directions (Section 3.2 / 5.1); otherwise the load waits.
+  uint64_t off = c->arena.alloc_avoiding(L.arena_bytes, busy_ranges());
   while (off == UINT64_MAX) {   // budget has room but no hole is wide enough: keep evicting
     int v = c->res.oldest(mi);
     if (v < 0) return CTN_E_BUSY;
-    int rc = do_swap_out(c, v);
-    if (rc) return rc;
+    evict_logical(c, v);
     victims.push_back(v);
-    off = c->arena.alloc(L.arena_bytes);
+    off = c->arena.alloc_avoiding(L.arena_bytes, busy_ranges());
   }
   m->arena_off = off;
-  // A load into a range that an offload is still reading must wait for it;
-  // loads into other ranges overlap with the offload (Section 3.2 / 5.1).
-  for (size_t i = 0; i < c->pending.size();) {
-    PendingRelease& p = c->pending[i];
-    const hipError_t q = hipEventQuery(p.done);
-    if (q == hipSuccess) {
-      c->pending.erase(c->pending.begin() + i);
-      continue;
-    }
-    (void)hipGetLastError();   // "not ready" is an answer, not a failure to report later
-    if (p.off < off + L.arena_bytes && off < p.off + p.len) CTN_HIP(c, hipStreamWaitEvent(c->s_h2d, p.done, 0));
-    ++i;
+  bool reuses_victim_range = false;
+  for (const PendingRelease& p : c->pending)
+    if (p.off < off + L.arena_bytes && off < p.off + p.len && !c->models[p.model]->offload_enqueued)
+      reuses_victim_range = true;
+  if (reuses_victim_range) {     // the completion events the load must wait on have to exist first
+    rc = flush_deferred(c);
+    if (rc) return rc;
   }
+  for (const PendingRelease& p : c->pending)
+    if (p.off < off + L.arena_bytes && off < p.off + p.len) CTN_HIP(c, hipStreamWaitEvent(c->s_h2d, p.done, 0));
   // The load reads the host tensors this model's own offload may still be writing.
   if (m->pending_out) CTN_HIP(c, hipStreamWaitEvent(c->s_h2d, m->ev_out_done, 0));
   char* arena = static_cast<char*>(c->cfg.arena_dev) + off;
+  // Kernel-issued host reads collapse when an offload is writing to the host
+  // at the same time; the DMA engines' reads do not.
+  const bool load_by_kernel = c->cfg.transfer_mode == CTN_XFER_KERNEL ||
+                              (c->cfg.transfer_mode == CTN_XFER_AUTO && c->pending.empty() && m->fragmented);
   CTN_HIP(c, hipEventRecord(m->ev_in_start, c->s_h2d));
   for (int b = 0; b < L.n_blocks; ++b) {
-    if (c->cfg.transfer_mode == CTN_XFER_KERNEL) {
+    if (load_by_kernel) {
       CopyTable t{};
-      for (int ti : L.block_tensors[b]) {
-        t.seg[t.n].src = m->host_dev[ti];
-        t.seg[t.n].dst = arena + L.offset[ti];
-        t.seg[t.n].n16 = L.nbytes[ti] / 16;
+      for (const Model::Run& r : m->runs[b]) {
+        t.seg[t.n].src = m->host_dev[r.first];
+        t.seg[t.n].dst = arena + L.offset[r.first];
+        t.seg[t.n].n16 = r.bytes / 16;
         ++t.n;
       }
       if (!copy_table_finish(t)) return CTN_E_INVAL;
-      CTN_HIP(c, launch_copy_table(t, c->cfg.copy_blocks, c->s_h2d));
-    } else {
+      CTN_HIP(c, launch_copy_table(t, c->cfg.copy_blocks, c->s_h2d, kCopyH2D));
+    } else if (c->cfg.transfer_mode == CTN_XFER_DMA) {   // one message per tensor (Section 5.1)
       for (int ti : L.block_tensors[b])
         CTN_HIP(c, hipMemcpyAsync(arena + L.offset[ti], m->host[ti], L.nbytes[ti], hipMemcpyHostToDevice,
+                                  c->s_h2d));
+    } else {                                             // one message per run of adjacent tensors
+      for (const Model::Run& r : m->runs[b])
+        CTN_HIP(c, hipMemcpyAsync(arena + L.offset[r.first], m->host[r.first], r.bytes, hipMemcpyHostToDevice,
                                   c->s_h2d));
     }
     CTN_HIP(c, hipEventRecord(m->ev_block[b], c->s_h2d));
@@ -233,6 +299,54 @@ int ensure_resident(ctn_ctx* c, int mi) {
   return CTN_OK;
 }
 
+constexpr int kDefaultCopyCus = 8;
+
+// Three streams, each with its own hardware queue and a disjoint set of
+// compute units: bits [0, n) of the CU mask for swap-in, [n, 2n) for swap-out,
+// the rest for inference.  Consecutive mask bits fall on consecutive XCDs, so
+// n = 8 takes one compute unit from every XCD.  A wavefront of the copy
+// kernel spends microseconds waiting on each host-link load; sharing a compute
+// unit's memory pipeline with it stalls the forward pass's wavefronts, which
+// this partition prevents.
+int create_partitioned_streams(ctn_ctx* c, int copy_cus) {
+  int dev = 0;
+  hipDeviceProp_t prop;
+  CTN_HIP(c, hipGetDevice(&dev));
+  CTN_HIP(c, hipGetDeviceProperties(&prop, dev));
+  const int n_cu = prop.multiProcessorCount;
+  if (n_cu < 4 * copy_cus) return CTN_E_INVAL;
+  const int words = (n_cu + 31) / 32;
+  auto make = [&](int lo, int hi, hipStream_t* out) -> hipError_t {
+    std::vector<uint32_t> mask(words, 0u);
+    for (int b = lo; b < hi; ++b) mask[b / 32] |= 1u << (b % 32);
+    return hipExtStreamCreateWithCUMask(out, (uint32_t)words, mask.data());
+  };
+  CTN_HIP(c, make(0, copy_cus, &c->s_h2d));
+  CTN_HIP(c, make(copy_cus, 2 * copy_cus, &c->s_d2h));
+  CTN_HIP(c, make(2 * copy_cus, n_cu, &c->s_compute));
+  CTN_HIP(c, hipStreamCreateWithFlags(&c->s_wide, hipStreamNonBlocking));
+  CTN_HIP(c, hipEventCreateWithFlags(&c->ev_compute_done, hipEventDisableTiming));
+  c->own_streams = true;
+  return CTN_OK;
+}
+
+// True when no load or offload is still running (events queried, flags refreshed).
+bool link_quiet(ctn_ctx* c) {
+  bool quiet = true;
+  for (auto& m : c->models) {
+    if (m->pending_in) {
+      if (hipEventQuery(m->ev_block.back()) == hipSuccess) m->pending_in = false;
+      else quiet = false;
+    }
+    if (m->pending_out) {
+      if (hipEventQuery(m->ev_out_done) == hipSuccess) m->pending_out = false;
+      else quiet = false;
+    }
+  }
+  (void)hipGetLastError();
+  return quiet;
+}
+
 template <typename T>
 T* dev_tensor(ctn_ctx* c, Model* m, int ti) {
   return reinterpret_cast<T*>(static_cast<char*>(c->cfg.arena_dev) + m->arena_off + m->lay.offset[ti]);
@@ -244,23 +358,34 @@ extern "C" {
 
 int ctn_create(const ctn_config* cfg, ctn_ctx** out) {
   if (!cfg || !out) return CTN_E_INVAL;
-  if (!cfg->arena_dev || !cfg->workspace_dev || !cfg->stream_compute || !cfg->stream_h2d || !cfg->stream_d2h)
-    return CTN_E_INVAL;
+  if (!cfg->arena_dev || !cfg->workspace_dev) return CTN_E_INVAL;
+  const bool own_streams = !cfg->stream_compute && !cfg->stream_h2d && !cfg->stream_d2h;
+  if (!own_streams && (!cfg->stream_compute || !cfg->stream_h2d || !cfg->stream_d2h)) return CTN_E_INVAL;
+  if (cfg->copy_cus < 0 || cfg->copy_cus > 64 || (cfg->copy_cus > 0 && cfg->copy_cus < 8)) return CTN_E_INVAL;
   if (reinterpret_cast<uintptr_t>(cfg->arena_dev) % kAlign || reinterpret_cast<uintptr_t>(cfg->workspace_dev) % kAlign)
     return CTN_E_INVAL;
   if (cfg->hbm_budget_bytes == 0 || cfg->arena_bytes == 0) return CTN_E_INVAL;
-  if (cfg->transfer_mode != CTN_XFER_DMA && cfg->transfer_mode != CTN_XFER_KERNEL) return CTN_E_INVAL;
-  if (cfg->stream_h2d == cfg->stream_compute || cfg->stream_d2h == cfg->stream_compute ||
-      cfg->stream_h2d == cfg->stream_d2h)
+  if (cfg->transfer_mode < CTN_XFER_DMA || cfg->transfer_mode > CTN_XFER_AUTO) return CTN_E_INVAL;
+  if (!own_streams && (cfg->stream_h2d == cfg->stream_compute || cfg->stream_d2h == cfg->stream_compute ||
+                       cfg->stream_h2d == cfg->stream_d2h))
     return CTN_E_INVAL;
   int n_dev = 0;
   if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev < 1) return CTN_E_HIP;   // no silent fallback
   ctn_ctx* c = new (std::nothrow) ctn_ctx();
   if (!c) return CTN_E_NOMEM;
   c->cfg = *cfg;
-  c->s_compute = static_cast<hipStream_t>(cfg->stream_compute);
-  c->s_h2d = static_cast<hipStream_t>(cfg->stream_h2d);
-  c->s_d2h = static_cast<hipStream_t>(cfg->stream_d2h);
+  if (own_streams) {
+    int rc = create_partitioned_streams(c, cfg->copy_cus ? cfg->copy_cus : kDefaultCopyCus);
+    if (rc) {
+      g_last_hip = c->last_hip;
+      delete c;
+      return rc;
+    }
+  } else {
+    c->s_compute = static_cast<hipStream_t>(cfg->stream_compute);
+    c->s_h2d = static_cast<hipStream_t>(cfg->stream_h2d);
+    c->s_d2h = static_cast<hipStream_t>(cfg->stream_d2h);
+  }
   c->res = Residency(cfg->hbm_budget_bytes);
   c->arena.reset(cfg->arena_bytes / kAlign * kAlign);
   c->stats.budget_bytes = cfg->hbm_budget_bytes;
@@ -273,6 +398,7 @@ int ctn_sync(ctn_ctx* c) {
   CTN_HIP(c, hipStreamSynchronize(c->s_h2d));
   CTN_HIP(c, hipStreamSynchronize(c->s_d2h));
   CTN_HIP(c, hipStreamSynchronize(c->s_compute));
+  if (c->s_wide) CTN_HIP(c, hipStreamSynchronize(c->s_wide));
   for (auto& m : c->models) m->pending_in = m->pending_out = false;
   c->pending.clear();
   return CTN_OK;
@@ -286,6 +412,11 @@ int ctn_destroy(ctn_ctx* c) {
     for (hipEvent_t e : {m->ev_in_start, m->ev_out_start, m->ev_out_done, m->ev_last_use})
       if (e) (void)hipEventDestroy(e);
   }
+  if (c->own_streams) {
+    for (hipStream_t st : {c->s_compute, c->s_h2d, c->s_d2h, c->s_wide})
+      if (st) (void)hipStreamDestroy(st);
+    if (c->ev_compute_done) (void)hipEventDestroy(c->ev_compute_done);
+  }
   delete c;
   return rc;
 }
@@ -296,6 +427,7 @@ int ctn_host_alloc(uint64_t nbytes, void** out) {
   hipError_t e = hipHostMalloc(&p, nbytes, hipHostMallocMapped | hipHostMallocPortable);
   if (e != hipSuccess) {
     (void)hipGetLastError();
+    g_last_hip = (int)e;
     return e == hipErrorOutOfMemory ? CTN_E_NOMEM : CTN_E_HIP;
   }
   *out = p;
@@ -341,6 +473,24 @@ int ctn_register_model(ctn_ctx* c, const ctn_model_desc* desc, const ctn_param* 
     }
     m->host_dev.push_back(dp);
   }
+  m->runs.assign(L.n_blocks, {});
+  for (int b = 0; b < L.n_blocks; ++b)
+    for (int ti : L.block_tensors[b]) {
+      auto& rs = m->runs[b];
+      if (!rs.empty()) {
+        Model::Run& r = rs.back();
+        const bool host_adjacent = static_cast<char*>(m->host[r.first]) + r.bytes == m->host[ti];
+        const bool arena_adjacent = L.offset[r.first] + r.bytes == L.offset[ti];
+        if (host_adjacent && arena_adjacent) {
+          r.bytes += L.nbytes[ti];
+          continue;
+        }
+      }
+      rs.push_back({ti, L.nbytes[ti]});
+    }
+  size_t n_runs = 0;
+  for (auto& rs : m->runs) n_runs += rs.size();
+  m->fragmented = n_runs > 4 * static_cast<size_t>(L.n_blocks);
   m->ev_block.resize(L.n_blocks);
   for (auto& e : m->ev_block) CTN_HIP(c, hipEventCreate(&e));
   CTN_HIP(c, hipEventCreate(&m->ev_in_start));
@@ -355,15 +505,20 @@ int ctn_register_model(ctn_ctx* c, const ctn_model_desc* desc, const ctn_param* 
 
 int ctn_swap_in(ctn_ctx* c, ctn_model mi) {
   if (!get_model(c, mi)) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
-  return ensure_resident(c, mi);
+  const int rc = ensure_resident(c, mi);
+  const int rc2 = flush_deferred(c);
+  return rc ? rc : rc2;
 }
 
 int ctn_swap_out(ctn_ctx* c, ctn_model mi) {
   Model* m = get_model(c, mi);
   if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
   std::vector<int> victims;
-  if (m->resident) victims.push_back(mi);
-  int rc = do_swap_out(c, mi);
+  if (m->resident) {
+    victims.push_back(mi);
+    evict_logical(c, mi);
+  }
+  int rc = flush_deferred(c);
   if (rc) return rc;
   c->stats.resident_bytes = c->res.resident_bytes();
   log_event(c, 2, mi, victims);
@@ -395,8 +550,8 @@ uint64_t ctn_arena_bytes(const ctn_model_desc* desc) {
   return make_layout(*desc).arena_bytes;
 }
 
-int ctn_infer(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int32_t batch, int32_t seq, void* logits_out,
-              int32_t out_is_device) {
+static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int32_t batch, int32_t seq,
+                         void* logits_out, int32_t out_is_device, float** logits_dev, uint64_t* logits_bytes) {
   Model* m = get_model(c, mi);
   if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
   if (!ids_host || !logits_out) return CTN_E_INVAL;
@@ -415,7 +570,12 @@ int ctn_infer(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int32_t batch, 
   if (rc) return rc;
   c->stats.n_infer += 1;
 
+  // With library-owned streams the masked compute stream keeps the forward pass
+  // off the copy kernels' compute units; when nothing is moving, the unmasked
+  // stream gives it the whole chip.  Both orders of use are chained by an event.
   hipStream_t s = c->s_compute;
+  if (c->s_wide && link_quiet(c)) s = c->s_wide;
+  if (c->last_compute && c->last_compute != s) CTN_HIP(c, hipStreamWaitEvent(s, c->ev_compute_done, 0));
   const int h = d.hidden, hl = L.hl(), fl = L.fl(), vl = L.vl();
   CTN_HIP(c, hipMemcpyAsync(act.ids, ids_host, 4ull * M, hipMemcpyHostToDevice, s));
   float* logits = out_is_device ? static_cast<float*>(logits_out) : act.logits;
@@ -431,8 +591,10 @@ int ctn_infer(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int32_t batch, 
     if (c->cfg.pipeline) CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block[1 + l], 0));
     auto T = [&](int w) { return dev_tensor<_Float16>(c, m, L.layer_tensor(l, w)); };
     CTN_HIP(c, launch_layernorm(act.x, T(LN1_W), T(LN1_B), act.a, M, h, s));
-    // q | k | v weights and biases are adjacent in the arena: one product
-    CTN_HIP(c, launch_gemm(act.a, T(Q_W), T(Q_B), act.qkv, M, 3 * hl, h, CTN_EPI_BIAS_F16, s));
+    // q | k | v: three column-parallel projections of the same input in one launch
+    const _Float16* const wqkv[3] = {T(Q_W), T(K_W), T(V_W)};
+    const _Float16* const bqkv[3] = {T(Q_B), T(K_B), T(V_B)};
+    CTN_HIP(c, launch_gemm3(act.a, wqkv, bqkv, act.qkv, M, hl, h, CTN_EPI_BIAS_F16, s));
     CTN_HIP(c, launch_attention(act.qkv, act.attn, batch, seq, L.local_heads(), L.head_dim(), s));
     // row parallel: this rank's partial sum joins the residual stream (the
     // cross-rank reduction is the identity on one GPU), bias added once
@@ -446,8 +608,28 @@ int ctn_infer(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int32_t batch, 
   CTN_HIP(c, launch_gemm(act.a, tok, nullptr, logits, M, vl, h, CTN_EPI_F32, s));   // tied head, vocabulary slice
   CTN_HIP(c, hipEventRecord(m->ev_last_use, s));
   m->used_since_load = true;
+  if (c->s_wide) {
+    CTN_HIP(c, hipEventRecord(c->ev_compute_done, s));
+    c->last_compute = s;
+    // whoever synchronises the primary compute stream also waits for this inference
+    if (s != c->s_compute) CTN_HIP(c, hipStreamWaitEvent(c->s_compute, c->ev_compute_done, 0));
+  }
+  *logits_dev = logits;
+  *logits_bytes = 4ull * M * vl;
+  return CTN_OK;
+}
+
+int ctn_infer(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int32_t batch, int32_t seq, void* logits_out,
+              int32_t out_is_device) {
+  float* logits = nullptr;
+  uint64_t nbytes = 0;
+  const int rc = infer_enqueue(c, mi, ids_host, batch, seq, logits_out, out_is_device, &logits, &nbytes);
+  // the victims' offloads go out after the load and the forward pass are in their queues
+  const int rc2 = c ? flush_deferred(c) : CTN_OK;
+  if (rc || rc2) return rc ? rc : rc2;
   if (!out_is_device) {
-    CTN_HIP(c, hipMemcpyAsync(logits_out, logits, 4ull * M * vl, hipMemcpyDeviceToHost, s));
+    hipStream_t s = c->last_compute ? c->last_compute : c->s_compute;
+    CTN_HIP(c, hipMemcpyAsync(logits_out, logits, nbytes, hipMemcpyDeviceToHost, s));
     CTN_HIP(c, hipStreamSynchronize(s));
   }
   return CTN_OK;
@@ -513,9 +695,17 @@ int ctn_debug_read_param(ctn_ctx* c, ctn_model mi, int32_t index, void* dst, uin
   return CTN_OK;
 }
 
+int ctn_get_streams(ctn_ctx* c, void** compute, void** h2d, void** d2h) {
+  if (!c) return CTN_E_INVAL;
+  if (compute) *compute = c->s_compute;
+  if (h2d) *h2d = c->s_h2d;
+  if (d2h) *d2h = c->s_d2h;
+  return CTN_OK;
+}
+
 int ctn_set_mode(ctn_ctx* c, int32_t transfer_mode, int32_t pipeline, int32_t copy_blocks) {
   if (!c) return CTN_E_INVAL;
-  if (transfer_mode != CTN_XFER_DMA && transfer_mode != CTN_XFER_KERNEL) return CTN_E_INVAL;
+  if (transfer_mode < CTN_XFER_DMA || transfer_mode > CTN_XFER_AUTO) return CTN_E_INVAL;
   if (copy_blocks < 0 || copy_blocks > 4096) return CTN_E_INVAL;
   c->cfg.transfer_mode = transfer_mode;
   c->cfg.pipeline = pipeline ? 1 : 0;
@@ -523,7 +713,7 @@ int ctn_set_mode(ctn_ctx* c, int32_t transfer_mode, int32_t pipeline, int32_t co
   return CTN_OK;
 }
 
-int ctn_last_hip_error(ctn_ctx* c) { return c ? c->last_hip : 0; }
+int ctn_last_hip_error(ctn_ctx* c) { return c ? c->last_hip : g_last_hip; }
 
 const char* ctn_strerror(int code) {
   switch (code) {
@@ -580,7 +770,7 @@ int ctn_op_copy(void* dst, const void* src, uint64_t nbytes, int32_t blocks, voi
   t.n = 1;
   t.seg[0] = {src, dst, nbytes / 16};
   if (!copy_table_finish(t)) return CTN_E_INVAL;
-  return op_rc(launch_copy_table(t, blocks, static_cast<hipStream_t>(stream)));
+  return op_rc(launch_copy_table(t, blocks, static_cast<hipStream_t>(stream), kCopyOther));
 }
 
 int ctn_op_dma(void* dst, const void* src, uint64_t nbytes, void* stream) {

@@ -11,10 +11,10 @@ class Rig:
     """A context with its arena, workspace, streams and pinned host pool."""
 
     def __init__(self, descs, budget=None, max_tokens=64, arena_bytes=None, mode=P.XFER_KERNEL,
-                 pipeline=True, host_bytes=None):
+                 pipeline=True, host_bytes=None, torch_streams=False):
         self.dev = torch.device("cuda:0")
         torch.cuda.set_device(0)
-        self.s_compute, self.s_h2d, self.s_d2h = (torch.cuda.Stream() for _ in range(3))
+        streams = [torch.cuda.Stream() for _ in range(3)] if torch_streams else [None] * 3
         need = [P.arena_bytes(d) for d in descs]
         arena_bytes = arena_bytes or sum(need)
         budget = budget or sum(shard_bytes(d) for d in descs)
@@ -22,8 +22,7 @@ class Rig:
         self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device=self.dev)
         self.workspace = torch.empty(ws, dtype=torch.uint8, device=self.dev)
         torch.cuda.synchronize()
-        self.ctx = P.Context(budget, self.arena, self.workspace, self.s_compute, self.s_h2d, self.s_d2h,
-                             transfer_mode=mode, pipeline=pipeline)
+        self.ctx = P.Context(budget, self.arena, self.workspace, *streams, transfer_mode=mode, pipeline=pipeline)
         host_bytes = host_bytes or sum(shard_bytes(d) + 256 * len(param_list(d)) for d in descs) + 4096
         self.pool = P.HostPool(host_bytes)
         self.descs = list(descs)

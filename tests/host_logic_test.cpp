@@ -1,0 +1,90 @@
+// CPU test of the host-only bookkeeping (no HIP): the arena range allocator against a
+// brute-force byte map, and the residency policy's budget invariant.
+#include <cassert>
+#include <cstdio>
+#include <algorithm>
+#include <cstdlib>
+#include <random>
+#include <vector>
+
+#include "residency.hpp"
+
+using ctn::RangeAllocator;
+
+static bool overlaps(uint64_t a, uint64_t al, uint64_t b, uint64_t bl) { return a < b + bl && b < a + al; }
+
+int main() {
+  std::mt19937_64 rng(12345);
+  for (int round = 0; round < 300; ++round) {
+    const uint64_t total = 64 + rng() % 200;
+    RangeAllocator ra(total);
+    std::vector<int> map(total, 0);   // 0 free, 1 allocated
+    struct Blk { uint64_t off, len; };
+    std::vector<Blk> live;
+    std::vector<RangeAllocator::Range> busy;   // recently released, "still being offloaded"
+    for (int step = 0; step < 200; ++step) {
+      if (live.empty() || rng() % 3) {
+        const uint64_t len = 1 + rng() % 40;
+        // brute force: does any free placement exist, and one that avoids `busy`?
+        bool any = false, clean = false;
+        for (uint64_t o = 0; o + len <= total; ++o) {
+          bool free_here = true;
+          for (uint64_t k = o; k < o + len; ++k) free_here &= map[k] == 0;
+          if (!free_here) continue;
+          any = true;
+          bool ok = true;
+          for (auto& b : busy) ok &= !overlaps(o, len, b.off, b.len);
+          clean |= ok;
+        }
+        const bool used_avoiding = rng() % 2;
+        const uint64_t off = used_avoiding ? ra.alloc_avoiding(len, busy) : (busy.clear(), ra.alloc(len));
+        if (!any) { assert(off == UINT64_MAX); continue; }
+        assert(off != UINT64_MAX && off + len <= total);
+        for (uint64_t k = off; k < off + len; ++k) { assert(map[k] == 0); map[k] = 1; }
+        if (clean && !busy.empty())
+          for (auto& b : busy) assert(!overlaps(off, len, b.off, b.len));
+        if (!clean && used_avoiding && !busy.empty()) {
+          // no clean placement: the one chosen must wait on the earliest-finishing set possible
+          auto cost = [&](uint64_t o) {
+            int c = -1;
+            for (size_t k = 0; k < busy.size(); ++k) if (overlaps(o, len, busy[k].off, busy[k].len)) c = (int)k;
+            return c;
+          };
+          // brute force over every free placement that was available before this allocation
+          int best = 1 << 30;
+          for (uint64_t o = 0; o + len <= total; ++o) {
+            bool free_here = true;
+            for (uint64_t k = o; k < o + len; ++k) free_here &= (map[k] == 0) || (k >= off && k < off + len);
+            if (free_here) best = std::min(best, cost(o));
+          }
+          assert(cost(off) == best);
+        }
+        live.push_back({off, len});
+      } else {
+        const size_t i = rng() % live.size();
+        for (uint64_t k = live[i].off; k < live[i].off + live[i].len; ++k) map[k] = 0;
+        ra.release(live[i].off, live[i].len);
+        busy.push_back({live[i].off, live[i].len});
+        if (busy.size() > 2) busy.erase(busy.begin());
+        live.erase(live.begin() + i);
+      }
+    }
+    for (auto& b : live) ra.release(b.off, b.len);
+    assert(ra.largest_hole() == total);          // everything coalesced back into one hole
+  }
+  // residency: budget never exceeded, oldest() is the least recently used
+  ctn::Residency r(100);
+  for (int i = 0; i < 5; ++i) r.add_model(30 + i);
+  std::vector<int> order;
+  for (int step = 0; step < 1000; ++step) {
+    const int m = rng() % 5;
+    if (r.resident(m)) { r.touch(m); }
+    else {
+      while (r.over_budget_with(m)) { int v = r.oldest(m); assert(v >= 0 && v != m); r.mark_evicted(v); }
+      r.mark_resident(m);
+    }
+    assert(r.resident_bytes() <= 100 && r.peak_bytes() <= 100);
+  }
+  std::puts("host logic ok");
+  return 0;
+}

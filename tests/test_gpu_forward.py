@@ -40,15 +40,16 @@ TINY = [
 ]
 
 
+@pytest.mark.parametrize("torch_streams", [False, True])
 @pytest.mark.parametrize("desc,batch,seq", TINY)
-def test_small_shards_every_mode(desc, batch, seq):
-    rig = Rig([desc], max_tokens=batch * seq)
+def test_small_shards_every_mode(desc, batch, seq, torch_streams):
+    rig = Rig([desc], max_tokens=batch * seq, torch_streams=torch_streams)
     try:
         m = rig.add(desc, seed=77)
         ids = token_ids(9, batch, seq, desc.vocab)
         want = oracle_logits(rig, m, desc, ids)
         outs = []
-        for mode in (P.XFER_KERNEL, P.XFER_DMA):
+        for mode in (P.XFER_KERNEL, P.XFER_DMA, P.XFER_AUTO):
             for pipe in (True, False):
                 rig.ctx.set_mode(mode, pipe)
                 rig.arena.fill_(0x7E)                 # NaN pattern: reading a block before it lands shows up
@@ -64,7 +65,7 @@ def test_small_shards_every_mode(desc, batch, seq):
         for o in outs[1:]:
             assert np.array_equal(o, outs[0])
         st = rig.ctx.stats()
-        assert st["n_miss"] == 4 and st["n_hit"] == 4 and st["n_infer"] == 8
+        assert st["n_miss"] == 6 and st["n_hit"] == 6 and st["n_infer"] == 12
     finally:
         rig.close()
 
@@ -97,7 +98,7 @@ def test_infer_under_eviction_pressure_matches_oracle():
     """Three models, room for two: every request may trigger swap-out + swap-in."""
     desc = ShardDesc(2, 256, 1024, 4, vocab=1000, max_pos=64)
     size = shard_bytes(desc)
-    rig = Rig([desc] * 3, budget=2 * size, arena_bytes=2 * P.arena_bytes(desc), max_tokens=16)
+    rig = Rig([desc] * 3, budget=2 * size, arena_bytes=3 * P.arena_bytes(desc), max_tokens=16, mode=P.XFER_AUTO)
     try:
         ms = [rig.add(desc, seed=40 + i) for i in range(3)]
         orig = [[t.copy() for t in rig.tensors[m]] for m in ms]

@@ -24,7 +24,7 @@ def check_device_copy(rig, m, desc):
         assert np.array_equal(as_bytes(got), img.tensors[i]), f"tensor {i}"
 
 
-@pytest.mark.parametrize("mode", [P.XFER_KERNEL, P.XFER_DMA])
+@pytest.mark.parametrize("mode", [P.XFER_KERNEL, P.XFER_DMA, P.XFER_AUTO])
 @pytest.mark.parametrize("desc", [SMALL, SMALL_TP])
 def test_round_trip_scribble_and_poison(mode, desc):
     rig = Rig([desc], mode=mode)
@@ -85,7 +85,7 @@ def test_many_cycles_any_order_keeps_host_bits():
             if rng.random() < 0.3:
                 rig.ctx.swap_out(m)
             else:
-                rig.ctx.set_mode(int(rng.integers(0, 2)), True)
+                rig.ctx.set_mode(int(rng.integers(0, 3)), True)
                 rig.ctx.swap_in(m)
                 if rng.random() < 0.5:
                     rig.ctx.wait(m)
