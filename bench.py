@@ -34,9 +34,10 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
 PCIE5_X16_NOMINAL_GBPS = 64.0
-# HBM traffic of one h2d copy launch (201,404,416 B layer block) from the rocprofv3 --pmc runs
-# summarised in profiles/copy_table_kernel_opt6.7b_tp2_pmc.md; None until measured.
-COPY_KERNEL_TRAFFIC_BYTES = None
+# Memory traffic of one h2d copy launch of a 201,404,416 B layer block, from the two rocprofv3 --pmc
+# passes summarised in profiles/counters_opt6.7b_tp2_pmc.md: FETCH_SIZE 98,373 KiB x 2.0 (calibration
+# factor of that counter) of loads from the host mapping + WRITE_SIZE 196,684 KiB x 1.0 of HBM stores.
+COPY_KERNEL_TRAFFIC = {"opt6.7b_tp2": {"fetch_bytes": 98373 * 2 * 1024, "write_bytes": 196684 * 1024}}
 
 
 def log(*a):
@@ -74,6 +75,7 @@ def measure_link_peak(torch, P, B, pool_bytes=1 << 30, reps=10):
 
 
 MODES = {"dma": 0, "kernel": 1, "auto": 2}
+GAP = 4096   # bytes between host tensors in the "separate" layout
 
 
 def measure_bidir_peak(torch, P, B, ctx, nbytes=1 << 29, reps=5):
@@ -123,19 +125,49 @@ def run_swap(args):
     ctx = P.Context(nbytes, arena, ws, transfer_mode=P.XFER_KERNEL, pipeline=True,
                     copy_blocks=args.copy_blocks, copy_cus=args.copy_cus)
     s_c = ctx.stream_compute
-    pool = P.HostPool(2 * (nbytes + 256 * len(param_list(desc))) + 4096)
+    # Host parameter store.  "separate": every tensor is its own pinned region with a gap before
+    # the next one, as individually allocated parameter tensors are (the paper's per-tensor
+    # messages, Section 5.1).  "packed": the tensors of a shard lie back to back in one slab.
+    n_t = len(param_list(desc))
+    pool = P.HostPool(4 * nbytes + 2 * n_t * (256 + GAP) + 2 * n_t * 256 + 8192)
     t0 = time.time()
-    tensors = [fill_shard(desc, cfg["wseed"] + k, alloc=lambda s: pool.take(s), threads=16) for k in range(2)]
-    models = [ctx.register_model(desc, t) for t in tensors]
+    sep = [fill_shard(desc, cfg["wseed"] + k, alloc=lambda s: pool.take(s, gap=GAP), threads=16) for k in range(2)]
+    packed = []
+    for k in range(2):
+        packed.append([pool.take(t.shape) for t in sep[k]])
+        for dst, src in zip(packed[k], sep[k]):
+            dst[...] = src
+    primary, other = (sep, packed) if args.host_layout == "separate" else (packed, sep)
+    tensors = primary
+    models = [ctx.register_model(desc, t) for t in primary]
+    models_other = [ctx.register_model(desc, t) for t in other]
     ids = [token_ids(cfg["idseed"] + k, batch, seq, desc.vocab) for k in range(2)]
     log(f"[bench] weights generated and registered in {time.time()-t0:.1f}s")
 
     bidir = measure_bidir_peak(torch, P, B, ctx)
     log(f"[bench] both directions at once (DMA): h2d {bidir['h2d']:.2f} GB/s, d2h {bidir['d2h']:.2f} GB/s")
 
-    def request(k):
-        ctx.infer(models[k], ids[k], out=logits)
+    def request(k, pair=None):
+        ctx.infer((pair or models)[k], ids[k], out=logits)
         s_c.synchronize()
+
+    def alternate(pair, steps, warmup):
+        """Alternating blocking requests to the two models of `pair`; returns wall seconds and latencies."""
+        for m in models + models_other:
+            ctx.swap_out(m)
+        ctx.sync()
+        for i in range(warmup):
+            request(i % 2, pair)
+        torch.cuda.synchronize()
+        lat = []
+        t_start = time.perf_counter()
+        for i in range(steps):
+            t = time.perf_counter()
+            request((warmup + i) % 2, pair)
+            lat.append((time.perf_counter() - t) * 1e3)
+        ctx.sync()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t_start, lat
 
     # ---- side measurements (outside the timed region) ---------------------------
     side = {}
@@ -149,6 +181,7 @@ def run_swap(args):
             ctx.swap_out(models[0]); ctx.wait(models[0])
             i_ms, o_ms, blocks = ctx.last_swap_ms(models[0])
             ins.append(i_ms); outs.append(o_ms)
+            side.setdefault(f"blocks_{key}", []).append(list(blocks))
         side[f"swap_in_ms_{key}"] = median(ins)
         side[f"swap_out_ms_{key}"] = median(outs)
     ctx.set_mode(P.XFER_KERNEL, True, args.copy_blocks)
@@ -174,37 +207,50 @@ def run_swap(args):
     ctx.swap_out(models[0]); ctx.wait(models[0])
     ctx.sync()
 
+    # the same alternation on the other host layout, for the report
+    ctx.set_mode(MODES[args.transfer], True, args.copy_blocks)
+    w_other, lat_other = alternate(models_other, 4, 2)
+    side["other_layout_ms_per_step"] = w_other / 4 * 1e3
+
     # ---- timed region -------------------------------------------------------------
-    for i in range(args.warmup):
-        request(i % 2)
-    torch.cuda.synchronize()
-    lat, in_ms, out_ms = [], [], []
-    t_start = time.perf_counter()
-    for i in range(args.steps):
-        t = time.perf_counter()
-        request((args.warmup + i) % 2)
-        lat.append((time.perf_counter() - t) * 1e3)
-    ctx.sync()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t_start
-    # per-launch durations of the h2d copy kernel, from the HIP events the library records on
-    # the h2d stream after every transfer block (last step of each model)
-    launch_ms, launch_bytes = [], []
+    in_ms, out_ms = [], []
+    wall, lat = alternate(models, args.steps, args.warmup)
+    # per-launch durations of the h2d transfers of the timed region, from the HIP events the
+    # library records on the h2d stream after every transfer block (last load of each model)
+    specs = param_list(desc)
+    sizes = [2 * int(np.prod(sh)) for _, sh, _ in specs]
+    b0 = sizes[0] + sizes[1] + sizes[-2] + sizes[-1]        # block 0: embeddings + final LayerNorm
+    per_layer = sum(sizes[2:18])                            # then one equal block per layer
+    block_bytes = [b0] + [per_layer] * desc.layers
+    timed_blocks = []
     for k in range(2):
         i_ms, o_ms, blocks = ctx.last_swap_ms(models[k])
         in_ms.append(i_ms)
         out_ms.append(o_ms)
-        d = np.diff([0.0] + list(blocks))
-        launch_ms += list(d)
-    # bytes per block: block 0 = embeddings + final LN, then equal layer blocks
-    specs = param_list(desc)
-    sizes = [2 * int(np.prod(s)) for _, s, _ in specs]
-    b0 = sizes[0] + sizes[1] + sizes[-2] + sizes[-1]
-    per_layer = sum(sizes[2:18])
-    launch_bytes = ([b0] + [per_layer] * desc.layers) * 2
+        timed_blocks.append(list(blocks))
+    loads_by_kernel = args.transfer == "kernel" or (args.transfer == "auto" and args.host_layout == "separate")
+    if loads_by_kernel:
+        roof_blocks, roof_where = timed_blocks, "timed region (last load of each model)"
+    else:
+        roof_blocks, roof_where = side["blocks_kernel"], "kernel-mode loads of this run outside the timed region " \
+                                                          "(the timed region's loads went through the DMA engines)"
+    launch_ms = [d for blocks in roof_blocks for d in np.diff([0.0] + blocks)]
     avg_launch_ms = float(np.mean(launch_ms))
-    avg_launch_bytes = float(np.mean(launch_bytes))
+    avg_launch_bytes = float(np.mean(block_bytes))
     achieved = avg_launch_bytes / avg_launch_ms / 1e6
+
+    # the largest product of a layer (fc1: [M, h] x [f/t, h]^T) alone, for the MFMA roofline
+    gM, gN, gK = M, desc.local_ffn, desc.hidden
+    ga = torch.randn(gM, gK, device="cuda").half()
+    gw = torch.randn(gN, gK, device="cuda").half()
+    gb = torch.zeros(gN, device="cuda").half()
+    go = torch.empty(gM, gN, device="cuda").half()
+    sg = torch.cuda.Stream()
+    B.op_gemm(ga, gw, gb, go, gM, gN, gK, P.EPI_BIAS_RELU_F16, sg)
+    reps = 20
+    gms = ev_time(torch, sg, lambda: [B.op_gemm(ga, gw, gb, go, gM, gN, gK, P.EPI_BIAS_RELU_F16, sg)
+                                      for _ in range(reps)]) / reps
+    gemm_tflops = 2.0 * gM * gN * gK / gms / 1e9
 
     value = args.steps * nbytes / wall / 1e9
     flop = forward_flop(desc, batch, seq)
@@ -214,8 +260,8 @@ def run_swap(args):
         "ms_per_step": round(wall / args.steps * 1e3, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{args.config} shard x2 models, budget 1 resident, alternating blocking requests, "
-                               f"batch {batch} x seq {seq}", "shard_bytes": nbytes, "tensors": len(specs),
-                   "transfer": args.transfer, "pipeline": "per-layer events",
+                               f"batch {batch} x seq {seq}", "shard_bytes": nbytes, "tensors": n_t,
+                   "transfer": args.transfer, "host_layout": args.host_layout, "pipeline": "per-layer events",
                    "copy_blocks": args.copy_blocks, "copy_cus": args.copy_cus},
         "swap_in_gbps_device_timeline": round(nbytes / median(in_ms) / 1e6, 3),
         "shard_load_latency_s": round(median(in_ms) / 1e3, 5),
@@ -242,11 +288,26 @@ def run_swap(args):
         "roofline": {
             "kernel": "copy_table_kernel<0> (host -> HBM, one launch per transfer block)",
             "bound": "host_link", "achieved": round(achieved, 3), "peak": round(link["h2d"], 3), "unit": "GB/s",
-            "frac": round(achieved / link["h2d"], 4), "traffic": COPY_KERNEL_TRAFFIC_BYTES,
+            "frac": round(achieved / link["h2d"], 4),
+            "traffic": sum(COPY_KERNEL_TRAFFIC[args.config].values()) if args.config in COPY_KERNEL_TRAFFIC else None,
+            "traffic_detail": dict(COPY_KERNEL_TRAFFIC.get(args.config, {}),
+                                   note="per layer-block launch: bytes loaded over the host link + bytes stored to HBM; "
+                                        "algorithmic = 201,404,416 each"),
             "peak_source": "measured: median 1 GiB hipMemcpyAsync pinned->HBM in this run "
                            f"(PCIe Gen5 x16 nominal {PCIE5_X16_NOMINAL_GBPS} GB/s; HBM peak {HBM_PEAK_GBPS} GB/s is not the bound)",
             "bytes_per_launch": avg_launch_bytes, "avg_launch_ms": round(avg_launch_ms, 4),
-            "launches_timed": len(launch_ms),
+            "launches_timed": len(launch_ms), "measured_over": roof_where,
+        },
+        "roofline_gemm": {
+            "kernel": f"gemm_nt_kernel<128,128,64,64> fc1 shape M={gM} N={gN} K={gK}, bias+ReLU epilogue",
+            "bound": "mfma", "achieved": round(gemm_tflops, 2), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(gemm_tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None,
+            "avg_launch_ms": round(gms, 4), "launches_timed": reps,
+        },
+        "other_host_layout": {
+            "layout": "packed" if args.host_layout == "separate" else "separate",
+            "ms_per_step": round(side["other_layout_ms_per_step"], 3),
+            "value_gbps": round(nbytes / side["other_layout_ms_per_step"] / 1e6, 3),
         },
     }
     if not args.no_cpu_baseline:
@@ -255,6 +316,42 @@ def run_swap(args):
     del tensors
     pool.close()
     print(json.dumps(result), flush=True)
+
+
+def run_counters(args):
+    """Short run for `rocprofv3 --pmc`: a plain device-to-device copy of known size (calibration of
+    FETCH_SIZE / WRITE_SIZE), then one kernel-mode swap-in, one resident forward, one swap-out."""
+    import torch
+    import paper_2306_13835_amd as P
+    from paper_2306_13835_amd import binding as B
+    from synth import CONFIGS, fill_shard, token_ids, shard_bytes, param_list
+    torch.cuda.set_device(0)
+    torch.zeros(1, device="cuda")
+    cfg = CONFIGS[args.config]
+    desc, batch, seq = cfg["desc"], cfg["batch"], cfg["seq"]
+    nbytes, M = shard_bytes(desc), batch * seq
+    arena = torch.empty(P.arena_bytes(desc), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(P.workspace_bytes(desc, M), dtype=torch.uint8, device="cuda")
+    logits = torch.empty(batch, seq, desc.vocab // desc.tp, dtype=torch.float32, device="cuda")
+    ctx = P.Context(nbytes, arena, ws, transfer_mode=P.XFER_KERNEL, pipeline=False)
+    pool = P.HostPool(nbytes + len(param_list(desc)) * (256 + GAP) + 8192)
+    tensors = fill_shard(desc, cfg["wseed"], alloc=lambda s: pool.take(s, gap=GAP), threads=16)
+    m = ctx.register_model(desc, tensors)
+    cal = 1 << 30
+    a = torch.zeros(cal, dtype=torch.uint8, device="cuda")
+    b = torch.empty(cal, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    B.op_copy(b, a, cal, 1024, ctx.stream_compute)           # copy_table_kernel<2>: reads and writes 2^30 B
+    ctx.stream_compute.synchronize()
+    ctx.swap_in(m); ctx.wait(m)                              # copy_table_kernel<0> x (layers + 1)
+    ctx.infer(m, token_ids(cfg["idseed"], batch, seq, desc.vocab), out=logits)
+    ctx.sync()
+    ctx.swap_out(m); ctx.wait(m)                             # copy_table_kernel<1> x (layers + 1)
+    ctx.close()
+    del tensors
+    pool.close()
+    print(json.dumps({"workload": "counters", "config": args.config, "calibration_copy_bytes": cal,
+                      "shard_bytes": nbytes}), flush=True)
 
 
 def cpu_baseline(tensors, ids, desc, nbytes):
@@ -288,11 +385,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", choices=["swap", "serve"], default="swap")
+    ap.add_argument("--workload", choices=["swap", "serve", "counters"], default="swap")
     ap.add_argument("--config", default="opt6.7b_tp2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--transfer", choices=["auto", "kernel", "dma"], default="auto",
                     help="transfer mode of the timed region")
+    ap.add_argument("--host-layout", choices=["separate", "packed"], default="separate",
+                    help="how the parameter tensors lie in pinned host memory")
     ap.add_argument("--copy-blocks", type=int, default=0, help="workgroups per copy kernel (0: library default)")
     ap.add_argument("--copy-cus", type=int, default=0, help="compute units reserved per transfer direction")
     args = ap.parse_args()
@@ -302,7 +401,9 @@ def main():
         sys.exit(2)
     import paper_2306_13835_amd as P
     P.lib()   # fails loudly when the HIP library is not built
-    if args.workload == "serve":
+    if args.workload == "counters":
+        run_counters(args)
+    elif args.workload == "serve":
         from paper_2306_13835_amd.serve_bench import run_serve
         run_serve(args)
     else:

@@ -154,9 +154,11 @@ class HostPool:
         self.bytes = np.frombuffer(self._buf, dtype=np.uint8)
         self._cur = 0
 
-    def take(self, shape, dtype=np.float16, align: int = 256) -> np.ndarray:
+    def take(self, shape, dtype=np.float16, align: int = 256, gap: int = 0) -> np.ndarray:
+        """Next `align`-aligned array; `gap` bytes are skipped first, so that consecutive arrays
+        are not adjacent (as separately allocated tensors would not be)."""
         n = int(np.prod(shape)) * np.dtype(dtype).itemsize
-        lo = (self._cur + align - 1) // align * align
+        lo = (self._cur + gap + align - 1) // align * align
         if lo + n > self.nbytes:
             raise MemoryError("HostPool exhausted")
         self._cur = lo + n

@@ -41,7 +41,7 @@ struct Model {
   bool resident = false;
   uint64_t arena_off = 0;
   uint64_t out_off = 0;              // range the current / last offload reads from
-  bool fragmented = true;            // many runs per block: the copy kernel beats per-run DMA when the link is quiet
+  bool fragmented = true;            // more than 4 runs per block on average
   bool offload_enqueued = true;      // false between the eviction decision and the offload's enqueue
   std::vector<hipEvent_t> ev_block;  // recorded on the h2d stream after each block
   hipEvent_t ev_in_start = nullptr, ev_out_start = nullptr, ev_out_done = nullptr, ev_last_use = nullptr;
@@ -258,10 +258,11 @@ int ensure_resident(ctn_ctx* c, int mi) {
   // The load reads the host tensors this model's own offload may still be writing.
   if (m->pending_out) CTN_HIP(c, hipStreamWaitEvent(c->s_h2d, m->ev_out_done, 0));
   char* arena = static_cast<char*>(c->cfg.arena_dev) + off;
-  // Kernel-issued host reads collapse when an offload is writing to the host
-  // at the same time; the DMA engines' reads do not.
+  // AUTO: a host list in many pieces is gathered by one kernel launch per block
+  // (no per-piece cost); a packed one goes through the DMA engines, whose host
+  // reads keep their rate when an offload is writing to the host at the same time.
   const bool load_by_kernel = c->cfg.transfer_mode == CTN_XFER_KERNEL ||
-                              (c->cfg.transfer_mode == CTN_XFER_AUTO && c->pending.empty() && m->fragmented);
+                              (c->cfg.transfer_mode == CTN_XFER_AUTO && m->fragmented);
   CTN_HIP(c, hipEventRecord(m->ev_in_start, c->s_h2d));
   for (int b = 0; b < L.n_blocks; ++b) {
     if (load_by_kernel) {
