@@ -388,6 +388,7 @@ def main():
     ap.add_argument("--workload", choices=["swap", "serve", "counters"], default="swap")
     ap.add_argument("--config", default="opt6.7b_tp2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--requests", type=int, default=0, help="serve workload: number of requests (0: all 2000)")
     ap.add_argument("--transfer", choices=["auto", "kernel", "dma"], default="auto",
                     help="transfer mode of the timed region")
     ap.add_argument("--host-layout", choices=["separate", "packed"], default="separate",

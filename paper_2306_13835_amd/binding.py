@@ -18,7 +18,7 @@ DECLARED_SYMBOLS = [
     "ctn_arena_bytes", "ctn_is_resident", "ctn_get_stats", "ctn_get_events", "ctn_last_swap_ms",
     "ctn_debug_read_param", "ctn_get_streams", "ctn_set_mode", "ctn_last_hip_error", "ctn_strerror",
     "ctn_residency_replay", "ctn_op_copy", "ctn_op_dma", "ctn_op_embed", "ctn_op_layernorm",
-    "ctn_op_gemm", "ctn_op_attention",
+    "ctn_op_gemm", "ctn_op_attention", "ctn_debug_gemm_tile",
 ]
 
 
@@ -103,6 +103,7 @@ def lib() -> C.CDLL:
         "ctn_op_layernorm": (C.c_int, [vp, vp, vp, vp, i32, i32, vp]),
         "ctn_op_gemm": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, vp]),
         "ctn_op_attention": (C.c_int, [vp, vp, i32, i32, i32, i32, vp]),
+        "ctn_debug_gemm_tile": (C.c_int, [i32]),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
@@ -328,3 +329,7 @@ def op_gemm(A, W, bias, out, M, N, K, epilogue, stream):
 def op_attention(qkv, out, batch, seq, heads, head_dim, stream):
     _op(lib().ctn_op_attention(_addr(qkv), _addr(out), batch, seq, heads, head_dim, stream.cuda_stream),
         "ctn_op_attention")
+
+
+def debug_gemm_tile(cfg: int):
+    _op(lib().ctn_debug_gemm_tile(cfg), "ctn_debug_gemm_tile")

@@ -28,9 +28,7 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BK = 64;          // K extent of one LDS stage
 constexpr int LDS_PAD = 8;      // halves of padding per LDS row (16 bytes)
-constexpr int LDS_ROW = BK + LDS_PAD;
 constexpr int kXcds = 8;
 
 // Workgroup id -> tile id such that XCD x (ids congruent to x mod 8) owns a
@@ -53,12 +51,17 @@ struct GemmArgs {
   int M, N, K, ldc, parts;
 };
 
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int BK, int WM, int WN, int EPI>
 __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
+  constexpr int LDS_ROW = BK + LDS_PAD;
+  constexpr int LPR = BK / 8;          // 16-byte lanes per tile row in the cooperative load
+  constexpr int RPP = 256 / LPR;       // tile rows covered by one pass of the 256 threads
+  static_assert(BK == 32 || BK == 64, "K extent of one LDS stage");
+  static_assert(BM % RPP == 0 && BN % RPP == 0, "cooperative load covers whole passes");
   static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts per workgroup");
   static_assert(WM % 32 == 0 && WN % 32 == 0 && BM % 32 == 0 && BN % 32 == 0, "32x32 MFMA tiles");
   constexpr int TM = WM / 32, TN = WN / 32;     // MFMA tiles per wavefront
-  constexpr int PA = BM / 32, PB = BN / 32;     // 32-row passes of the cooperative loads
+  constexpr int PA = BM / RPP, PB = BN / RPP;   // passes of the cooperative loads
 
   __shared__ __attribute__((aligned(16))) _Float16 As[2][BM][LDS_ROW];
   __shared__ __attribute__((aligned(16))) _Float16 Bs[2][BN][LDS_ROW];
@@ -77,7 +80,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave % (BM / WM)) * WM, wn0 = (wave / (BM / WM)) * WN;
-  const int lrow = tid >> 3, lcol = (tid & 7) * 8;   // cooperative load: 32 rows x 8 lanes x 16 B
+  const int lrow = tid / LPR, lcol = (tid % LPR) * 8;   // cooperative load: RPP rows x LPR lanes x 16 B
 
   float16v acc[TM][TN];
 #pragma unroll
@@ -92,22 +95,22 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
     const int kc = k0 + lcol;
 #pragma unroll
     for (int p = 0; p < PA; ++p) {
-      const int r = m0 + p * 32 + lrow;
+      const int r = m0 + p * RPP + lrow;
       ra[p] = u32x4{0u, 0u, 0u, 0u};
       if (r < M && kc < K) ra[p] = *reinterpret_cast<const u32x4*>(A + static_cast<int64_t>(r) * K + kc);
     }
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
-      const int r = n0 + p * 32 + lrow;
+      const int r = n0 + p * RPP + lrow;
       rb[p] = u32x4{0u, 0u, 0u, 0u};
       if (r < N && kc < K) rb[p] = *reinterpret_cast<const u32x4*>(W + static_cast<int64_t>(r) * K + kc);
     }
   };
   auto store_lds = [&](int buf) {
 #pragma unroll
-    for (int p = 0; p < PA; ++p) *reinterpret_cast<u32x4*>(&As[buf][p * 32 + lrow][lcol]) = ra[p];
+    for (int p = 0; p < PA; ++p) *reinterpret_cast<u32x4*>(&As[buf][p * RPP + lrow][lcol]) = ra[p];
 #pragma unroll
-    for (int p = 0; p < PB; ++p) *reinterpret_cast<u32x4*>(&Bs[buf][p * 32 + lrow][lcol]) = rb[p];
+    for (int p = 0; p < PB; ++p) *reinterpret_cast<u32x4*>(&Bs[buf][p * RPP + lrow][lcol]) = rb[p];
   };
 
   const int ksteps = (K + BK - 1) / BK;
@@ -171,11 +174,11 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
   }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int BK, int WM, int WN>
 hipError_t launch_tiles(const GemmArgs& g, int epi, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * g.parts;
   const dim3 grid(tiles), block(256);
-#define CTN_GEMM(E) hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, WM, WN, E>), grid, block, 0, s, g)
+#define CTN_GEMM(E) hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g)
   switch (epi) {
     case CTN_EPI_BIAS_F16: CTN_GEMM(CTN_EPI_BIAS_F16); break;
     case CTN_EPI_BIAS_RELU_F16: CTN_GEMM(CTN_EPI_BIAS_RELU_F16); break;
@@ -187,16 +190,175 @@ hipError_t launch_tiles(const GemmArgs& g, int epi, hipStream_t s) {
   return hipGetLastError();
 }
 
-}  // namespace
 
-static hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s) {
+// ---- M <= 64: weights streamed once from HBM ---------------------------------
+//
+// With a few dozen tokens the product is bound by reading W once (M flop per
+// weight byte is far below the machine balance).  What matters is the number
+// of bytes in flight, not the matrix cores: a workgroup of 16 wavefronts owns
+// 16 output features and ALL tokens; wavefront w takes the 32-wide K chunks
+// w, w+16, w+32, ... so that at any moment the 16 wavefronts read 1 KiB of
+// each of the 16 weight rows, four chunks ahead.  Fragments go from global
+// memory straight into v_mfma_f32_16x16x32_f16 operands (no LDS staging: no
+// operand is reused inside the workgroup).  The 16 partial tiles are summed
+// through LDS in a fixed order, so results do not depend on timing.
+typedef float float4v __attribute__((ext_vector_type(4)));
+constexpr int SK_WAVES = 16;
+
+// MT = 16-token tiles (M <= 16*MT), NT = 16-feature tiles per workgroup, UNROLL = K chunks in flight.
+// Every A fragment is used for NT products, so the L2 traffic for A is M/(16*NT) times that of W.
+template <int MT, int NT, int UNROLL, int EPI>
+__global__ __launch_bounds__(SK_WAVES * 64) void gemm_skinny_kernel(const GemmArgs g) {
+  constexpr int BN = 16 * NT;
+  __shared__ float part[SK_WAVES][MT * 16][BN + 1];
+  const int M = g.M, N = g.N, K = g.K;
+  const int tiles_n = (N + BN - 1) / BN;
+  const int part_id = blockIdx.x / tiles_n;
+  const int n0 = (blockIdx.x % tiles_n) * BN;
+  const _Float16* __restrict__ A = g.A;
+  const _Float16* __restrict__ W = part_id == 0 ? g.W[0] : (part_id == 1 ? g.W[1] : g.W[2]);
+  const _Float16* __restrict__ bias = part_id == 0 ? g.bias[0] : (part_id == 1 ? g.bias[1] : g.bias[2]);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r16 = lane & 15, kg = lane >> 4;          // operand row / column and 8-wide K group of this lane
+
+  float4v acc[MT][NT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[t][j] = float4v{0.f, 0.f, 0.f, 0.f};
+
+  const _Float16* wrow[NT];
+  bool n_ok[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int n_row = n0 + j * 16 + r16;
+    n_ok[j] = n_row < N;
+    wrow[j] = W + static_cast<int64_t>(n_ok[j] ? n_row : 0) * K;
+  }
+  const int chunks = (K + 31) / 32;
+  for (int c0 = wave; c0 < chunks; c0 += SK_WAVES * UNROLL) {
+    half8 wf[UNROLL][NT], af[UNROLL][MT];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int k = (c0 + u * SK_WAVES) * 32 + kg * 8;
+      const bool k_ok = k < K;                         // also false for chunks past the end
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        wf[u][j] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+        if (k_ok && n_ok[j]) wf[u][j] = *reinterpret_cast<const half8*>(wrow[j] + k);
+      }
+#pragma unroll
+      for (int t = 0; t < MT; ++t) {
+        const int m = t * 16 + r16;
+        af[u][t] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+        if (k_ok && m < M) af[u][t] = *reinterpret_cast<const half8*>(A + static_cast<int64_t>(m) * K + k);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          acc[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[u][t], wf[u][j], acc[t][j], 0, 0, 0);
+  }
+  // accumulator layout of a 16x16 tile: lane holds column (lane % 16), rows 4*(lane/16) + e
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) part[wave][t * 16 + 4 * kg + e][j * 16 + r16] = acc[t][j][e];
+  __syncthreads();
+  for (int idx = tid; idx < MT * 16 * BN; idx += SK_WAVES * 64) {
+    const int m = idx / BN, j = idx % BN, n = n0 + j;
+    if (m >= M || n >= N) continue;
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < SK_WAVES; ++w) v += part[w][m][j];      // fixed order: deterministic
+    if (EPI != CTN_EPI_F32) v += static_cast<float>(bias[n]);
+    const int64_t o = static_cast<int64_t>(m) * g.ldc + part_id * N + n;
+    if (EPI == CTN_EPI_BIAS_F16) {
+      static_cast<_Float16*>(g.out)[o] = static_cast<_Float16>(v);
+    } else if (EPI == CTN_EPI_BIAS_RELU_F16) {
+      static_cast<_Float16*>(g.out)[o] = static_cast<_Float16>(v > 0.f ? v : 0.f);
+    } else if (EPI == CTN_EPI_BIAS_RESID_F32) {
+      static_cast<float*>(g.out)[o] += v;
+    } else {
+      static_cast<float*>(g.out)[o] = v;
+    }
+  }
+}
+
+template <int MT, int NT, int UNROLL>
+hipError_t launch_skinny(const GemmArgs& g, int epi, hipStream_t s) {
+  const dim3 grid(((g.N + 16 * NT - 1) / (16 * NT)) * g.parts), block(SK_WAVES * 64);
+#define CTN_SK(E) hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, UNROLL, E>), grid, block, 0, s, g)
+  switch (epi) {
+    case CTN_EPI_BIAS_F16: CTN_SK(CTN_EPI_BIAS_F16); break;
+    case CTN_EPI_BIAS_RELU_F16: CTN_SK(CTN_EPI_BIAS_RELU_F16); break;
+    case CTN_EPI_BIAS_RESID_F32: CTN_SK(CTN_EPI_BIAS_RESID_F32); break;
+    case CTN_EPI_F32: CTN_SK(CTN_EPI_F32); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef CTN_SK
+  return hipGetLastError();
+}
+
+// variant 0: 16 features per workgroup (most workgroups); variant 1: 32 (half the A traffic)
+hipError_t launch_skinny_any(const GemmArgs& g, int epi, hipStream_t s, int variant) {
+  if (g.M <= 16) return variant ? launch_skinny<1, 2, 4>(g, epi, s) : launch_skinny<1, 1, 4>(g, epi, s);
+  if (g.M <= 32) return variant ? launch_skinny<2, 2, 2>(g, epi, s) : launch_skinny<2, 1, 4>(g, epi, s);
+  if (g.M <= 48) return variant ? launch_skinny<3, 2, 2>(g, epi, s) : launch_skinny<3, 1, 4>(g, epi, s);
+  return variant ? launch_skinny<4, 2, 2>(g, epi, s) : launch_skinny<4, 1, 4>(g, epi, s);
+}
+
+int g_force_tile = -1;   // test / tuning hook: tile configuration forced for every product
+
+hipError_t launch_config(int cfg, const GemmArgs& g, int epi, hipStream_t s) {
+  switch (cfg) {
+    case 0: return launch_tiles<128, 128, 64, 64, 64>(g, epi, s);
+    case 1: return launch_tiles<128, 64, 64, 64, 32>(g, epi, s);
+    case 2: return launch_tiles<256, 128, 32, 128, 64>(g, epi, s);
+    case 3: return launch_tiles<128, 256, 32, 64, 128>(g, epi, s);
+    case 4: return launch_tiles<256, 128, 64, 128, 64>(g, epi, s);
+    case 5: return launch_tiles<128, 128, 32, 64, 64>(g, epi, s);
+    case 6: return launch_tiles<64, 64, 64, 32, 32>(g, epi, s);
+    case 7: return launch_tiles<32, 128, 64, 32, 32>(g, epi, s);
+    case 8: return launch_tiles<256, 256, 32, 128, 128>(g, epi, s);
+    case 9: return g.M <= 64 ? launch_skinny_any(g, epi, s, 0) : hipErrorInvalidValue;
+    case 10: return g.M <= 64 ? launch_skinny_any(g, epi, s, 1) : hipErrorInvalidValue;
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   if (g.K <= 0 || g.K % 8 || g.parts < 1 || g.parts > 3) return hipErrorInvalidValue;
   for (int p = 0; p < g.parts; ++p)
     if (!g.W[p] || (epi != CTN_EPI_F32 && !g.bias[p])) return hipErrorInvalidValue;
-  if (g.M <= 32) return launch_tiles<32, 128, 32, 32>(g, epi, s);
-  if (g.M <= 64) return launch_tiles<64, 64, 32, 32>(g, epi, s);
-  return launch_tiles<128, 128, 64, 64>(g, epi, s);
+  if (g_force_tile >= 0 && !(g_force_tile >= 9 && g.M > 64)) return launch_config(g_force_tile, g, epi, s);
+  if (g.M <= 64) {
+    // measured on MI355X: very wide outputs (the vocabulary head) re-read A too often in the
+    // streaming kernel; mid-size outputs take 32 features per workgroup to halve A's L2 traffic
+    const int64_t n_total = static_cast<int64_t>(g.N) * g.parts;
+    if (n_total > 16384) return launch_config(g.M <= 32 ? 7 : 6, g, epi, s);
+    return launch_skinny_any(g, epi, s, n_total >= 6144 ? 1 : 0);
+  }
+  // Tile choice by how the tile count fills 256 CUs (2 workgroups of 128x128x64 each, 3 of 128x128x32):
+  const int t0 = ((g.M + 127) / 128) * ((g.N + 127) / 128) * g.parts;
+  if (t0 <= 128) return launch_config(6, g, epi, s);               // few tiles: 64x64
+  if (t0 <= 320) return launch_config(1, g, epi, s);               // under one round: 128x64 doubles the count
+  if (t0 > 512 && t0 <= 768) return launch_config(5, g, epi, s);   // between one and two rounds: 3 per CU
+  return launch_config(0, g, epi, s);
+}
+
+}  // namespace
+
+int gemm_force_tile(int cfg) {
+  if (cfg < -1 || cfg > 10) return -1;
+  g_force_tile = cfg;
+  return 0;
 }
 
 hipError_t launch_gemm(const _Float16* A, const _Float16* W, const _Float16* bias, void* out, int M, int N,

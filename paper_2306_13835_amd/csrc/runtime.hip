@@ -801,6 +801,8 @@ int ctn_op_gemm(const void* A, const void* W, const void* bias, void* out, int32
                            static_cast<hipStream_t>(stream)));
 }
 
+int ctn_debug_gemm_tile(int32_t cfg) { return gemm_force_tile(cfg) == 0 ? CTN_OK : CTN_E_INVAL; }
+
 int ctn_op_attention(const void* qkv, void* out, int32_t batch, int32_t seq, int32_t heads, int32_t head_dim,
                      void* stream) {
   if (!qkv || !out || batch < 0 || seq < 0 || heads < 0) return CTN_E_INVAL;

@@ -1,0 +1,45 @@
+"""Serial oldest-request-first serving loop over a swapping context.
+
+Section 3.1 / 4 of the paper: the engine keeps one queue per model, always serves the oldest
+pending request and swaps models on demand with LRU replacement.  With a maximum batch size of
+one and one GPU this is a single FIFO over the merged arrival stream; the loop below replays an
+arrival trace in real time (open loop: latency includes queueing behind earlier requests) and
+calls `ctn_infer` for each request.  All swapping decisions are taken inside the library.
+"""
+from __future__ import annotations
+
+import time
+from typing import Callable, Sequence
+
+import numpy as np
+
+
+def serve_trace(ctx, models: Sequence[int], arrival_s: np.ndarray, model_of: np.ndarray,
+                ids_of: Callable[[int], np.ndarray], out, time_scale: float = 1.0,
+                progress: Callable[[int], None] = None):
+    """Replays the trace; returns (latency_s, service_s, was_miss) arrays.
+
+    `out` is a device tensor receiving the logits of each request (overwritten every time);
+    a request is complete when its logits are complete on the compute stream.
+    """
+    n = len(arrival_s)
+    lat = np.zeros(n)
+    svc = np.zeros(n)
+    miss = np.zeros(n, dtype=bool)
+    arr = np.asarray(arrival_s, dtype=np.float64) * time_scale
+    t0 = time.perf_counter()
+    for i in range(n):
+        now = time.perf_counter() - t0
+        if now < arr[i]:
+            time.sleep(arr[i] - now)
+        m = models[int(model_of[i])]
+        start = time.perf_counter() - t0
+        miss[i] = not ctx.is_resident(m)
+        ctx.infer(m, ids_of(i), out=out)
+        ctx.stream_compute.synchronize()
+        end = time.perf_counter() - t0
+        lat[i] = end - arr[i]
+        svc[i] = end - start
+        if progress is not None:
+            progress(i)
+    return lat, svc, miss

@@ -81,7 +81,7 @@ def test_layernorm(stream, rows, hidden):
     assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.maximum(np.abs(want), 2.0 ** -14) + 1e-6)
 
 
-GEMM_SHAPES = [(8, 2304, 768), (1, 128, 64), (33, 200, 72), (64, 6144, 4096), (130, 257, 136),
+GEMM_SHAPES = [(8, 2304, 768), (1, 128, 64), (33, 200, 72), (16, 50, 40), (17, 4096, 2048), (48, 33, 8192), (49, 640, 264), (64, 6144, 4096), (130, 257, 136),
                (1024, 4096, 2048), (300, 50272 // 4, 512), (2048, 1280, 5120)]
 
 
@@ -134,3 +134,33 @@ def test_attention(stream, batch, seq, heads, d):
     # probabilities are rounded to fp16 before the second product, outputs to fp16
     assert np.abs(got - want).max() <= 4e-3 * max(1.0, np.abs(want).max())
     assert np.abs(got - want).mean() <= 4e-4 * np.abs(want).mean() + 1e-5
+
+
+@pytest.mark.parametrize("cfg", range(11))
+@pytest.mark.parametrize("M,N,K,epi", [(300, 520, 328, P.EPI_BIAS_RESID_F32), (257, 129, 64, P.EPI_BIAS_RELU_F16),
+                                       (61, 200, 1096, P.EPI_BIAS_F16), (9, 77, 40, P.EPI_F32)])
+def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
+    """Each tile shape the library can pick, forced through the tuning hook, on ragged sizes."""
+    rng = np.random.default_rng(cfg * 1000 + M)
+    A, W, bias = f16(rng, (M, K)), f16(rng, (N, K), 0.05), f16(rng, N, 0.5)
+    res = rng.standard_normal((M, N)).astype(np.float32)
+    acc = A.astype(np.float64) @ W.astype(np.float64).T + bias.astype(np.float64)
+    if epi == P.EPI_BIAS_RESID_F32:
+        want, out = res + acc, dev(res)
+    elif epi == P.EPI_BIAS_RELU_F16:
+        want, out = np.maximum(acc, 0), torch.empty(M, N, dtype=torch.float16, device="cuda")
+    elif epi == P.EPI_BIAS_F16:
+        want, out = acc, torch.empty(M, N, dtype=torch.float16, device="cuda")
+    else:
+        want, out = acc - bias.astype(np.float64), torch.empty(M, N, dtype=torch.float32, device="cuda")
+    B.debug_gemm_tile(cfg)
+    try:
+        B.op_gemm(dev(A), dev(W), dev(bias), out, M, N, K, epi, stream)
+        stream.synchronize()
+    finally:
+        B.debug_gemm_tile(-1)
+    got = out.cpu().numpy().astype(np.float64)
+    tol = 2.0 ** -10 * np.abs(want) + 1e-4 if out.dtype == torch.float16 else 1e-4
+    assert np.all(np.abs(got - want) <= tol)
+    with pytest.raises(P.CtnError):
+        B.debug_gemm_tile(11)

@@ -161,3 +161,35 @@ def test_register_errors_and_idempotence():
         assert rig.ctx.stats()["n_swap_in"] == 1 and rig.ctx.stats()["n_hit"] == 1
     finally:
         rig.close()
+
+
+def test_serving_loop_decisions_equal_oracle_and_results_are_deterministic():
+    """The serving loop on small shards: the residency decisions taken on the GPU path equal the
+    oracle's on the same request order; repeating a (model, ids) pair gives identical logits."""
+    from paper_2306_13835_amd.serving import serve_trace
+    from synth import gamma_zipf_trace, token_ids
+    desc = ShardDesc(2, 256, 1024, 4, vocab=1000, max_pos=64)
+    size, n = shard_bytes(desc), 6
+    rig = Rig([desc] * n, budget=2 * size + 5, arena_bytes=3 * P.arena_bytes(desc), max_tokens=16, mode=P.XFER_AUTO)
+    try:
+        ms = [rig.add(desc, seed=70 + i) for i in range(n)]
+        arr, mod = gamma_zipf_trace(n, 400.0, 4.0, 1.5, 150, seed=9)
+        ids = [token_ids(1000 + (i % 7), 1, 16, desc.vocab) for i in range(150)]
+        out = torch.empty(1, 16, desc.vocab, dtype=torch.float32, device="cuda")
+        seen = {}
+        def check(i):
+            key = (int(mod[i]), i % 7)
+            got = out.cpu().numpy().copy()
+            if key in seen:
+                assert np.array_equal(seen[key], got)
+            seen[key] = got
+        lat, svc, miss = serve_trace(rig.ctx, ms, arr, mod, lambda i: ids[i], out, progress=check)
+        rig.ctx.sync()
+        ref = LruResidency(2 * size + 5, [size] * n)
+        for m in mod:
+            ref.touch(int(m))
+        assert rig.ctx.events() == ref.events
+        assert [bool(x) for x in miss] == [e[0] == "miss" for e in ref.events]
+        assert (lat >= svc - 1e-6).all() and rig.ctx.stats()["peak_resident_bytes"] <= 2 * size + 5
+    finally:
+        rig.close()
