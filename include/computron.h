@@ -237,7 +237,7 @@ int ctn_op_layernorm(const float* x, const void* gain_f16, const void* bias_f16,
  * cores, then the chosen epilogue.  K % 8 == 0. */
 int ctn_op_gemm(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,
                 int32_t N, int32_t K, int32_t epilogue, void* stream);
-/* Test and tuning hook, process wide: forces tile configuration cfg (0..10; 9 and 10 = the streaming kernels for M <= 64, ignored for larger M) on every product of
+/* Test and tuning hook, process wide: forces tile configuration cfg (0..13; 9 and 10 = the streaming kernels for M <= 64, ignored for larger M) on every product of
  * ctn_op_gemm and ctn_infer; -1 restores the library's choice.  CTN_E_INVAL outside that range. */
 int ctn_debug_gemm_tile(int32_t cfg);
 /* Causal self-attention of every (batch, head): qkv fp16 [batch*seq, 3*heads*d]

@@ -52,13 +52,15 @@ struct GemmArgs {
 };
 
 template <int BM, int BN, int BK, int WM, int WN, int EPI>
-__global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, (WM * WN > 64 * 64 && WM * WN <= 128 * 64 && 4 * (BM + BN) * (BK + 8) <= 80 * 1024) ? 2 : 1)
+void gemm_nt_kernel(const GemmArgs g) {
+  constexpr int THREADS = (BM / WM) * (BN / WN) * 64;
   constexpr int LDS_ROW = BK + LDS_PAD;
   constexpr int LPR = BK / 8;          // 16-byte lanes per tile row in the cooperative load
-  constexpr int RPP = 256 / LPR;       // tile rows covered by one pass of the 256 threads
+  constexpr int RPP = THREADS / LPR;   // tile rows covered by one pass of the workgroup
   static_assert(BK == 32 || BK == 64, "K extent of one LDS stage");
   static_assert(BM % RPP == 0 && BN % RPP == 0, "cooperative load covers whole passes");
-  static_assert((BM / WM) * (BN / WN) == 4, "four wavefronts per workgroup");
+  static_assert(THREADS >= 256 && THREADS <= 1024, "4 to 16 wavefronts per workgroup");
   static_assert(WM % 32 == 0 && WN % 32 == 0 && BM % 32 == 0 && BN % 32 == 0, "32x32 MFMA tiles");
   constexpr int TM = WM / 32, TN = WN / 32;     // MFMA tiles per wavefront
   constexpr int PA = BM / RPP, PB = BN / RPP;   // passes of the cooperative loads
@@ -177,7 +179,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
 template <int BM, int BN, int BK, int WM, int WN>
 hipError_t launch_tiles(const GemmArgs& g, int epi, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * g.parts;
-  const dim3 grid(tiles), block(256);
+  const dim3 grid(tiles), block((BM / WM) * (BN / WN) * 64);
 #define CTN_GEMM(E) hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g)
   switch (epi) {
     case CTN_EPI_BIAS_F16: CTN_GEMM(CTN_EPI_BIAS_F16); break;
@@ -326,6 +328,9 @@ hipError_t launch_config(int cfg, const GemmArgs& g, int epi, hipStream_t s) {
     case 6: return launch_tiles<64, 64, 64, 32, 32>(g, epi, s);
     case 7: return launch_tiles<32, 128, 64, 32, 32>(g, epi, s);
     case 8: return launch_tiles<256, 256, 32, 128, 128>(g, epi, s);
+    case 11: return launch_tiles<256, 128, 64, 64, 64>(g, epi, s);    // 8 wavefronts
+    case 12: return launch_tiles<256, 256, 32, 64, 64>(g, epi, s);    // 16 wavefronts
+    case 13: return launch_tiles<256, 128, 32, 64, 64>(g, epi, s);    // 8 wavefronts, smaller stages
     case 9: return g.M <= 64 ? launch_skinny_any(g, epi, s, 0) : hipErrorInvalidValue;
     case 10: return g.M <= 64 ? launch_skinny_any(g, epi, s, 1) : hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
@@ -346,6 +351,8 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s) {
     return launch_skinny_any(g, epi, s, n_total >= 6144 ? 1 : 0);
   }
   // Tile choice by how the tile count fills 256 CUs (2 workgroups of 128x128x64 each, 3 of 128x128x32):
+  const int t_big = ((g.M + 255) / 256) * ((g.N + 127) / 128) * g.parts;
+  if (t_big >= 512) return launch_config(2, g, epi, s);            // plenty of work: 256x128 tiles, 128x64 per wave
   const int t0 = ((g.M + 127) / 128) * ((g.N + 127) / 128) * g.parts;
   if (t0 <= 128) return launch_config(6, g, epi, s);               // few tiles: 64x64
   if (t0 <= 320) return launch_config(1, g, epi, s);               // under one round: 128x64 doubles the count
@@ -356,7 +363,7 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s) {
 }  // namespace
 
 int gemm_force_tile(int cfg) {
-  if (cfg < -1 || cfg > 10) return -1;
+  if (cfg < -1 || cfg > 13) return -1;
   g_force_tile = cfg;
   return 0;
 }

@@ -136,7 +136,7 @@ def test_attention(stream, batch, seq, heads, d):
     assert np.abs(got - want).mean() <= 4e-4 * np.abs(want).mean() + 1e-5
 
 
-@pytest.mark.parametrize("cfg", range(11))
+@pytest.mark.parametrize("cfg", range(14))
 @pytest.mark.parametrize("M,N,K,epi", [(300, 520, 328, P.EPI_BIAS_RESID_F32), (257, 129, 64, P.EPI_BIAS_RELU_F16),
                                        (61, 200, 1096, P.EPI_BIAS_F16), (9, 77, 40, P.EPI_F32)])
 def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
@@ -163,4 +163,4 @@ def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
     tol = 2.0 ** -10 * np.abs(want) + 1e-4 if out.dtype == torch.float16 else 1e-4
     assert np.all(np.abs(got - want) <= tol)
     with pytest.raises(P.CtnError):
-        B.debug_gemm_tile(11)
+        B.debug_gemm_tile(14)
