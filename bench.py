@@ -385,9 +385,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", choices=["swap", "serve", "counters"], default="swap")
+    ap.add_argument("--workload", choices=["swap", "serve", "grid", "counters"], default="swap")
     ap.add_argument("--config", default="opt6.7b_tp2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--duration", type=float, default=30.0, help="grid workload: seconds of arrivals per trial")
     ap.add_argument("--requests", type=int, default=0, help="serve workload: number of requests (0: all 2000)")
     ap.add_argument("--transfer", choices=["auto", "kernel", "dma"], default="auto",
                     help="transfer mode of the timed region")
@@ -404,6 +405,9 @@ def main():
     P.lib()   # fails loudly when the HIP library is not built
     if args.workload == "counters":
         run_counters(args)
+    elif args.workload == "grid":
+        from paper_2306_13835_amd.serve_bench import run_grid
+        run_grid(args)
     elif args.workload == "serve":
         from paper_2306_13835_amd.serve_bench import run_serve
         run_serve(args)

@@ -212,6 +212,47 @@ const char* ctn_strerror(int code);
 int ctn_residency_replay(uint64_t budget_bytes, const uint64_t* sizes, int32_t n_models,
                          const int32_t* trace, uint64_t n, ctn_event* out);
 
+/* ---- serving engine (Section 3.1: per-model request queues, oldest first;
+ *      Section 5.2: maximum batch size) ----------------------------------------- */
+
+typedef struct ctn_engine ctn_engine;
+
+/* One dispatched batch of a replay: requests[offset .. offset+count) of the flat
+ * request array (indices into the trace, oldest first), all of `model`. */
+typedef struct {
+  double start, finish;
+  int32_t model, count, miss, reserved;
+  uint64_t offset;
+} ctn_batch_record;
+
+/* An engine over a context: one FIFO queue per registered model, batches of at
+ * most max_batch requests, every request exactly seq tokens long. */
+int ctn_engine_create(ctn_ctx* ctx, int32_t max_batch, int32_t seq, ctn_engine** out);
+int ctn_engine_destroy(ctn_engine* eng);
+/* Queues one request: ids (host, int32[seq], values in [0, vocab)) are copied;
+ * timestamp is the caller's clock (seconds).  *request_id counts from 0. */
+int ctn_engine_submit(ctn_engine* eng, ctn_model m, const int32_t* ids_host, double timestamp,
+                      int64_t* request_id);
+/* Dispatches one batch: the queue whose oldest request is oldest, up to
+ * max_batch of its requests, one ctn_infer (a use for the LRU policy; swaps as
+ * needed).  logits_out (device, fp32 [max_batch, seq, vocab/tp]) receives the
+ * batch's logits, request k of the batch in row k; the call returns with the
+ * work enqueued on the compute stream.  served_ids (host, cap >= max_batch)
+ * receives the request ids; *n_served == 0 when nothing is queued. */
+int ctn_engine_step(ctn_engine* eng, void* logits_out, int64_t* served_ids, int32_t cap, int32_t* n_served,
+                    ctn_model* model, int32_t* was_miss);
+int ctn_engine_pending(ctn_engine* eng, int64_t* n);
+/* Host only, simulated clock: replays a trace (arrival times ascending, host
+ * arrays of n entries) through the same queues, batch selection and
+ * replacement policy; a batch of b requests takes t_base + b * t_per_request
+ * (+ t_miss when its model was not resident) and the next one is dispatched
+ * when it has finished.  batches (cap entries) and requests (n entries) are
+ * host arrays. */
+int ctn_engine_replay(int32_t n_models, int32_t max_batch, uint64_t budget_bytes, const uint64_t* sizes,
+                      const double* arrival, const int32_t* model_of, uint64_t n, double t_base,
+                      double t_per_request, double t_miss, ctn_batch_record* batches, uint64_t cap,
+                      uint64_t* n_batches, uint64_t* requests);
+
 /* ---- single operations (each enqueues on `stream`, a hipStream_t; all data
  *      pointers are device pointers unless stated) --------------------------- */
 

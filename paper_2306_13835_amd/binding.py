@@ -18,7 +18,8 @@ DECLARED_SYMBOLS = [
     "ctn_arena_bytes", "ctn_is_resident", "ctn_get_stats", "ctn_get_events", "ctn_last_swap_ms",
     "ctn_debug_read_param", "ctn_get_streams", "ctn_set_mode", "ctn_last_hip_error", "ctn_strerror",
     "ctn_residency_replay", "ctn_op_copy", "ctn_op_dma", "ctn_op_embed", "ctn_op_layernorm",
-    "ctn_op_gemm", "ctn_op_attention", "ctn_debug_gemm_tile",
+    "ctn_op_gemm", "ctn_op_attention", "ctn_debug_gemm_tile", "ctn_engine_create", "ctn_engine_destroy",
+    "ctn_engine_submit", "ctn_engine_step", "ctn_engine_pending", "ctn_engine_replay",
 ]
 
 
@@ -48,6 +49,11 @@ class Stats(C.Structure):
 class Event(C.Structure):
     _fields_ = [("kind", C.c_int32), ("model", C.c_int32), ("n_victims", C.c_int32),
                 ("victims", C.c_int32 * 13)]
+
+
+class BatchRecord(C.Structure):
+    _fields_ = [("start", C.c_double), ("finish", C.c_double), ("model", C.c_int32), ("count", C.c_int32),
+                ("miss", C.c_int32), ("reserved", C.c_int32), ("offset", C.c_uint64)]
 
 
 class CtnError(RuntimeError):
@@ -104,6 +110,13 @@ def lib() -> C.CDLL:
         "ctn_op_gemm": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, vp]),
         "ctn_op_attention": (C.c_int, [vp, vp, i32, i32, i32, i32, vp]),
         "ctn_debug_gemm_tile": (C.c_int, [i32]),
+        "ctn_engine_create": (C.c_int, [vp, i32, i32, P(vp)]),
+        "ctn_engine_destroy": (C.c_int, [vp]),
+        "ctn_engine_submit": (C.c_int, [vp, i32, vp, C.c_double, P(i64)]),
+        "ctn_engine_step": (C.c_int, [vp, vp, P(i64), i32, P(i32), P(i32), P(i32)]),
+        "ctn_engine_pending": (C.c_int, [vp, P(i64)]),
+        "ctn_engine_replay": (C.c_int, [i32, i32, u64, P(u64), P(C.c_double), P(i32), u64, C.c_double, C.c_double,
+                                        C.c_double, P(BatchRecord), u64, P(u64), P(u64)]),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
@@ -139,6 +152,68 @@ def residency_replay(budget: int, sizes: Sequence[int], trace: Sequence[int]):
     if rc:
         raise CtnError(rc, "ctn_residency_replay")
     return _events_to_list(out, n)
+
+
+def engine_replay(n_models: int, max_batch: int, budget: int, sizes: Sequence[int], arrival, model_of,
+                  t_base: float, t_per_request: float, t_miss: float):
+    """Host-only replay of the scheduler; returns [(start, finish, model, request indices, miss)]."""
+    n = len(arrival)
+    sz = (C.c_uint64 * len(sizes))(*[int(x) for x in sizes])
+    arr = (C.c_double * max(n, 1))(*[float(x) for x in arrival])
+    mod = (C.c_int32 * max(n, 1))(*[int(x) for x in model_of])
+    rec = (BatchRecord * max(n, 1))()
+    req = (C.c_uint64 * max(n, 1))()
+    nb = C.c_uint64()
+    rc = lib().ctn_engine_replay(n_models, max_batch, int(budget), sz, arr, mod, n, t_base, t_per_request, t_miss,
+                                 rec, n, C.byref(nb), req)
+    if rc:
+        raise CtnError(rc, "ctn_engine_replay")
+    return [(r.start, r.finish, r.model, tuple(int(req[r.offset + k]) for k in range(r.count)), bool(r.miss))
+            for r in rec[:nb.value]]
+
+
+class Engine:
+    """ctn_engine: per-model FIFO queues over a Context, oldest-first batches of at most max_batch."""
+
+    def __init__(self, ctx: "Context", max_batch: int, seq: int):
+        self.ctx, self.max_batch, self.seq = ctx, max_batch, seq
+        h = C.c_void_p()
+        rc = lib().ctn_engine_create(ctx.h, max_batch, seq, C.byref(h))
+        if rc:
+            raise CtnError(rc, "ctn_engine_create")
+        self.h = h
+        self._served = (C.c_int64 * max_batch)()
+
+    def submit(self, model: int, ids: np.ndarray, timestamp: float) -> int:
+        ids = np.ascontiguousarray(ids, dtype=np.int32).reshape(-1)
+        if ids.size != self.seq:
+            raise ValueError("request length differs from the engine's")
+        rid = C.c_int64()
+        rc = lib().ctn_engine_submit(self.h, model, ids.ctypes.data, float(timestamp), C.byref(rid))
+        if rc:
+            raise CtnError(rc, "ctn_engine_submit")
+        return rid.value
+
+    def step(self, logits_out):
+        """Dispatches one batch; returns (request ids, model, was_miss) or None when idle."""
+        n, m, miss = C.c_int32(), C.c_int32(), C.c_int32()
+        rc = lib().ctn_engine_step(self.h, _addr(logits_out), self._served, self.max_batch, C.byref(n),
+                                   C.byref(m), C.byref(miss))
+        if rc:
+            raise CtnError(rc, "ctn_engine_step", lib().ctn_last_hip_error(self.ctx.h) if rc == -5 else 0)
+        if n.value == 0:
+            return None
+        return [int(self._served[i]) for i in range(n.value)], m.value, bool(miss.value)
+
+    def pending(self) -> int:
+        n = C.c_int64()
+        lib().ctn_engine_pending(self.h, C.byref(n))
+        return n.value
+
+    def close(self):
+        if self.h:
+            lib().ctn_engine_destroy(self.h)
+            self.h = None
 
 
 class HostPool:

@@ -16,6 +16,7 @@
 #include <vector>
 
 #include "computron.h"
+#include "engine.hpp"
 #include "kernels.h"
 #include "layout.hpp"
 #include "residency.hpp"
@@ -48,6 +49,16 @@ struct Model {
   bool used_since_load = false;      // ev_last_use recorded since the last swap-in
   bool load_recorded = false, out_recorded = false;
   bool pending_in = false, pending_out = false;
+
+  Model() = default;
+  Model(const Model&) = delete;
+  Model& operator=(const Model&) = delete;
+  ~Model() {   // also runs when registration fails half way
+    for (hipEvent_t e : ev_block)
+      if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {ev_in_start, ev_out_start, ev_out_done, ev_last_use})
+      if (e) (void)hipEventDestroy(e);
+  }
 };
 
 struct Activations {   // carved from the workspace for one inference of M tokens
@@ -408,11 +419,7 @@ int ctn_sync(ctn_ctx* c) {
 int ctn_destroy(ctn_ctx* c) {
   if (!c) return CTN_E_INVAL;
   int rc = ctn_sync(c);
-  for (auto& m : c->models) {
-    for (hipEvent_t e : m->ev_block) (void)hipEventDestroy(e);
-    for (hipEvent_t e : {m->ev_in_start, m->ev_out_start, m->ev_out_done, m->ev_last_use})
-      if (e) (void)hipEventDestroy(e);
-  }
+  c->models.clear();   // destroys every model's events
   if (c->own_streams) {
     for (hipStream_t st : {c->s_compute, c->s_h2d, c->s_d2h, c->s_wide})
       if (st) (void)hipStreamDestroy(st);
@@ -492,7 +499,7 @@ int ctn_register_model(ctn_ctx* c, const ctn_model_desc* desc, const ctn_param* 
   size_t n_runs = 0;
   for (auto& rs : m->runs) n_runs += rs.size();
   m->fragmented = n_runs > 4 * static_cast<size_t>(L.n_blocks);
-  m->ev_block.resize(L.n_blocks);
+  m->ev_block.assign(L.n_blocks, nullptr);
   for (auto& e : m->ev_block) CTN_HIP(c, hipEventCreate(&e));
   CTN_HIP(c, hipEventCreate(&m->ev_in_start));
   CTN_HIP(c, hipEventCreate(&m->ev_out_start));
@@ -757,6 +764,127 @@ int ctn_residency_replay(uint64_t budget, const uint64_t* sizes, int32_t n_model
     }
     out[i] = e;
   }
+  return CTN_OK;
+}
+
+// ---- serving engine ------------------------------------------------------------
+
+struct ctn_engine {
+  ctn_ctx* ctx;
+  int max_batch, seq;
+  RequestQueues queues;
+  int64_t next_id = 0;
+  std::vector<int32_t> packed;   // ids of the batch being dispatched
+};
+
+int ctn_engine_create(ctn_ctx* c, int32_t max_batch, int32_t seq, ctn_engine** out) {
+  if (!c || !out || max_batch < 1 || seq < 1) return CTN_E_INVAL;
+  ctn_engine* e = new (std::nothrow) ctn_engine{c, max_batch, seq, RequestQueues(), 0, {}};
+  if (!e) return CTN_E_NOMEM;
+  *out = e;
+  return CTN_OK;
+}
+
+int ctn_engine_destroy(ctn_engine* e) {
+  delete e;
+  return CTN_OK;
+}
+
+int ctn_engine_submit(ctn_engine* e, ctn_model m, const int32_t* ids, double timestamp, int64_t* request_id) {
+  if (!e || !ids) return CTN_E_INVAL;
+  Model* mod = get_model(e->ctx, m);
+  if (!mod) return CTN_E_NOMODEL;
+  if (e->seq > mod->lay.d.max_pos) return CTN_E_SHAPE;
+  for (int i = 0; i < e->seq; ++i)
+    if (ids[i] < 0 || ids[i] >= mod->lay.d.vocab) return CTN_E_INVAL;
+  e->queues.ensure(static_cast<int>(e->ctx->models.size()));
+  QueuedRequest r{e->next_id, timestamp, std::vector<int32_t>(ids, ids + e->seq)};
+  e->queues.push(m, std::move(r));
+  if (request_id) *request_id = e->next_id;
+  e->next_id += 1;
+  return CTN_OK;
+}
+
+int ctn_engine_pending(ctn_engine* e, int64_t* n) {
+  if (!e || !n) return CTN_E_INVAL;
+  *n = e->queues.pending();
+  return CTN_OK;
+}
+
+int ctn_engine_step(ctn_engine* e, void* logits_out, int64_t* served, int32_t cap, int32_t* n_served,
+                    ctn_model* model, int32_t* was_miss) {
+  if (!e || !logits_out || !served || !n_served || cap < e->max_batch) return CTN_E_INVAL;
+  *n_served = 0;
+  const int m = e->queues.pick();
+  if (m < 0) return CTN_OK;
+  std::vector<QueuedRequest> batch = e->queues.pop(m, e->max_batch);
+  e->packed.clear();
+  for (const QueuedRequest& r : batch) e->packed.insert(e->packed.end(), r.ids.begin(), r.ids.end());
+  if (model) *model = m;
+  if (was_miss) *was_miss = e->ctx->models[m]->resident ? 0 : 1;
+  const int rc = ctn_infer(e->ctx, m, e->packed.data(), static_cast<int32_t>(batch.size()), e->seq, logits_out, 1);
+  if (rc) {   // put the requests back in order so nothing is lost
+    for (auto it = batch.rbegin(); it != batch.rend(); ++it) e->queues.push_front(m, std::move(*it));
+    return rc;
+  }
+  for (size_t i = 0; i < batch.size(); ++i) served[i] = batch[i].id;
+  *n_served = static_cast<int32_t>(batch.size());
+  return CTN_OK;
+}
+
+int ctn_engine_replay(int32_t n_models, int32_t max_batch, uint64_t budget, const uint64_t* sizes,
+                      const double* arrival, const int32_t* model_of, uint64_t n, double t_base,
+                      double t_per_request, double t_miss, ctn_batch_record* batches, uint64_t cap,
+                      uint64_t* n_batches, uint64_t* requests) {
+  if (n_models <= 0 || max_batch < 1 || !sizes || !n_batches || (n && (!arrival || !model_of || !batches || !requests)))
+    return CTN_E_INVAL;
+  for (uint64_t i = 0; i < n; ++i) {
+    if (model_of[i] < 0 || model_of[i] >= n_models) return CTN_E_NOMODEL;
+    if (i && arrival[i] < arrival[i - 1]) return CTN_E_INVAL;
+  }
+  Residency res(budget);
+  for (int i = 0; i < n_models; ++i) {
+    if (sizes[i] > budget) return CTN_E_TOO_BIG;
+    res.add_model(sizes[i]);
+  }
+  RequestQueues queues(n_models);
+  double now = 0.0;
+  uint64_t nxt = 0, served = 0, nb = 0;
+  while (served < n) {
+    while (nxt < n && arrival[nxt] <= now) {
+      queues.push(model_of[nxt], QueuedRequest{static_cast<int64_t>(nxt), arrival[nxt], {}});
+      ++nxt;
+    }
+    const int m = queues.pick();
+    if (m < 0) {
+      now = arrival[nxt];
+      continue;
+    }
+    std::vector<QueuedRequest> batch = queues.pop(m, max_batch);
+    bool miss = !res.resident(m);
+    if (miss) {
+      while (res.over_budget_with(m)) {
+        const int v = res.oldest(m);
+        if (v < 0) return CTN_E_BUSY;
+        res.mark_evicted(v);
+      }
+      res.mark_resident(m);
+    } else {
+      res.touch(m);
+    }
+    if (nb >= cap) return CTN_E_INVAL;
+    ctn_batch_record& b = batches[nb++];
+    b.start = now;
+    b.finish = now + t_base + t_per_request * static_cast<double>(batch.size()) + (miss ? t_miss : 0.0);
+    b.model = m;
+    b.count = static_cast<int32_t>(batch.size());
+    b.miss = miss ? 1 : 0;
+    b.reserved = 0;
+    b.offset = served;
+    for (const QueuedRequest& r : batch) requests[served++] = static_cast<uint64_t>(r.id);
+    now = b.finish;
+  }
+  *n_batches = nb;
   return CTN_OK;
 }
 

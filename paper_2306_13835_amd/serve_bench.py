@@ -104,3 +104,84 @@ def run_serve(args):
     del keep
     pool.close()
     print(json.dumps(res), flush=True)
+
+
+# Average end-to-end latencies the paper prints (Tables 1 and 2; 4 x A100, OPT-13B, TP=2 x PP=2,
+# unit not printed, seconds by context).  Context only: another machine, the whole model.
+PAPER_TABLES = {
+    "3 models / 2 resident, max batch 8": {"(1, 1, 1)": (1.262, 0.606, 0.518), "(10, 1, 1)": (1.172, 0.886, 0.550),
+                                           "(10, 10, 1)": (1.014, 0.716, 0.374)},
+    "6 models / 4 resident, max batch 32": {"(1, 1, 1, 1, 1, 1)": (1.847, 1.282, 0.174),
+                                            "(10, 10, 1, 1, 1, 1)": (2.017, 1.413, 0.229),
+                                            "(10, 10, 10, 10, 1, 1)": (1.535, 1.470, 0.312)},
+}
+GRIDS = [
+    ("3 models / 2 resident, max batch 8", 3, 2, 8, [(1, 1, 1), (10, 1, 1), (10, 10, 1)]),
+    ("6 models / 4 resident, max batch 32", 6, 4, 32, [(1,) * 6, (10, 10, 1, 1, 1, 1), (10, 10, 10, 10, 1, 1)]),
+]
+CVS = (0.25, 1.0, 4.0)
+
+
+def run_grid(args):
+    """The paper's simulated workloads (Section 5.2) on one worker's shard: Gamma arrivals per model
+    over `--duration` seconds, 8 input tokens per request, oldest-first batching, LRU swapping."""
+    import torch
+    import paper_2306_13835_amd as P
+    from paper_2306_13835_amd.serving import serve_engine
+    from synth import CONFIGS, fill_shard, token_ids, shard_bytes, param_list
+    from synth.arrivals import gamma_rates_trace
+
+    torch.cuda.set_device(0)
+    torch.zeros(1, device="cuda")
+    desc = CONFIGS["opt13b_tp4"]["desc"]          # one GPU's quarter of OPT-13B, as in the paper's 4-GPU runs
+    seq, nbytes = 8, shard_bytes(desc)
+    gap = 4096 if args.host_layout == "separate" else 0
+    n_t = len(param_list(desc))
+    max_models = max(g[1] for g in GRIDS)
+    pool = P.HostPool(max_models * (nbytes + n_t * (256 + gap)) + 8192)
+    t0 = time.time()
+    keep = [fill_shard(desc, 60 + k, alloc=lambda s: pool.take(s, gap=gap), threads=16) for k in range(max_models)]
+    log(f"[grid] {max_models} shards ({max_models * nbytes / 1e9:.1f} GB pinned) ready in {time.time() - t0:.1f}s")
+    results = {}
+    for name, n_models, resident, max_batch, skews in GRIDS:
+        budget = resident * nbytes
+        arena = torch.empty((resident + 1) * P.arena_bytes(desc), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(P.workspace_bytes(desc, max_batch * seq), dtype=torch.uint8, device="cuda")
+        logits = torch.empty(max_batch, seq, desc.vocab // desc.tp, dtype=torch.float32, device="cuda")
+        ctx = P.Context(budget, arena, ws, transfer_mode={"dma": 0, "kernel": 1, "auto": 2}[args.transfer], pipeline=True)
+        models = [ctx.register_model(desc, keep[k]) for k in range(n_models)]
+        eng = P.Engine(ctx, max_batch, seq)
+        table = {}
+        for skew in skews:
+            row = []
+            for cv in CVS:
+                arr, mod = gamma_rates_trace(skew, cv, args.duration, seed=700 + int(cv * 100))
+                ids = [token_ids(2000 + i, 1, seq, desc.vocab) for i in range(len(arr))]
+                for k in range(min(resident, n_models)):       # warm-up requests, not recorded (Section 5.2)
+                    eng.submit(models[k], ids[0], 0.0)
+                    eng.step(logits)
+                ctx.sync()
+                st0 = ctx.stats()
+                lat, batches = serve_engine(ctx, eng, models, arr, mod, lambda i: ids[i], logits)
+                ctx.sync()
+                st = ctx.stats()
+                row.append({"cv": cv, "requests": len(arr), "mean_s": round(float(lat.mean()), 4),
+                            "p50_s": round(float(np.percentile(lat, 50)), 4), "p99_s": round(float(np.percentile(lat, 99)), 4),
+                            "swaps": st["n_miss"] - st0["n_miss"], "batches": len(batches),
+                            "mean_batch": round(float(np.mean([b[0] for b in batches])), 2)})
+                log(f"[grid] {name} rates {skew} CV {cv}: mean {row[-1]['mean_s']} s, p99 {row[-1]['p99_s']} s, "
+                    f"{row[-1]['swaps']} swaps / {len(arr)} requests")
+            table[str(tuple(skew))] = row
+        results[name] = table
+        eng.close()
+        ctx.close()
+        del arena, ws, logits
+    out = {"metric": "average end-to-end request latency per (rates, CV), the paper's Section 5.2 grids on one worker's shard",
+           "unit": "s", "n_gpus": 1, "higher_is_better": False, "data": "synthetic", "dtype": "f16",
+           "config": {"workload": f"opt13b_tp4 shard ({nbytes} B) x 3 and x 6 models, {args.duration:.0f} s Gamma arrivals, "
+                                  f"{seq} tokens per request, oldest-first batching, LRU", "transfer": args.transfer,
+                      "host_layout": args.host_layout},
+           "results": results, "paper_tables_context": PAPER_TABLES}
+    del keep
+    pool.close()
+    print(json.dumps(out), flush=True)

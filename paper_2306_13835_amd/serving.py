@@ -43,3 +43,43 @@ def serve_trace(ctx, models: Sequence[int], arrival_s: np.ndarray, model_of: np.
         if progress is not None:
             progress(i)
     return lat, svc, miss
+
+
+def serve_engine(ctx, engine, models: Sequence[int], arrival_s: np.ndarray, model_of: np.ndarray,
+                 ids_of: Callable[[int], np.ndarray], out, on_batch: Callable = None):
+    """Real-time replay through the library's engine (per-model queues, oldest-first batches of at
+    most `engine.max_batch`, Sections 3.1 / 4 / 5.2).  Requests are submitted when their arrival
+    time has passed; the loop dispatches one batch at a time and waits for its logits.
+    Returns (latency_s per request, list of (n_requests, model, was_miss, service_s) per batch)."""
+    n = len(arrival_s)
+    lat = np.zeros(n)
+    batches = []
+    nxt = done = 0
+    base = None                      # the engine's id of trace request 0 (earlier submissions shift it)
+    t0 = time.perf_counter()
+    while done < n:
+        now = time.perf_counter() - t0
+        while nxt < n and arrival_s[nxt] <= now:
+            rid = engine.submit(models[int(model_of[nxt])], ids_of(nxt), float(arrival_s[nxt]))
+            if base is None:
+                base = rid
+            assert rid - base == nxt
+            nxt += 1
+        start = time.perf_counter() - t0
+        r = engine.step(out)
+        if r is None:
+            pause = arrival_s[nxt] - (time.perf_counter() - t0)
+            if pause > 0:
+                time.sleep(pause)
+            continue
+        ctx.stream_compute.synchronize()
+        end = time.perf_counter() - t0
+        served, m, miss = r
+        served = [rid - base for rid in served]
+        for rid in served:
+            lat[rid] = end - arrival_s[rid]
+        done += len(served)
+        batches.append((len(served), m, miss, end - start))
+        if on_batch is not None:
+            on_batch(served, m, miss)
+    return lat, batches

@@ -88,3 +88,26 @@ def test_no_device_fails_loudly():
     cfg = P.binding.Config(1 << 20, 256, 1 << 20, 512, 1 << 20, 1, 2, 3, 1, 1, 0, 0)
     h = C.c_void_p()
     assert P.lib().ctn_create(C.byref(cfg), C.byref(h)) == -5
+
+
+@given(st.lists(st.tuples(st.floats(0, 30, allow_nan=False), st.integers(0, 3)), min_size=0, max_size=40),
+       st.integers(1, 5), st.integers(1, 3))
+@settings(max_examples=300, deadline=None)
+def test_engine_schedule_equals_oracle(reqs, max_batch, capacity):
+    """The library's queues + batch selection + replacement, on a simulated clock, against the oracle engine."""
+    from oracle.engine import simulate
+    reqs = sorted(reqs, key=lambda r: r[0])
+    arrival, model_of = [a for a, _ in reqs], [m for _, m in reqs]
+    t_base, t_req, t_miss = 0.5, 0.25, 2.0
+    got = P.engine_replay(4, max_batch, capacity * 10, [10] * 4, arrival, model_of, t_base, t_req, t_miss)
+    want, _ = simulate(arrival, model_of, 4, max_batch, capacity * 10, [10] * 4,
+                       lambda m, b, miss: t_base + t_req * b + (t_miss if miss else 0.0))
+    assert [(m, r, x) for _, _, m, r, x in got] == [(m, r, x) for _, _, m, r, x in want]
+    assert np.allclose([(a, b) for a, b, *_ in got], [(a, b) for a, b, *_ in want], rtol=0, atol=1e-9) or not got
+
+
+def test_engine_replay_errors():
+    with pytest.raises(P.CtnError):
+        P.engine_replay(2, 1, 10, [4, 4], [1.0, 0.5], [0, 1], 0.1, 0.1, 0.1)      # not sorted
+    with pytest.raises(P.CtnError):
+        P.engine_replay(2, 1, 10, [4, 4], [0.5, 1.0], [0, 2], 0.1, 0.1, 0.1)      # unknown model

@@ -70,6 +70,18 @@ def test_small_shards_every_mode(desc, batch, seq, torch_streams):
         rig.close()
 
 
+def test_longest_sequence_the_model_allows():
+    """seq = max_pos = 2048 (the largest position table the configs use), one batch row."""
+    desc = ShardDesc(1, 128, 512, 2, vocab=512, max_pos=2048)
+    rig = Rig([desc], max_tokens=2048)
+    try:
+        m = rig.add(desc, seed=11)
+        ids = token_ids(12, 1, 2048, desc.vocab)
+        assert_close(rig.ctx.infer(m, ids), oracle_logits(rig, m, desc, ids), "seq 2048")
+    finally:
+        rig.close()
+
+
 def test_device_output_and_shape_errors():
     desc, batch, seq = TINY[0]
     rig = Rig([desc], max_tokens=batch * seq)

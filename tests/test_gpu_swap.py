@@ -193,3 +193,42 @@ def test_serving_loop_decisions_equal_oracle_and_results_are_deterministic():
         assert (lat >= svc - 1e-6).all() and rig.ctx.stats()["peak_resident_bytes"] <= 2 * size + 5
     finally:
         rig.close()
+
+
+def test_engine_batches_rows_match_oracle_forward():
+    """Requests queued for three models, batches of up to 4: every request's logits row equals the
+    oracle's forward of that request alone; batches are single-model, oldest head first."""
+    from oracle import opt_shard as O
+    from synth import token_ids
+    desc = ShardDesc(2, 256, 1024, 4, vocab=1000, max_pos=64)
+    size = shard_bytes(desc)
+    rig = Rig([desc] * 3, budget=2 * size, arena_bytes=3 * P.arena_bytes(desc), max_tokens=4 * 8, mode=P.XFER_AUTO)
+    eng = P.Engine(rig.ctx, max_batch=4, seq=8)
+    try:
+        ms = [rig.add(desc, seed=80 + i) for i in range(3)]
+        which = [0, 1, 0, 0, 2, 0, 0, 1, 0, 2, 2]
+        ids = [token_ids(300 + i, 1, 8, desc.vocab) for i in range(len(which))]
+        for i, w in enumerate(which):
+            assert eng.submit(ms[w], ids[i], timestamp=float(i)) == i
+        assert eng.pending() == len(which)
+        out = torch.empty(4, 8, desc.vocab, dtype=torch.float32, device="cuda")
+        order = []
+        while True:
+            r = eng.step(out)
+            if r is None:
+                break
+            rig.ctx.stream_compute.synchronize()
+            served, m, miss = r
+            order.append((tuple(served), m))
+            got = out.cpu().numpy()
+            for row, rid in enumerate(served):
+                want = O.forward(rig.tensors[m], ids[rid], layers=desc.layers, heads=desc.heads)
+                assert np.abs(got[row] - want[0]).max() <= 2e-2
+                assert np.abs(got[row] - want[0]).mean() / np.abs(want).mean() <= 1e-3
+        assert order == [((0, 2, 3, 5), 0), ((1, 7), 1), ((4, 9, 10), 2), ((6, 8), 0)]
+        assert eng.pending() == 0
+        with pytest.raises(P.CtnError):
+            eng.submit(9, ids[0], 0.0)
+    finally:
+        eng.close()
+        rig.close()
