@@ -278,7 +278,15 @@ int ctn_op_layernorm(const float* x, const void* gain_f16, const void* bias_f16,
  * cores, then the chosen epilogue.  K % 8 == 0. */
 int ctn_op_gemm(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,
                 int32_t N, int32_t K, int32_t epilogue, void* stream);
-/* Test and tuning hook, process wide: forces tile configuration cfg (0..13; 9 and 10 = the streaming kernels for M <= 64, ignored for larger M) on every product of
+/* The same product with a device scratch buffer (16-byte aligned; may be NULL): products with
+ * M <= 64 may then cut K into slices computed by separate workgroups, whose fp32 partial tiles
+ * are added in a fixed order, so the result does not depend on timing.  ctn_infer does the same
+ * with a slice of its workspace. */
+int ctn_op_gemm_ws(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,
+                   int32_t N, int32_t K, int32_t epilogue, void* workspace, uint64_t workspace_bytes,
+                   void* stream);
+/* Test and tuning hook, process wide: forces tile configuration cfg (0..15; 9 and 10 = the streaming kernels for M <= 64, ignored for larger M; 14 and 15 = split-K
+ * over 64x64 / 32x128 tiles where a workspace is given) on every product of
  * ctn_op_gemm and ctn_infer; -1 restores the library's choice.  CTN_E_INVAL outside that range. */
 int ctn_debug_gemm_tile(int32_t cfg);
 /* Causal self-attention of every (batch, head): qkv fp16 [batch*seq, 3*heads*d]

@@ -18,7 +18,7 @@ DECLARED_SYMBOLS = [
     "ctn_arena_bytes", "ctn_is_resident", "ctn_get_stats", "ctn_get_events", "ctn_last_swap_ms",
     "ctn_debug_read_param", "ctn_get_streams", "ctn_set_mode", "ctn_last_hip_error", "ctn_strerror",
     "ctn_residency_replay", "ctn_op_copy", "ctn_op_dma", "ctn_op_embed", "ctn_op_layernorm",
-    "ctn_op_gemm", "ctn_op_attention", "ctn_debug_gemm_tile", "ctn_engine_create", "ctn_engine_destroy",
+    "ctn_op_gemm", "ctn_op_gemm_ws", "ctn_op_attention", "ctn_debug_gemm_tile", "ctn_engine_create", "ctn_engine_destroy",
     "ctn_engine_submit", "ctn_engine_step", "ctn_engine_pending", "ctn_engine_replay",
 ]
 
@@ -108,6 +108,7 @@ def lib() -> C.CDLL:
         "ctn_op_embed": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]),
         "ctn_op_layernorm": (C.c_int, [vp, vp, vp, vp, i32, i32, vp]),
         "ctn_op_gemm": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, vp]),
+        "ctn_op_gemm_ws": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, vp, u64, vp]),
         "ctn_op_attention": (C.c_int, [vp, vp, i32, i32, i32, i32, vp]),
         "ctn_debug_gemm_tile": (C.c_int, [i32]),
         "ctn_engine_create": (C.c_int, [vp, i32, i32, P(vp)]),
@@ -399,6 +400,12 @@ def op_layernorm(x, g, b, out, rows, hidden, stream):
 def op_gemm(A, W, bias, out, M, N, K, epilogue, stream):
     _op(lib().ctn_op_gemm(_addr(A), _addr(W), _addr(bias), _addr(out), M, N, K, epilogue, stream.cuda_stream),
         "ctn_op_gemm")
+
+
+def op_gemm_ws(A, W, bias, out, M, N, K, epilogue, workspace, stream):
+    nbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _op(lib().ctn_op_gemm_ws(_addr(A), _addr(W), _addr(bias), _addr(out), M, N, K, epilogue, _addr(workspace), nbytes,
+                             stream.cuda_stream), "ctn_op_gemm_ws")
 
 
 def op_attention(qkv, out, batch, seq, heads, head_dim, stream):

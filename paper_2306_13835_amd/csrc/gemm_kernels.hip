@@ -49,7 +49,13 @@ struct GemmArgs {
   const _Float16* bias[3];
   void* out;
   int M, N, K, ldc, parts;
+  // Split-K (small M): the K range is cut into `splits` slices, one workgroup per (tile, slice);
+  // every slice stores its fp32 partial tile into partial[slice][M][parts*N] and a second kernel
+  // adds the slices in a fixed order and applies the epilogue.  splits == 1: no partials.
+  int splits;
+  float* partial;
 };
+constexpr int EPI_PARTIAL = 100;   // internal epilogue: store the raw accumulator into the slice's partial buffer
 
 template <int BM, int BN, int BK, int WM, int WN, int EPI>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, (WM * WN > 64 * 64 && WM * WN <= 128 * 64 && 4 * (BM + BN) * (BK + 8) <= 80 * 1024) ? 2 : 1)
@@ -70,7 +76,9 @@ void gemm_nt_kernel(const GemmArgs g) {
 
   const int M = g.M, N = g.N, K = g.K;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n * g.parts);
+  int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n * g.parts * g.splits);
+  const int split = tile / (tiles_m * tiles_n * g.parts);
+  tile -= split * tiles_m * tiles_n * g.parts;
   const int part = tile / (tiles_m * tiles_n);
   tile -= part * tiles_m * tiles_n;
   const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;   // m fastest: W tile shared by neighbours
@@ -115,15 +123,22 @@ void gemm_nt_kernel(const GemmArgs g) {
     for (int p = 0; p < PB; ++p) *reinterpret_cast<u32x4*>(&Bs[buf][p * RPP + lrow][lcol]) = rb[p];
   };
 
-  const int ksteps = (K + BK - 1) / BK;
-  load_global(0);
-  store_lds(0);
+  // this workgroup's slice of the K steps (all of them when splits == 1)
+  const int ksteps_all = (K + BK - 1) / BK;
+  const int kt_begin = static_cast<int>(static_cast<int64_t>(ksteps_all) * split / g.splits);
+  const int kt_end = static_cast<int>(static_cast<int64_t>(ksteps_all) * (split + 1) / g.splits);
+  const int ksteps = kt_end - kt_begin;
+  const int kbase = kt_begin * BK;
+  if (ksteps > 0) {
+    load_global(kbase);
+    store_lds(0);
+  }
   __syncthreads();
 
   const int frow = lane & 31, fcol = (lane >> 5) * 8;
   for (int kt = 0; kt < ksteps; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < ksteps) load_global((kt + 1) * BK);   // in flight while this stage is multiplied
+    if (kt + 1 < ksteps) load_global(kbase + (kt + 1) * BK);   // in flight while this stage is multiplied
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       half8 af[TM], bf[TN];
@@ -153,7 +168,7 @@ void gemm_nt_kernel(const GemmArgs g) {
     const int n = n0 + wn0 + j * 32 + col_in;
     if (n >= N) continue;
     float bv = 0.f;
-    if (EPI != CTN_EPI_F32) bv = static_cast<float>(bias[n]);
+    if (EPI != CTN_EPI_F32 && EPI != EPI_PARTIAL) bv = static_cast<float>(bias[n]);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -162,7 +177,9 @@ void gemm_nt_kernel(const GemmArgs g) {
         if (m >= M) continue;
         const int64_t o = static_cast<int64_t>(m) * ldc + col0 + n;
         const float v = acc[i][j][e] + bv;
-        if (EPI == CTN_EPI_BIAS_F16) {
+        if (EPI == EPI_PARTIAL) {
+          g.partial[(static_cast<int64_t>(split) * M + m) * (static_cast<int64_t>(N) * g.parts) + col0 + n] = v;
+        } else if (EPI == CTN_EPI_BIAS_F16) {
           static_cast<_Float16*>(out)[o] = static_cast<_Float16>(v);
         } else if (EPI == CTN_EPI_BIAS_RELU_F16) {
           static_cast<_Float16*>(out)[o] = static_cast<_Float16>(v > 0.f ? v : 0.f);
@@ -178,10 +195,11 @@ void gemm_nt_kernel(const GemmArgs g) {
 
 template <int BM, int BN, int BK, int WM, int WN>
 hipError_t launch_tiles(const GemmArgs& g, int epi, hipStream_t s) {
-  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * g.parts;
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * g.parts * g.splits;
   const dim3 grid(tiles), block((BM / WM) * (BN / WN) * 64);
 #define CTN_GEMM(E) hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g)
   switch (epi) {
+    case EPI_PARTIAL: CTN_GEMM(EPI_PARTIAL); break;
     case CTN_EPI_BIAS_F16: CTN_GEMM(CTN_EPI_BIAS_F16); break;
     case CTN_EPI_BIAS_RELU_F16: CTN_GEMM(CTN_EPI_BIAS_RELU_F16); break;
     case CTN_EPI_BIAS_RESID_F32: CTN_GEMM(CTN_EPI_BIAS_RESID_F32); break;
@@ -315,6 +333,47 @@ hipError_t launch_skinny_any(const GemmArgs& g, int epi, hipStream_t s, int vari
   return variant ? launch_skinny<4, 2, 2>(g, epi, s) : launch_skinny<4, 1, 4>(g, epi, s);
 }
 
+// Second pass of a split-K product: out = epilogue(sum over slices, in slice order).
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs g) {
+  const int64_t ncols = static_cast<int64_t>(g.N) * g.parts;
+  const int64_t total = static_cast<int64_t>(g.M) * ncols;
+  for (int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; idx < total;
+       idx += static_cast<int64_t>(gridDim.x) * 256) {
+    const int64_t m = idx / ncols, c = idx % ncols;
+    const int part = static_cast<int>(c / g.N), n = static_cast<int>(c % g.N);
+    float v = 0.f;
+    for (int sidx = 0; sidx < g.splits; ++sidx) v += g.partial[(static_cast<int64_t>(sidx) * g.M + m) * ncols + c];
+    const _Float16* bias = part == 0 ? g.bias[0] : (part == 1 ? g.bias[1] : g.bias[2]);
+    if (EPI != CTN_EPI_F32) v += static_cast<float>(bias[n]);
+    const int64_t o = m * g.ldc + c;
+    if (EPI == CTN_EPI_BIAS_F16) {
+      static_cast<_Float16*>(g.out)[o] = static_cast<_Float16>(v);
+    } else if (EPI == CTN_EPI_BIAS_RELU_F16) {
+      static_cast<_Float16*>(g.out)[o] = static_cast<_Float16>(v > 0.f ? v : 0.f);
+    } else if (EPI == CTN_EPI_BIAS_RESID_F32) {
+      static_cast<float*>(g.out)[o] += v;
+    } else {
+      static_cast<float*>(g.out)[o] = v;
+    }
+  }
+}
+
+hipError_t launch_splitk_reduce(const GemmArgs& g, int epi, hipStream_t s) {
+  const int64_t total = static_cast<int64_t>(g.M) * g.N * g.parts;
+  const dim3 grid(static_cast<unsigned>((total + 255) / 256)), block(256);
+#define CTN_RED(E) hipLaunchKernelGGL((splitk_reduce_kernel<E>), grid, block, 0, s, g)
+  switch (epi) {
+    case CTN_EPI_BIAS_F16: CTN_RED(CTN_EPI_BIAS_F16); break;
+    case CTN_EPI_BIAS_RELU_F16: CTN_RED(CTN_EPI_BIAS_RELU_F16); break;
+    case CTN_EPI_BIAS_RESID_F32: CTN_RED(CTN_EPI_BIAS_RESID_F32); break;
+    case CTN_EPI_F32: CTN_RED(CTN_EPI_F32); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef CTN_RED
+  return hipGetLastError();
+}
+
 int g_force_tile = -1;   // test / tuning hook: tile configuration forced for every product
 
 hipError_t launch_config(int cfg, const GemmArgs& g, int epi, hipStream_t s) {
@@ -337,22 +396,52 @@ hipError_t launch_config(int cfg, const GemmArgs& g, int epi, hipStream_t s) {
   }
 }
 
-hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s) {
+// Split-K for small M: enough (tile, slice) workgroups to fill the chip twice, each slice at
+// least two K steps long, the partial buffer permitting.  Returns 1 when splitting does not pay.
+int choose_splits(const GemmArgs& g, int bm, int bn, size_t partial_floats) {
+  const int tiles = ((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) * g.parts;
+  const int ksteps = (g.K + 63) / 64;
+  int splits = 512 / (tiles > 0 ? tiles : 1);
+  if (splits > ksteps / 2) splits = ksteps / 2;
+  if (splits > 16) splits = 16;
+  const size_t per_slice = static_cast<size_t>(g.M) * g.N * g.parts;
+  if (per_slice && splits > static_cast<int>(partial_floats / per_slice)) splits = static_cast<int>(partial_floats / per_slice);
+  return splits < 2 ? 1 : splits;
+}
+
+hipError_t launch_splitk(GemmArgs g, int cfg, int splits, int epi, hipStream_t s) {
+  g.splits = splits;
+  hipError_t e = launch_config(cfg, g, EPI_PARTIAL, s);
+  if (e != hipSuccess) return e;
+  return launch_splitk_reduce(g, epi, s);
+}
+
+hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_floats) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   if (g.K <= 0 || g.K % 8 || g.parts < 1 || g.parts > 3) return hipErrorInvalidValue;
   for (int p = 0; p < g.parts; ++p)
     if (!g.W[p] || (epi != CTN_EPI_F32 && !g.bias[p])) return hipErrorInvalidValue;
-  if (g_force_tile >= 0 && !(g_force_tile >= 9 && g.M > 64)) return launch_config(g_force_tile, g, epi, s);
+  if (g_force_tile == 14 || g_force_tile == 15) {       // tuning hook: split-K over 64x64 / 32x128 tiles
+    const int cfg = g_force_tile == 14 ? 6 : 7;
+    const int splits = g.partial ? choose_splits(g, cfg == 6 ? 64 : 32, cfg == 6 ? 64 : 128, partial_floats) : 1;
+    return splits > 1 ? launch_splitk(g, cfg, splits, epi, s) : launch_config(cfg, g, epi, s);
+  }
+  if (g_force_tile >= 0 && !(g_force_tile >= 9 && g_force_tile <= 10 && g.M > 64)) return launch_config(g_force_tile, g, epi, s);
   if (g.M <= 64) {
     // measured on MI355X: very wide outputs (the vocabulary head) re-read A too often in the
     // streaming kernel; mid-size outputs take 32 features per workgroup to halve A's L2 traffic
     const int64_t n_total = static_cast<int64_t>(g.N) * g.parts;
     if (n_total > 16384) return launch_config(g.M <= 32 ? 7 : 6, g, epi, s);
+    if (g.M > 16 && g.partial) {                        // LDS-staged tiles, K split across workgroups
+      const int cfg = g.M <= 32 ? 7 : 6;
+      const int splits = choose_splits(g, cfg == 6 ? 64 : 32, cfg == 6 ? 64 : 128, partial_floats);
+      if (splits > 1) return launch_splitk(g, cfg, splits, epi, s);
+    }
     return launch_skinny_any(g, epi, s, n_total >= 6144 ? 1 : 0);
   }
-  // Tile choice by how the tile count fills 256 CUs (2 workgroups of 128x128x64 each, 3 of 128x128x32):
   const int t_big = ((g.M + 255) / 256) * ((g.N + 127) / 128) * g.parts;
   if (t_big >= 512) return launch_config(2, g, epi, s);            // plenty of work: 256x128 tiles, 128x64 per wave
+  // Tile choice by how the tile count fills 256 CUs (2 workgroups of 128x128x64 each, 3 of 128x128x32):
   const int t0 = ((g.M + 127) / 128) * ((g.N + 127) / 128) * g.parts;
   if (t0 <= 128) return launch_config(6, g, epi, s);               // few tiles: 64x64
   if (t0 <= 320) return launch_config(1, g, epi, s);               // under one round: 128x64 doubles the count
@@ -363,26 +452,26 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s) {
 }  // namespace
 
 int gemm_force_tile(int cfg) {
-  if (cfg < -1 || cfg > 13) return -1;
+  if (cfg < -1 || cfg > 15) return -1;
   g_force_tile = cfg;
   return 0;
 }
 
 hipError_t launch_gemm(const _Float16* A, const _Float16* W, const _Float16* bias, void* out, int M, int N,
-                       int K, int epi, hipStream_t s) {
+                       int K, int epi, hipStream_t s, float* partial, size_t partial_floats) {
   GemmArgs g{};
   g.A = A; g.W[0] = W; g.bias[0] = bias; g.out = out;
-  g.M = M; g.N = N; g.K = K; g.ldc = N; g.parts = 1;
-  return dispatch(g, epi, s);
+  g.M = M; g.N = N; g.K = K; g.ldc = N; g.parts = 1; g.splits = 1; g.partial = partial;
+  return dispatch(g, epi, s, partial_floats);
 }
 
 hipError_t launch_gemm3(const _Float16* A, const _Float16* const W[3], const _Float16* const bias[3], void* out,
-                        int M, int N, int K, int epi, hipStream_t s) {
+                        int M, int N, int K, int epi, hipStream_t s, float* partial, size_t partial_floats) {
   GemmArgs g{};
   g.A = A; g.out = out;
   for (int p = 0; p < 3; ++p) { g.W[p] = W[p]; g.bias[p] = bias[p]; }
-  g.M = M; g.N = N; g.K = K; g.ldc = 3 * N; g.parts = 3;
-  return dispatch(g, epi, s);
+  g.M = M; g.N = N; g.K = K; g.ldc = 3 * N; g.parts = 3; g.splits = 1; g.partial = partial;
+  return dispatch(g, epi, s, partial_floats);
 }
 
 }  // namespace ctn

@@ -1,6 +1,7 @@
 // Internal launch interface of the HIP kernels (not part of the C ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <cstddef>
 #include <cstdint>
 
 namespace ctn {
@@ -30,13 +31,16 @@ hipError_t launch_layernorm(const float* x, const _Float16* g, const _Float16* b
                             int hidden, hipStream_t s);
 
 // ---- dense products ------------------------------------------------------------
+// partial / partial_floats: optional fp32 scratch (device) that allows small-M products to split K
+// across workgroups; nullptr keeps every product in one pass.
 hipError_t launch_gemm(const _Float16* A, const _Float16* W, const _Float16* bias, void* out, int M, int N,
-                       int K, int epilogue, hipStream_t s);
+                       int K, int epilogue, hipStream_t s, float* partial = nullptr, size_t partial_floats = 0);
 // Test / tuning hook: force one tile configuration (0..8) for every product; -1 restores the heuristic.
 int gemm_force_tile(int cfg);
 // Three products sharing A in one launch: out[M, 3N] = [A W0^T + b0 | A W1^T + b1 | A W2^T + b2].
 hipError_t launch_gemm3(const _Float16* A, const _Float16* const W[3], const _Float16* const bias[3], void* out,
-                        int M, int N, int K, int epilogue, hipStream_t s);
+                        int M, int N, int K, int epilogue, hipStream_t s, float* partial = nullptr,
+                        size_t partial_floats = 0);
 hipError_t launch_attention(const _Float16* qkv, _Float16* out, int batch, int seq, int heads, int head_dim,
                             hipStream_t s);
 

@@ -9,6 +9,7 @@
 // Section 4 (LRU), Section 5.1 (per-tensor messages and their alpha cost).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <memory>
@@ -66,6 +67,8 @@ struct Activations {   // carved from the workspace for one inference of M token
   float* x;
   _Float16 *a, *qkv, *attn, *u;
   float* logits;
+  float* partial;            // split-K scratch for small batches (nullptr when M > 64)
+  uint64_t partial_floats;
   uint64_t bytes;
 };
 
@@ -129,6 +132,10 @@ uint64_t activation_bytes(const ctn_model_desc& d, int64_t M, bool with_logits, 
   const uint64_t o_ids = take(4ull * M), o_x = take(4ull * M * h), o_a = take(2ull * M * h),
                  o_qkv = take(2ull * M * 3 * hl), o_attn = take(2ull * M * hl), o_u = take(2ull * M * fl),
                  o_log = with_logits ? take(4ull * M * vl) : 0;
+  // up to 16 K-slices of the widest product that is ever split (not the vocabulary head)
+  const uint64_t widest = std::max<uint64_t>(std::max<uint64_t>(3 * hl, fl), h);
+  const uint64_t partial_floats = M <= 64 ? 16ull * M * widest : 0;
+  const uint64_t o_part = partial_floats ? take(4ull * partial_floats) : 0;
   if (out && base) {
     out->ids = reinterpret_cast<int32_t*>(base + o_ids);
     out->x = reinterpret_cast<float*>(base + o_x);
@@ -137,6 +144,8 @@ uint64_t activation_bytes(const ctn_model_desc& d, int64_t M, bool with_logits, 
     out->attn = reinterpret_cast<_Float16*>(base + o_attn);
     out->u = reinterpret_cast<_Float16*>(base + o_u);
     out->logits = with_logits ? reinterpret_cast<float*>(base + o_log) : nullptr;
+    out->partial = partial_floats ? reinterpret_cast<float*>(base + o_part) : nullptr;
+    out->partial_floats = partial_floats;
     out->bytes = cur;
   }
   return cur;
@@ -602,14 +611,14 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int3
     // q | k | v: three column-parallel projections of the same input in one launch
     const _Float16* const wqkv[3] = {T(Q_W), T(K_W), T(V_W)};
     const _Float16* const bqkv[3] = {T(Q_B), T(K_B), T(V_B)};
-    CTN_HIP(c, launch_gemm3(act.a, wqkv, bqkv, act.qkv, M, hl, h, CTN_EPI_BIAS_F16, s));
+    CTN_HIP(c, launch_gemm3(act.a, wqkv, bqkv, act.qkv, M, hl, h, CTN_EPI_BIAS_F16, s, act.partial, act.partial_floats));
     CTN_HIP(c, launch_attention(act.qkv, act.attn, batch, seq, L.local_heads(), L.head_dim(), s));
     // row parallel: this rank's partial sum joins the residual stream (the
     // cross-rank reduction is the identity on one GPU), bias added once
-    CTN_HIP(c, launch_gemm(act.attn, T(O_W), T(O_B), act.x, M, h, hl, CTN_EPI_BIAS_RESID_F32, s));
+    CTN_HIP(c, launch_gemm(act.attn, T(O_W), T(O_B), act.x, M, h, hl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats));
     CTN_HIP(c, launch_layernorm(act.x, T(LN2_W), T(LN2_B), act.a, M, h, s));
-    CTN_HIP(c, launch_gemm(act.a, T(FC1_W), T(FC1_B), act.u, M, fl, h, CTN_EPI_BIAS_RELU_F16, s));
-    CTN_HIP(c, launch_gemm(act.u, T(FC2_W), T(FC2_B), act.x, M, h, fl, CTN_EPI_BIAS_RESID_F32, s));
+    CTN_HIP(c, launch_gemm(act.a, T(FC1_W), T(FC1_B), act.u, M, fl, h, CTN_EPI_BIAS_RELU_F16, s, act.partial, act.partial_floats));
+    CTN_HIP(c, launch_gemm(act.u, T(FC2_W), T(FC2_B), act.x, M, h, fl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats));
   }
   CTN_HIP(c, launch_layernorm(act.x, dev_tensor<_Float16>(c, m, L.n_tensors - 2),
                               dev_tensor<_Float16>(c, m, L.n_tensors - 1), act.a, M, h, s));
@@ -927,6 +936,15 @@ int ctn_op_gemm(const void* A, const void* W, const void* bias, void* out, int32
   return op_rc(launch_gemm(static_cast<const _Float16*>(A), static_cast<const _Float16*>(W),
                            static_cast<const _Float16*>(bias), out, M, N, K, epilogue,
                            static_cast<hipStream_t>(stream)));
+}
+
+int ctn_op_gemm_ws(const void* A, const void* W, const void* bias, void* out, int32_t M, int32_t N, int32_t K,
+                   int32_t epilogue, void* workspace, uint64_t workspace_bytes, void* stream) {
+  if (!A || !W || !out || M < 0 || N < 0) return CTN_E_INVAL;
+  if (workspace && reinterpret_cast<uintptr_t>(workspace) % 16) return CTN_E_INVAL;
+  return op_rc(launch_gemm(static_cast<const _Float16*>(A), static_cast<const _Float16*>(W),
+                           static_cast<const _Float16*>(bias), out, M, N, K, epilogue,
+                           static_cast<hipStream_t>(stream), static_cast<float*>(workspace), workspace_bytes / 4));
 }
 
 int ctn_debug_gemm_tile(int32_t cfg) { return gemm_force_tile(cfg) == 0 ? CTN_OK : CTN_E_INVAL; }

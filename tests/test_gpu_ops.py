@@ -137,7 +137,7 @@ def test_attention(stream, batch, seq, heads, d):
     assert np.abs(got - want).mean() <= 4e-4 * np.abs(want).mean() + 1e-5
 
 
-@pytest.mark.parametrize("cfg", range(14))
+@pytest.mark.parametrize("cfg", range(16))
 @pytest.mark.parametrize("M,N,K,epi", [(300, 520, 328, P.EPI_BIAS_RESID_F32), (257, 129, 64, P.EPI_BIAS_RELU_F16),
                                        (61, 200, 1096, P.EPI_BIAS_F16), (9, 77, 40, P.EPI_F32)])
 def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
@@ -164,4 +164,42 @@ def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
     tol = 2.0 ** -10 * np.abs(want) + 1e-4 if out.dtype == torch.float16 else 1e-4
     assert np.all(np.abs(got - want) <= tol)
     with pytest.raises(P.CtnError):
-        B.debug_gemm_tile(14)
+        B.debug_gemm_tile(16)
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 4096, 8192), (64, 520, 1096), (17, 6144, 4096), (33, 200, 264), (48, 8192, 512)])
+@pytest.mark.parametrize("epi", [P.EPI_BIAS_F16, P.EPI_BIAS_RELU_F16, P.EPI_BIAS_RESID_F32, P.EPI_F32])
+@pytest.mark.parametrize("force", [-1, 14, 15])
+def test_gemm_split_k_with_workspace(stream, M, N, K, epi, force):
+    """Small-M products with a scratch buffer: K split across workgroups, partials added in order;
+    same bar as the one-pass product, and bit-identical when repeated."""
+    rng = np.random.default_rng(M + N + K + epi)
+    A, W, bias = f16(rng, (M, K)), f16(rng, (N, K), 0.05), f16(rng, N, 0.5)
+    res = rng.standard_normal((M, N)).astype(np.float32)
+    acc = A.astype(np.float64) @ W.astype(np.float64).T
+    if epi == P.EPI_BIAS_F16:
+        want, mk = acc + bias.astype(np.float64), lambda: torch.empty(M, N, dtype=torch.float16, device="cuda")
+    elif epi == P.EPI_BIAS_RELU_F16:
+        want, mk = np.maximum(acc + bias.astype(np.float64), 0), lambda: torch.empty(M, N, dtype=torch.float16, device="cuda")
+    elif epi == P.EPI_BIAS_RESID_F32:
+        want, mk = res + acc + bias.astype(np.float64), lambda: dev(res)
+    else:
+        want, mk = acc, lambda: torch.empty(M, N, dtype=torch.float32, device="cuda")
+    ws = torch.full((16 * M * N + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    outs = []
+    B.debug_gemm_tile(force)
+    try:
+        for _ in range(2):
+            out = mk()
+            B.op_gemm_ws(dev(A), dev(W), dev(bias), out, M, N, K, epi, ws, stream)
+            stream.synchronize()
+            outs.append(out.cpu().numpy())
+    finally:
+        B.debug_gemm_tile(-1)
+    assert np.array_equal(outs[0], outs[1])
+    got = outs[0].astype(np.float64)
+    scale = np.sqrt(K) * 0.05
+    if outs[0].dtype == np.float16:
+        assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.abs(want) + 1e-4 * scale + 1e-7)
+    else:
+        assert np.abs(got - want).max() <= 2e-5 * scale * max(1.0, np.log2(K)) + 1e-6 * np.abs(want).max()
