@@ -199,6 +199,10 @@ int ctn_last_swap_ms(ctn_ctx* ctx, ctn_model m, float* in_ms, float* out_ms, flo
 int ctn_debug_read_param(ctn_ctx* ctx, ctn_model m, int32_t index, void* dst_host, uint64_t cap);
 /* The three streams in use (hipStream_t), the library's own or the caller's. */
 int ctn_get_streams(ctn_ctx* ctx, void** compute, void** h2d, void** d2h);
+/* Library-owned streams only: replay captured HIP graphs for inferences on completely resident
+ * models while the link is idle; 0 (the default: replay measured no faster than direct launches
+ * on ROCm 7.2) launches every kernel directly. */
+int ctn_set_graphs(ctn_ctx* ctx, int32_t enable);
 /* Changes transfer mode / pipelining / copy-kernel width between operations. */
 int ctn_set_mode(ctn_ctx* ctx, int32_t transfer_mode, int32_t pipeline, int32_t copy_blocks);
 /* HIP status behind the last CTN_E_HIP of this context (ctx == NULL: of calls that take no context). */

@@ -16,7 +16,7 @@ DECLARED_SYMBOLS = [
     "ctn_create", "ctn_destroy", "ctn_host_alloc", "ctn_host_free", "ctn_register_model",
     "ctn_swap_in", "ctn_swap_out", "ctn_wait", "ctn_sync", "ctn_infer", "ctn_workspace_bytes",
     "ctn_arena_bytes", "ctn_is_resident", "ctn_get_stats", "ctn_get_events", "ctn_last_swap_ms",
-    "ctn_debug_read_param", "ctn_get_streams", "ctn_set_mode", "ctn_last_hip_error", "ctn_strerror",
+    "ctn_debug_read_param", "ctn_get_streams", "ctn_set_graphs", "ctn_set_mode", "ctn_last_hip_error", "ctn_strerror",
     "ctn_residency_replay", "ctn_op_copy", "ctn_op_dma", "ctn_op_embed", "ctn_op_layernorm",
     "ctn_op_gemm", "ctn_op_gemm_ws", "ctn_op_attention", "ctn_debug_gemm_tile", "ctn_engine_create", "ctn_engine_destroy",
     "ctn_engine_submit", "ctn_engine_step", "ctn_engine_pending", "ctn_engine_replay",
@@ -99,6 +99,7 @@ def lib() -> C.CDLL:
         "ctn_last_swap_ms": (C.c_int, [vp, i32, P(C.c_float), P(C.c_float), P(C.c_float), i32, P(i32)]),
         "ctn_debug_read_param": (C.c_int, [vp, i32, i32, vp, u64]),
         "ctn_get_streams": (C.c_int, [vp, P(vp), P(vp), P(vp)]),
+        "ctn_set_graphs": (C.c_int, [vp, i32]),
         "ctn_set_mode": (C.c_int, [vp, i32, i32, i32]),
         "ctn_last_hip_error": (C.c_int, [vp]),
         "ctn_strerror": (C.c_char_p, [C.c_int]),
@@ -367,6 +368,9 @@ class Context:
         self._check(lib().ctn_debug_read_param(self.h, m, index, dst.ctypes.data, dst.nbytes),
                     "ctn_debug_read_param")
         return dst
+
+    def set_graphs(self, enable: bool):
+        self._check(lib().ctn_set_graphs(self.h, int(bool(enable))), "ctn_set_graphs")
 
     def set_mode(self, transfer_mode: int, pipeline: bool, copy_blocks: int = 0):
         self._check(lib().ctn_set_mode(self.h, transfer_mode, int(bool(pipeline)), copy_blocks), "ctn_set_mode")

@@ -58,8 +58,7 @@ struct GemmArgs {
 constexpr int EPI_PARTIAL = 100;   // internal epilogue: store the raw accumulator into the slice's partial buffer
 
 template <int BM, int BN, int BK, int WM, int WN, int EPI>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, (WM * WN > 64 * 64 && WM * WN <= 128 * 64 && 4 * (BM + BN) * (BK + 8) <= 80 * 1024) ? 2 : 1)
-void gemm_nt_kernel(const GemmArgs g) {
+__device__ __forceinline__ void gemm_nt_body(const GemmArgs& g) {
   constexpr int THREADS = (BM / WM) * (BN / WN) * 64;
   constexpr int LDS_ROW = BK + LDS_PAD;
   constexpr int LPR = BK / 8;          // 16-byte lanes per tile row in the cooperative load
@@ -193,11 +192,31 @@ void gemm_nt_kernel(const GemmArgs g) {
   }
 }
 
+// Two entry points over the same body: with and without an explicit target of two wavefronts
+// per SIMD (at most 256 VGPRs).
+template <int BM, int BN, int BK, int WM, int WN, int EPI>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_nt_kernel(const GemmArgs g) {
+  gemm_nt_body<BM, BN, BK, WM, WN, EPI>(g);
+}
+template <int BM, int BN, int BK, int WM, int WN, int EPI>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_nt_kernel_occ2(const GemmArgs g) {
+  gemm_nt_body<BM, BN, BK, WM, WN, EPI>(g);
+}
+
 template <int BM, int BN, int BK, int WM, int WN>
 hipError_t launch_tiles(const GemmArgs& g, int epi, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * g.parts * g.splits;
   const dim3 grid(tiles), block((BM / WM) * (BN / WN) * 64);
-#define CTN_GEMM(E) hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g)
+  // two wavefronts per SIMD is what LDS allows anyway for these shapes (two 4-wave workgroups of up to
+  // 80 KiB, or one 8-wave workgroup); stating it keeps the register allocation at or below 256
+  constexpr int kWaves = (BM / WM) * (BN / WN);
+  constexpr bool kOcc2 = WM * WN >= 64 * 64 && WM * WN <= 128 * 64 &&
+                         ((kWaves == 4 && 4 * (BM + BN) * (BK + 8) <= 80 * 1024) || kWaves == 8);
+#define CTN_GEMM(E)                                                                                  \
+  do {                                                                                               \
+    if (kOcc2) hipLaunchKernelGGL((gemm_nt_kernel_occ2<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g); \
+    else hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g);          \
+  } while (0)
   switch (epi) {
     case EPI_PARTIAL: CTN_GEMM(EPI_PARTIAL); break;
     case CTN_EPI_BIAS_F16: CTN_GEMM(CTN_EPI_BIAS_F16); break;
@@ -445,7 +464,10 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
   const int t0 = ((g.M + 127) / 128) * ((g.N + 127) / 128) * g.parts;
   if (t0 <= 128) return launch_config(6, g, epi, s);               // few tiles: 64x64
   if (t0 <= 320) return launch_config(1, g, epi, s);               // under one round: 128x64 doubles the count
-  if (t0 > 512 && t0 <= 768) return launch_config(5, g, epi, s);   // between one and two rounds: 3 per CU
+  // 128x128x64 runs two workgroups per CU (512 per round), 128x128x32 three (768 per round, each
+  // round about 1.25 times as long): take the one with the cheaper last, partly filled round
+  const int rounds64 = (t0 + 511) / 512, rounds32 = (t0 + 767) / 768;
+  if (4 * rounds64 > 5 * rounds32) return launch_config(5, g, epi, s);
   return launch_config(0, g, epi, s);
 }
 

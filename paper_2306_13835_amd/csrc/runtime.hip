@@ -51,15 +51,29 @@ struct Model {
   bool load_recorded = false, out_recorded = false;
   bool pending_in = false, pending_out = false;
 
+  // Captured forward passes of this placement (see forward_graph).
+  struct Graph { uint64_t arena_off; int batch, seq; float* logits; hipGraphExec_t exec; };
+  std::vector<Graph> graphs;
+  void drop_graphs() {   // only when none of them can still be running
+    for (Graph& g : graphs) (void)hipGraphExecDestroy(g.exec);
+    graphs.clear();
+  }
+
   Model() = default;
   Model(const Model&) = delete;
   Model& operator=(const Model&) = delete;
   ~Model() {   // also runs when registration fails half way
+    drop_graphs();
     for (hipEvent_t e : ev_block)
       if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : {ev_in_start, ev_out_start, ev_out_done, ev_last_use})
       if (e) (void)hipEventDestroy(e);
   }
+};
+
+struct RetiredGraphs {   // captured forward passes of an evicted placement; destroyed once `done` has passed
+  std::vector<hipGraphExec_t> execs;
+  hipEvent_t done;
 };
 
 struct Activations {   // carved from the workspace for one inference of M tokens
@@ -82,12 +96,14 @@ struct ctn_ctx {
   // start while the link is quiet (all compute units, no copy wavefronts to avoid).
   hipStream_t s_wide = nullptr;
   hipStream_t last_compute = nullptr;
+  bool use_graphs = false;           // replay captured forward passes on the unmasked stream
   hipEvent_t ev_compute_done = nullptr;
   Residency res{0};
   RangeAllocator arena;
   std::vector<std::unique_ptr<Model>> models;
   std::vector<PendingRelease> pending;
   std::vector<int> deferred;         // evicted models whose offload is not enqueued yet
+  std::vector<RetiredGraphs> retired;
   std::vector<ctn_event> events;
   ctn_stats stats{};
   int last_hip = 0;
@@ -151,6 +167,38 @@ uint64_t activation_bytes(const ctn_model_desc& d, int64_t M, bool with_logits, 
   return cur;
 }
 
+// Graph executables of a placement that is being given up may still be running:
+// they are parked behind an event on the stream that replays them.
+void retire_graphs(ctn_ctx* c, Model* m) {
+  if (m->graphs.empty()) return;
+  RetiredGraphs r;
+  for (Model::Graph& g : m->graphs) r.execs.push_back(g.exec);
+  m->graphs.clear();
+  r.done = nullptr;
+  if (hipEventCreateWithFlags(&r.done, hipEventDisableTiming) != hipSuccess ||
+      hipEventRecord(r.done, c->s_wide) != hipSuccess) {
+    (void)hipGetLastError();
+    if (r.done) (void)hipEventDestroy(r.done);
+    r.done = nullptr;                // destroyed at the next full synchronisation instead
+  }
+  c->retired.push_back(std::move(r));
+}
+
+void purge_retired(ctn_ctx* c, bool all) {
+  for (size_t i = 0; i < c->retired.size();) {
+    RetiredGraphs& r = c->retired[i];
+    const bool done = all || (r.done && hipEventQuery(r.done) == hipSuccess);
+    if (!done) {
+      (void)hipGetLastError();
+      ++i;
+      continue;
+    }
+    for (hipGraphExec_t e : r.execs) (void)hipGraphExecDestroy(e);
+    if (r.done) (void)hipEventDestroy(r.done);
+    c->retired.erase(c->retired.begin() + i);
+  }
+}
+
 // Eviction happens in two steps so that, on a miss, the load of the requested
 // model and its forward pass can be enqueued before the (latency-insensitive)
 // offload of the victims: evict_logical() updates the bookkeeping and frees
@@ -159,6 +207,7 @@ uint64_t activation_bytes(const ctn_model_desc& d, int64_t M, bool with_logits, 
 void evict_logical(ctn_ctx* c, int mi) {
   Model* m = c->models[mi].get();
   m->resident = false;
+  retire_graphs(c, m);               // they point into the range being given up
   m->offload_enqueued = false;
   m->out_off = m->arena_off;
   c->arena.release(m->arena_off, m->lay.arena_bytes);
@@ -234,6 +283,7 @@ int ensure_resident(ctn_ctx* c, int mi) {
   if (L.param_bytes > c->res.budget() || L.arena_bytes > c->cfg.arena_bytes) return CTN_E_TOO_BIG;
   int rc = flush_deferred(c);
   if (rc) return rc;
+  purge_retired(c, false);
   // Forget offloads that have finished; the others still read their old ranges.
   for (size_t i = 0; i < c->pending.size();) {
     if (hipEventQuery(c->pending[i].done) == hipSuccess) {
@@ -348,6 +398,8 @@ int create_partitioned_streams(ctn_ctx* c, int copy_cus) {
   CTN_HIP(c, hipStreamCreateWithFlags(&c->s_wide, hipStreamNonBlocking));
   CTN_HIP(c, hipEventCreateWithFlags(&c->ev_compute_done, hipEventDisableTiming));
   c->own_streams = true;
+  c->use_graphs = false;   // measured on ROCm 7.2 / MI355X: replay is no faster than direct launches (the
+                           // time between the ~400 small kernels is spent on the device, not on the host)
   return CTN_OK;
 }
 
@@ -371,6 +423,85 @@ bool link_quiet(ctn_ctx* c) {
 template <typename T>
 T* dev_tensor(ctn_ctx* c, Model* m, int ti) {
   return reinterpret_cast<T*>(static_cast<char*>(c->cfg.arena_dev) + m->arena_off + m->lay.offset[ti]);
+}
+
+// The launch sequence of one forward pass on stream s.  with_waits: wait for the
+// transfer blocks' events (not needed, and not capturable across loads, when the
+// model is known to be completely resident).
+int forward_launches(ctn_ctx* c, Model* m, const Activations& act, int batch, int seq, float* logits, hipStream_t s,
+                     bool with_waits) {
+  const ShardLayout& L = m->lay;
+  const ctn_model_desc& d = L.d;
+  const int M = batch * seq;
+  const int h = d.hidden, hl = L.hl(), fl = L.fl(), vl = L.vl();
+  // The paper's rule (Section 3.2): a batch runs only on a fully loaded
+  // model.  With pipelining the same rule is applied per transfer block.
+  if (with_waits) {
+    if (!c->cfg.pipeline) CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block.back(), 0));
+    else CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block[0], 0));
+  }
+
+  const _Float16* tok = dev_tensor<_Float16>(c, m, 0);
+  CTN_HIP(c, launch_embed(act.ids, tok, dev_tensor<_Float16>(c, m, 1), act.x, M, seq, h, vl, d.rank, s));
+  for (int l = 0; l < d.layers; ++l) {
+    if (with_waits && c->cfg.pipeline) CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block[1 + l], 0));
+    auto T = [&](int w) { return dev_tensor<_Float16>(c, m, L.layer_tensor(l, w)); };
+    CTN_HIP(c, launch_layernorm(act.x, T(LN1_W), T(LN1_B), act.a, M, h, s));
+    // q | k | v: three column-parallel projections of the same input in one launch
+    const _Float16* const wqkv[3] = {T(Q_W), T(K_W), T(V_W)};
+    const _Float16* const bqkv[3] = {T(Q_B), T(K_B), T(V_B)};
+    CTN_HIP(c, launch_gemm3(act.a, wqkv, bqkv, act.qkv, M, hl, h, CTN_EPI_BIAS_F16, s, act.partial, act.partial_floats));
+    CTN_HIP(c, launch_attention(act.qkv, act.attn, batch, seq, L.local_heads(), L.head_dim(), s));
+    // row parallel: this rank's partial sum joins the residual stream (the
+    // cross-rank reduction is the identity on one GPU), bias added once
+    CTN_HIP(c, launch_gemm(act.attn, T(O_W), T(O_B), act.x, M, h, hl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats));
+    CTN_HIP(c, launch_layernorm(act.x, T(LN2_W), T(LN2_B), act.a, M, h, s));
+    CTN_HIP(c, launch_gemm(act.a, T(FC1_W), T(FC1_B), act.u, M, fl, h, CTN_EPI_BIAS_RELU_F16, s, act.partial, act.partial_floats));
+    CTN_HIP(c, launch_gemm(act.u, T(FC2_W), T(FC2_B), act.x, M, h, fl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats));
+  }
+  CTN_HIP(c, launch_layernorm(act.x, dev_tensor<_Float16>(c, m, L.n_tensors - 2),
+                              dev_tensor<_Float16>(c, m, L.n_tensors - 1), act.a, M, h, s));
+  CTN_HIP(c, launch_gemm(act.a, tok, nullptr, logits, M, vl, h, CTN_EPI_F32, s));   // tied head, vocabulary slice
+  return CTN_OK;
+}
+
+// Replays (capturing on first use) the forward pass of a completely resident model.
+int forward_graph(ctn_ctx* c, Model* m, const Activations& act, int batch, int seq, float* logits, hipStream_t s) {
+  for (const Model::Graph& g : m->graphs)
+    if (g.arena_off == m->arena_off && g.batch == batch && g.seq == seq && g.logits == logits) {
+      CTN_HIP(c, hipGraphLaunch(g.exec, s));
+      return CTN_OK;
+    }
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+  if (hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+    (void)hipGetLastError();
+    c->use_graphs = false;   // this runtime cannot capture here: keep launching directly
+    return forward_launches(c, m, act, batch, seq, logits, s, true);
+  }
+  const int rc = forward_launches(c, m, act, batch, seq, logits, s, false);
+  const hipError_t e_end = hipStreamEndCapture(s, &graph);
+  if (rc || e_end != hipSuccess || !graph) {
+    if (graph) (void)hipGraphDestroy(graph);
+    (void)hipGetLastError();
+    if (rc) return rc;
+    c->use_graphs = false;
+    return forward_launches(c, m, act, batch, seq, logits, s, true);
+  }
+  const hipError_t e_inst = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (e_inst != hipSuccess || !exec) {
+    (void)hipGetLastError();
+    c->use_graphs = false;
+    return forward_launches(c, m, act, batch, seq, logits, s, true);
+  }
+  if (m->graphs.size() >= 8) {           // bounded cache: drop the oldest capture
+    (void)hipGraphExecDestroy(m->graphs.front().exec);
+    m->graphs.erase(m->graphs.begin());
+  }
+  m->graphs.push_back({m->arena_off, batch, seq, logits, exec});
+  CTN_HIP(c, hipGraphLaunch(exec, s));
+  return CTN_OK;
 }
 
 }  // namespace
@@ -420,6 +551,7 @@ int ctn_sync(ctn_ctx* c) {
   CTN_HIP(c, hipStreamSynchronize(c->s_d2h));
   CTN_HIP(c, hipStreamSynchronize(c->s_compute));
   if (c->s_wide) CTN_HIP(c, hipStreamSynchronize(c->s_wide));
+  purge_retired(c, true);
   for (auto& m : c->models) m->pending_in = m->pending_out = false;
   c->pending.clear();
   return CTN_OK;
@@ -597,32 +729,16 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int3
   CTN_HIP(c, hipMemcpyAsync(act.ids, ids_host, 4ull * M, hipMemcpyHostToDevice, s));
   float* logits = out_is_device ? static_cast<float*>(logits_out) : act.logits;
 
-  // The paper's rule (Section 3.2): a batch runs only on a fully loaded
-  // model.  With pipelining the same rule is applied per transfer block.
-  if (!c->cfg.pipeline) CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block.back(), 0));
-  else CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block[0], 0));
-
-  const _Float16* tok = dev_tensor<_Float16>(c, m, 0);
-  CTN_HIP(c, launch_embed(act.ids, tok, dev_tensor<_Float16>(c, m, 1), act.x, M, seq, h, vl, d.rank, s));
-  for (int l = 0; l < d.layers; ++l) {
-    if (c->cfg.pipeline) CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block[1 + l], 0));
-    auto T = [&](int w) { return dev_tensor<_Float16>(c, m, L.layer_tensor(l, w)); };
-    CTN_HIP(c, launch_layernorm(act.x, T(LN1_W), T(LN1_B), act.a, M, h, s));
-    // q | k | v: three column-parallel projections of the same input in one launch
-    const _Float16* const wqkv[3] = {T(Q_W), T(K_W), T(V_W)};
-    const _Float16* const bqkv[3] = {T(Q_B), T(K_B), T(V_B)};
-    CTN_HIP(c, launch_gemm3(act.a, wqkv, bqkv, act.qkv, M, hl, h, CTN_EPI_BIAS_F16, s, act.partial, act.partial_floats));
-    CTN_HIP(c, launch_attention(act.qkv, act.attn, batch, seq, L.local_heads(), L.head_dim(), s));
-    // row parallel: this rank's partial sum joins the residual stream (the
-    // cross-rank reduction is the identity on one GPU), bias added once
-    CTN_HIP(c, launch_gemm(act.attn, T(O_W), T(O_B), act.x, M, h, hl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats));
-    CTN_HIP(c, launch_layernorm(act.x, T(LN2_W), T(LN2_B), act.a, M, h, s));
-    CTN_HIP(c, launch_gemm(act.a, T(FC1_W), T(FC1_B), act.u, M, fl, h, CTN_EPI_BIAS_RELU_F16, s, act.partial, act.partial_floats));
-    CTN_HIP(c, launch_gemm(act.u, T(FC2_W), T(FC2_B), act.x, M, h, fl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats));
+  // A resident model on an idle link needs no event waits: the whole launch
+  // sequence is captured once per (model placement, shape, output) as a HIP
+  // graph and replayed, which removes the per-launch host cost of ~400 small kernels.
+  const bool replayable = c->use_graphs && s == c->s_wide && !m->pending_in;
+  if (replayable) {
+    rc = forward_graph(c, m, act, batch, seq, logits, s);
+  } else {
+    rc = forward_launches(c, m, act, batch, seq, logits, s, true);
   }
-  CTN_HIP(c, launch_layernorm(act.x, dev_tensor<_Float16>(c, m, L.n_tensors - 2),
-                              dev_tensor<_Float16>(c, m, L.n_tensors - 1), act.a, M, h, s));
-  CTN_HIP(c, launch_gemm(act.a, tok, nullptr, logits, M, vl, h, CTN_EPI_F32, s));   // tied head, vocabulary slice
+  if (rc) return rc;
   CTN_HIP(c, hipEventRecord(m->ev_last_use, s));
   m->used_since_load = true;
   if (c->s_wide) {
@@ -717,6 +833,12 @@ int ctn_get_streams(ctn_ctx* c, void** compute, void** h2d, void** d2h) {
   if (compute) *compute = c->s_compute;
   if (h2d) *h2d = c->s_h2d;
   if (d2h) *d2h = c->s_d2h;
+  return CTN_OK;
+}
+
+int ctn_set_graphs(ctn_ctx* c, int32_t enable) {
+  if (!c) return CTN_E_INVAL;
+  c->use_graphs = enable && c->s_wide != nullptr;
   return CTN_OK;
 }
 

@@ -179,3 +179,35 @@ def test_full_size_shards_sampled_batch_rows(name, rows):
         assert np.array_equal(rig.tensors[m][4], keep)
     finally:
         rig.close()
+
+
+def test_graph_replay_equals_direct_launches_across_evictions():
+    """Resident inferences replay a captured graph: every replay, with other work and
+    synchronisations in between and after the model has moved to another arena range, must be
+    bit-identical to the directly launched forward pass."""
+    desc = ShardDesc(2, 256, 1024, 4, vocab=1000, max_pos=64)
+    size = shard_bytes(desc)
+    rig = Rig([desc] * 3, budget=2 * size, arena_bytes=3 * P.arena_bytes(desc), max_tokens=32, mode=P.XFER_AUTO)
+    try:
+        ms = [rig.add(desc, seed=90 + i) for i in range(3)]
+        ids = {(m, k): token_ids(400 + 10 * m + k, 2, 8 + 8 * k, desc.vocab) for m in ms for k in (0, 1)}
+        rig.ctx.set_graphs(False)
+        ref = {}
+        for key, x in ids.items():
+            ref[key] = rig.ctx.infer(key[0], x).copy()
+        rig.ctx.sync()
+        rig.ctx.set_graphs(True)
+        dev_out = torch.empty(2, 16, desc.vocab, dtype=torch.float32, device="cuda")
+        for rnd in range(4):
+            for key, x in ids.items():
+                for rep in range(3):                       # first call after a load captures, the rest replay
+                    got = rig.ctx.infer(key[0], x)
+                    assert np.array_equal(got, ref[key]), (rnd, key, rep)
+                if key[1] == 1:                            # device output: a different graph key
+                    rig.ctx.infer(key[0], x, out=dev_out)
+                    rig.ctx.sync()
+                    assert np.array_equal(dev_out.cpu().numpy(), ref[key])
+                torch.zeros(1024, device="cuda").sum().item()   # unrelated eager work + a synchronisation
+        assert rig.ctx.stats()["n_miss"] > 6               # the models really moved between rounds
+    finally:
+        rig.close()
