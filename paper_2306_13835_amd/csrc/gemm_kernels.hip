@@ -459,9 +459,19 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
     return launch_skinny_any(g, epi, s, n_total >= 6144 ? 1 : 0);
   }
   const int t_big = ((g.M + 255) / 256) * ((g.N + 127) / 128) * g.parts;
-  if (t_big >= 512) return launch_config(2, g, epi, s);            // plenty of work: 256x128 tiles, 128x64 per wave
+  if (t_big >= 512 && g.K <= 4096) return launch_config(2, g, epi, s);   // plenty of work: 256x128 tiles, 128x64 per wave
+                                                                          // (measured slower than 128x128 at K = 8192)
   // Tile choice by how the tile count fills 256 CUs (2 workgroups of 128x128x64 each, 3 of 128x128x32):
   const int t0 = ((g.M + 127) / 128) * ((g.N + 127) / 128) * g.parts;
+  if (g.partial && t0 <= 256 && g.K >= 4096) {
+    // at most one 128x128 tile per CU and a long K: two to four K slices fill the second workgroup
+    // slot of every CU; the ordered reduction costs one more small kernel
+    int splits = 512 / t0;
+    if (splits > 4) splits = 4;
+    const size_t per_slice = static_cast<size_t>(g.M) * g.N * g.parts;
+    if (splits > static_cast<int>(partial_floats / per_slice)) splits = static_cast<int>(partial_floats / per_slice);
+    if (splits >= 2) return launch_splitk(g, 0, splits, epi, s);
+  }
   if (t0 <= 128) return launch_config(6, g, epi, s);               // few tiles: 64x64
   if (t0 <= 320) return launch_config(1, g, epi, s);               // under one round: 128x64 doubles the count
   // 128x128x64 runs two workgroups per CU (512 per round), 128x128x32 three (768 per round, each

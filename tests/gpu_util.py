@@ -11,7 +11,7 @@ class Rig:
     """A context with its arena, workspace, streams and pinned host pool."""
 
     def __init__(self, descs, budget=None, max_tokens=64, arena_bytes=None, mode=P.XFER_KERNEL,
-                 pipeline=True, host_bytes=None, torch_streams=False):
+                 pipeline=True, host_bytes=None, torch_streams=False, gap=0):
         self.dev = torch.device("cuda:0")
         torch.cuda.set_device(0)
         streams = [torch.cuda.Stream() for _ in range(3)] if torch_streams else [None] * 3
@@ -23,13 +23,16 @@ class Rig:
         self.workspace = torch.empty(ws, dtype=torch.uint8, device=self.dev)
         torch.cuda.synchronize()
         self.ctx = P.Context(budget, self.arena, self.workspace, *streams, transfer_mode=mode, pipeline=pipeline)
-        host_bytes = host_bytes or sum(shard_bytes(d) + 256 * len(param_list(d)) for d in descs) + 4096
+        self.gap = gap     # bytes skipped between host tensors: > 0 makes every tensor its own region
+        host_bytes = host_bytes or sum(shard_bytes(d) + (256 + gap) * len(param_list(d)) for d in descs) + 4096
         self.pool = P.HostPool(host_bytes)
+        if gap:
+            self.pool.bytes[:] = 0     # so that tests can see a stray write between tensors
         self.descs = list(descs)
         self.models, self.tensors = [], []
 
     def add(self, desc, seed):
-        t = fill_shard(desc, seed, alloc=lambda shape: self.pool.take(shape))
+        t = fill_shard(desc, seed, alloc=lambda shape: self.pool.take(shape, gap=self.gap))
         m = self.ctx.register_model(desc, t)
         self.models.append(m)
         self.tensors.append(t)

@@ -24,10 +24,11 @@ def check_device_copy(rig, m, desc):
         assert np.array_equal(as_bytes(got), img.tensors[i]), f"tensor {i}"
 
 
+@pytest.mark.parametrize("gap", [0, 48, 4096])      # packed slab / tensors 48 B apart / separate regions
 @pytest.mark.parametrize("mode", [P.XFER_KERNEL, P.XFER_DMA, P.XFER_AUTO])
 @pytest.mark.parametrize("desc", [SMALL, SMALL_TP])
-def test_round_trip_scribble_and_poison(mode, desc):
-    rig = Rig([desc], mode=mode)
+def test_round_trip_scribble_and_poison(mode, desc, gap):
+    rig = Rig([desc], mode=mode, gap=gap)
     try:
         m = rig.add(desc, seed=5)
         orig = [t.copy() for t in rig.tensors[m]]
@@ -44,6 +45,12 @@ def test_round_trip_scribble_and_poison(mode, desc):
         assert not rig.ctx.is_resident(m)
         for t, o in zip(rig.tensors[m], orig):
             assert np.array_equal(as_bytes(t), as_bytes(o))
+        if gap:   # nothing may be written between the tensors
+            used = np.zeros(rig.pool.nbytes, dtype=bool)
+            for t in rig.tensors[m]:
+                off = t.ctypes.data - rig.pool.ptr
+                used[off:off + t.nbytes] = True
+            assert not rig.pool.bytes[~used].any()
         st = rig.ctx.stats()
         assert st["bytes_h2d"] == st["bytes_d2h"] == shard_bytes(desc)
         assert st["resident_bytes"] == 0 and st["peak_resident_bytes"] == shard_bytes(desc)
@@ -73,9 +80,10 @@ def test_dma_and_kernel_paths_leave_identical_arenas():
         rig.close()
 
 
-def test_many_cycles_any_order_keeps_host_bits():
+@pytest.mark.parametrize("gap", [0, 4096])
+def test_many_cycles_any_order_keeps_host_bits(gap):
     descs = [SMALL, SMALL_TP, SMALL]
-    rig = Rig(descs, budget=shard_bytes(SMALL) + shard_bytes(SMALL_TP) + 100)
+    rig = Rig(descs, budget=shard_bytes(SMALL) + shard_bytes(SMALL_TP) + 100, gap=gap)
     try:
         ms = [rig.add(d, seed=20 + i) for i, d in enumerate(descs)]
         orig = [[t.copy() for t in rig.tensors[m]] for m in ms]
