@@ -228,7 +228,7 @@ def run_swap(args):
         in_ms.append(i_ms)
         out_ms.append(o_ms)
         timed_blocks.append(list(blocks))
-    loads_by_kernel = args.transfer == "kernel" or (args.transfer == "auto" and args.host_layout == "separate")
+    loads_by_kernel = args.transfer == "kernel"   # "auto" switches to DMA while earlier offloads are running
     if loads_by_kernel:
         roof_blocks, roof_where = timed_blocks, "timed region (last load of each model)"
     else:

@@ -87,10 +87,10 @@ typedef struct {
   int32_t transfer_mode;     /* CTN_XFER_DMA: one hipMemcpyAsync per tensor (the paper's per-tensor
                                 messages, Section 5.1); CTN_XFER_KERNEL: one copy kernel per layer
                                 block; CTN_XFER_AUTO: loads of a host list in many separate pieces
-                                use the copy kernel, loads of a list whose tensors are back to
-                                back on the host use one DMA copy per run of adjacent tensors
-                                (the DMA engines' host reads keep their rate against a concurrent
-                                offload, kernel-issued reads lose about 40 %); offloads use DMA */
+                                use the copy kernel unless an earlier offload is still running
+                                (then, and for lists whose tensors lie back to back on the host,
+                                one DMA copy per run of adjacent tensors: the DMA engines share a
+                                link that is busy in both directions more evenly); offloads use DMA */
   int32_t pipeline;          /* 0: inference waits for the whole shard (the paper's rule, Section 3.2);
                                 1: inference waits layer by layer */
   int32_t copy_blocks;       /* workgroups of a copy kernel; 0 = library default */
