@@ -7,6 +7,7 @@
 #include <random>
 #include <vector>
 
+#include "engine.hpp"
 #include "residency.hpp"
 
 using ctn::RangeAllocator;
@@ -84,6 +85,26 @@ int main() {
       r.mark_resident(m);
     }
     assert(r.resident_bytes() <= 100 && r.peak_bytes() <= 100);
+  }
+  // request queues: oldest head first (ties: lower model), FIFO per model, pop respects the cap
+  {
+    ctn::RequestQueues q(3);
+    assert(q.pick() == -1 && q.pending() == 0);
+    int64_t id = 0;
+    const double ts[] = {5.0, 1.0, 1.0, 3.0, 0.5, 7.0};
+    const int model[] = {0, 2, 1, 1, 2, 0};
+    for (int i = 0; i < 6; ++i) q.push(model[i], ctn::QueuedRequest{id++, ts[i], {}});
+    assert(q.pending() == 6);
+    assert(q.pick() == 2);                        // head of queue 2 has timestamp 1.0 (0.5 is behind it)
+    auto b = q.pop(2, 8);
+    assert(b.size() == 2 && b[0].id == 1 && b[1].id == 4);
+    assert(q.pick() == 1);
+    b = q.pop(1, 1);
+    assert(b.size() == 1 && b[0].id == 2);
+    q.push_front(1, std::move(b[0]));             // a failed dispatch puts requests back in order
+    b = q.pop(1, 8);
+    assert(b.size() == 2 && b[0].id == 2 && b[1].id == 3);
+    assert(q.pick() == 0 && q.pop(0, 1)[0].id == 0 && q.pop(0, 1)[0].id == 5 && q.pick() == -1);
   }
   std::puts("host logic ok");
   return 0;
