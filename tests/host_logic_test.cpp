@@ -91,7 +91,7 @@ int main() {
     ctn::RequestQueues q(3);
     assert(q.pick() == -1 && q.pending() == 0);
     int64_t id = 0;
-    const double ts[] = {5.0, 1.0, 1.0, 3.0, 0.5, 7.0};
+    const double ts[] = {5.0, 1.0, 1.5, 3.0, 0.5, 7.0};
     const int model[] = {0, 2, 1, 1, 2, 0};
     for (int i = 0; i < 6; ++i) q.push(model[i], ctn::QueuedRequest{id++, ts[i], {}});
     assert(q.pending() == 6);
@@ -105,6 +105,9 @@ int main() {
     b = q.pop(1, 8);
     assert(b.size() == 2 && b[0].id == 2 && b[1].id == 3);
     assert(q.pick() == 0 && q.pop(0, 1)[0].id == 0 && q.pop(0, 1)[0].id == 5 && q.pick() == -1);
+    q.push(2, ctn::QueuedRequest{9, 4.0, {}});
+    q.push(1, ctn::QueuedRequest{10, 4.0, {}});
+    assert(q.pick() == 1);                        // equal timestamps: the lower model index wins
   }
   std::puts("host logic ok");
   return 0;
