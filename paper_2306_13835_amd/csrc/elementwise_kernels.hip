@@ -49,15 +49,17 @@ __device__ inline float wave_sum(float v) {
 // One 64-lane wavefront per row, the row held in registers (NV float4 per
 // lane): mean, then the mean of squared deviations (biased), both reduced
 // across the wavefront, then normalise, scale, shift, round to fp16.
-template <int NV>
-__global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ x,
-                                                        const _Float16* __restrict__ g,
+// FUSE: first finish a split-K product's residual update of this row (x += slices + bias, written
+// back to x), in the same order of additions as the stand-alone reduction.
+template <int NV, bool FUSE>
+__global__ __launch_bounds__(256) void layernorm_kernel(float* __restrict__ x, const _Float16* __restrict__ g,
                                                         const _Float16* __restrict__ b,
-                                                        _Float16* __restrict__ out, int rows, int hidden) {
+                                                        _Float16* __restrict__ out, int rows, int hidden,
+                                                        const PendingSum pend) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
-  const float4v* xr = reinterpret_cast<const float4v*>(x + static_cast<int64_t>(row) * hidden);
+  float4v* xr = reinterpret_cast<float4v*>(x + static_cast<int64_t>(row) * hidden);
   const int nvec = hidden / 4;
   float4v v[NV];
   float sum = 0.f;
@@ -66,6 +68,16 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
     const int c = lane + i * 64;
     if (c < nvec) {
       v[i] = xr[c];
+      if (FUSE) {
+        float4v t = {0.f, 0.f, 0.f, 0.f};
+        for (int sl = 0; sl < pend.splits; ++sl)
+          t += reinterpret_cast<const float4v*>(pend.partial + (static_cast<int64_t>(sl) * rows + row) * hidden)[c];
+        const half4 bb = reinterpret_cast<const half4*>(pend.bias)[c];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] += static_cast<float>(bb[e]);
+        v[i] += t;
+        xr[c] = v[i];
+      }
       sum += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
     } else {
       v[i] = float4v{0.f, 0.f, 0.f, 0.f};
@@ -112,13 +124,19 @@ hipError_t launch_embed(const int32_t* ids, const _Float16* tok, const _Float16*
   return hipGetLastError();
 }
 
-hipError_t launch_layernorm(const float* x, const _Float16* g, const _Float16* b, _Float16* out, int rows,
-                            int hidden, hipStream_t s) {
+hipError_t launch_layernorm(float* x, const _Float16* g, const _Float16* b, _Float16* out, int rows, int hidden,
+                            hipStream_t s, const PendingSum* pending) {
   if (rows <= 0) return hipSuccess;
   if (hidden % 4 || hidden <= 0 || hidden > 64 * 4 * 32) return hipErrorInvalidValue;
   const dim3 grid((rows + 3) / 4), block(256);
   const int nv = (hidden / 4 + 63) / 64;
-#define CTN_LN(NV) hipLaunchKernelGGL(layernorm_kernel<NV>, grid, block, 0, s, x, g, b, out, rows, hidden)
+  const bool fuse = pending && pending->splits > 0;
+  const PendingSum pend = fuse ? *pending : PendingSum{};
+#define CTN_LN(NV)                                                                                              \
+  do {                                                                                                          \
+    if (fuse) hipLaunchKernelGGL((layernorm_kernel<NV, true>), grid, block, 0, s, x, g, b, out, rows, hidden, pend);  \
+    else hipLaunchKernelGGL((layernorm_kernel<NV, false>), grid, block, 0, s, x, g, b, out, rows, hidden, pend); \
+  } while (0)
   if (nv <= 4) CTN_LN(4);
   else if (nv <= 8) CTN_LN(8);
   else if (nv <= 16) CTN_LN(16);

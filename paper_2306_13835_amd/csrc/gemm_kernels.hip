@@ -428,14 +428,24 @@ int choose_splits(const GemmArgs& g, int bm, int bn, size_t partial_floats) {
   return splits < 2 ? 1 : splits;
 }
 
-hipError_t launch_splitk(GemmArgs g, int cfg, int splits, int epi, hipStream_t s) {
+hipError_t launch_splitk(GemmArgs g, int cfg, int splits, int epi, hipStream_t s, PendingSum* defer) {
   g.splits = splits;
   hipError_t e = launch_config(cfg, g, EPI_PARTIAL, s);
   if (e != hipSuccess) return e;
+  if (defer && epi == CTN_EPI_BIAS_RESID_F32 && g.parts == 1 && g.ldc == g.N && g.M >= 256) {
+    // the caller's next kernel reads x anyway and finishes the update there (one wavefront per
+    // row: only worth it when there are many rows; with few rows and many slices the stand-alone
+    // reduction, which spreads over the whole chip, is faster: 4.3 against 6.1 ms per 1 x 64 forward)
+    defer->partial = g.partial;
+    defer->splits = splits;
+    defer->bias = g.bias[0];
+    return hipSuccess;
+  }
   return launch_splitk_reduce(g, epi, s);
 }
 
-hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_floats) {
+hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_floats, PendingSum* defer = nullptr) {
+  if (defer) *defer = PendingSum{};
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   if (g.K <= 0 || g.K % 8 || g.parts < 1 || g.parts > 3) return hipErrorInvalidValue;
   for (int p = 0; p < g.parts; ++p)
@@ -443,7 +453,7 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
   if (g_force_tile == 14 || g_force_tile == 15) {       // tuning hook: split-K over 64x64 / 32x128 tiles
     const int cfg = g_force_tile == 14 ? 6 : 7;
     const int splits = g.partial ? choose_splits(g, cfg == 6 ? 64 : 32, cfg == 6 ? 64 : 128, partial_floats) : 1;
-    return splits > 1 ? launch_splitk(g, cfg, splits, epi, s) : launch_config(cfg, g, epi, s);
+    return splits > 1 ? launch_splitk(g, cfg, splits, epi, s, defer) : launch_config(cfg, g, epi, s);
   }
   if (g_force_tile >= 0 && !(g_force_tile >= 9 && g_force_tile <= 10 && g.M > 64)) return launch_config(g_force_tile, g, epi, s);
   if (g.M <= 64) {
@@ -454,7 +464,7 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
     if (g.M > 16 && g.partial) {                        // LDS-staged tiles, K split across workgroups
       const int cfg = g.M <= 32 ? 7 : 6;
       const int splits = choose_splits(g, cfg == 6 ? 64 : 32, cfg == 6 ? 64 : 128, partial_floats);
-      if (splits > 1) return launch_splitk(g, cfg, splits, epi, s);
+      if (splits > 1) return launch_splitk(g, cfg, splits, epi, s, defer);
     }
     return launch_skinny_any(g, epi, s, n_total >= 6144 ? 1 : 0);
   }
@@ -470,7 +480,7 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
     if (splits > 4) splits = 4;
     const size_t per_slice = static_cast<size_t>(g.M) * g.N * g.parts;
     if (splits > static_cast<int>(partial_floats / per_slice)) splits = static_cast<int>(partial_floats / per_slice);
-    if (splits >= 2) return launch_splitk(g, 0, splits, epi, s);
+    if (splits >= 2) return launch_splitk(g, 0, splits, epi, s, defer);
   }
   if (t0 <= 128) return launch_config(6, g, epi, s);               // few tiles: 64x64
   if (t0 <= 320) return launch_config(1, g, epi, s);               // under one round: 128x64 doubles the count
@@ -490,11 +500,11 @@ int gemm_force_tile(int cfg) {
 }
 
 hipError_t launch_gemm(const _Float16* A, const _Float16* W, const _Float16* bias, void* out, int M, int N,
-                       int K, int epi, hipStream_t s, float* partial, size_t partial_floats) {
+                       int K, int epi, hipStream_t s, float* partial, size_t partial_floats, PendingSum* defer) {
   GemmArgs g{};
   g.A = A; g.W[0] = W; g.bias[0] = bias; g.out = out;
   g.M = M; g.N = N; g.K = K; g.ldc = N; g.parts = 1; g.splits = 1; g.partial = partial;
-  return dispatch(g, epi, s, partial_floats);
+  return dispatch(g, epi, s, partial_floats, defer);
 }
 
 hipError_t launch_gemm3(const _Float16* A, const _Float16* const W[3], const _Float16* const bias[3], void* out,

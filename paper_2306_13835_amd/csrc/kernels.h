@@ -24,17 +24,29 @@ enum { kCopyH2D = 0, kCopyD2H = 1, kCopyOther = 2 };
 hipError_t launch_copy_table(const CopyTable& t, int blocks, hipStream_t s, int dir);
 int default_copy_blocks();
 
+// A residual update that a split-K product has left undone: x[row][col] += sum over slices (in
+// slice order) of partial[slice][row][col] + bias[col].  splits == 0: nothing pending.
+struct PendingSum {
+  const float* partial = nullptr;
+  int splits = 0;
+  const _Float16* bias = nullptr;
+};
+
 // ---- elementwise -------------------------------------------------------------
 hipError_t launch_embed(const int32_t* ids, const _Float16* tok, const _Float16* pos, float* x, int M,
                         int seq, int hidden, int vocab_local, int rank, hipStream_t s);
-hipError_t launch_layernorm(const float* x, const _Float16* g, const _Float16* b, _Float16* out, int rows,
-                            int hidden, hipStream_t s);
+// pending (optional): apply that residual update to x (x is written back) before normalising.
+hipError_t launch_layernorm(float* x, const _Float16* g, const _Float16* b, _Float16* out, int rows, int hidden,
+                            hipStream_t s, const PendingSum* pending = nullptr);
 
 // ---- dense products ------------------------------------------------------------
 // partial / partial_floats: optional fp32 scratch (device) that allows small-M products to split K
 // across workgroups; nullptr keeps every product in one pass.
+// defer (optional, residual epilogue only): when the product is split, leave the summation of the
+// slices and the residual update to the caller (*defer describes it) instead of running the reduce kernel.
 hipError_t launch_gemm(const _Float16* A, const _Float16* W, const _Float16* bias, void* out, int M, int N,
-                       int K, int epilogue, hipStream_t s, float* partial = nullptr, size_t partial_floats = 0);
+                       int K, int epilogue, hipStream_t s, float* partial = nullptr, size_t partial_floats = 0,
+                       PendingSum* defer = nullptr);
 // Test / tuning hook: force one tile configuration (0..8) for every product; -1 restores the heuristic.
 int gemm_force_tile(int cfg);
 // Three products sharing A in one launch: out[M, 3N] = [A W0^T + b0 | A W1^T + b1 | A W2^T + b2].

@@ -452,12 +452,14 @@ int forward_launches(ctn_ctx* c, Model* m, const Activations& act, int batch, in
     else CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block[0], 0));
   }
 
+  // A split-K row-parallel product leaves its residual update to the LayerNorm that follows it.
+  PendingSum pend;
   const _Float16* tok = dev_tensor<_Float16>(c, m, 0);
   CTN_HIP(c, launch_embed(act.ids, tok, dev_tensor<_Float16>(c, m, 1), act.x, M, seq, h, vl, d.rank, s));
   for (int l = 0; l < d.layers; ++l) {
     if (with_waits && c->cfg.pipeline) CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block[1 + l], 0));
     auto T = [&](int w) { return dev_tensor<_Float16>(c, m, L.layer_tensor(l, w)); };
-    CTN_HIP(c, launch_layernorm(act.x, T(LN1_W), T(LN1_B), act.a, M, h, s));
+    CTN_HIP(c, launch_layernorm(act.x, T(LN1_W), T(LN1_B), act.a, M, h, s, &pend));
     // q | k | v: three column-parallel projections of the same input in one launch
     const _Float16* const wqkv[3] = {T(Q_W), T(K_W), T(V_W)};
     const _Float16* const bqkv[3] = {T(Q_B), T(K_B), T(V_B)};
@@ -465,13 +467,13 @@ int forward_launches(ctn_ctx* c, Model* m, const Activations& act, int batch, in
     CTN_HIP(c, launch_attention(act.qkv, act.attn, batch, seq, L.local_heads(), L.head_dim(), s));
     // row parallel: this rank's partial sum joins the residual stream (the
     // cross-rank reduction is the identity on one GPU), bias added once
-    CTN_HIP(c, launch_gemm(act.attn, T(O_W), T(O_B), act.x, M, h, hl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats));
-    CTN_HIP(c, launch_layernorm(act.x, T(LN2_W), T(LN2_B), act.a, M, h, s));
+    CTN_HIP(c, launch_gemm(act.attn, T(O_W), T(O_B), act.x, M, h, hl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats, &pend));
+    CTN_HIP(c, launch_layernorm(act.x, T(LN2_W), T(LN2_B), act.a, M, h, s, &pend));
     CTN_HIP(c, launch_gemm(act.a, T(FC1_W), T(FC1_B), act.u, M, fl, h, CTN_EPI_BIAS_RELU_F16, s, act.partial, act.partial_floats));
-    CTN_HIP(c, launch_gemm(act.u, T(FC2_W), T(FC2_B), act.x, M, h, fl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats));
+    CTN_HIP(c, launch_gemm(act.u, T(FC2_W), T(FC2_B), act.x, M, h, fl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats, &pend));
   }
   CTN_HIP(c, launch_layernorm(act.x, dev_tensor<_Float16>(c, m, L.n_tensors - 2),
-                              dev_tensor<_Float16>(c, m, L.n_tensors - 1), act.a, M, h, s));
+                              dev_tensor<_Float16>(c, m, L.n_tensors - 1), act.a, M, h, s, &pend));
   CTN_HIP(c, launch_gemm(act.a, tok, nullptr, logits, M, vl, h, CTN_EPI_F32, s));   // tied head, vocabulary slice
   return CTN_OK;
 }
@@ -1059,7 +1061,7 @@ int ctn_op_embed(const int32_t* ids, const void* tok, const void* pos, float* x,
 int ctn_op_layernorm(const float* x, const void* g, const void* b, void* out, int32_t rows, int32_t hidden,
                      void* stream) {
   if (!x || !g || !b || !out || rows < 0) return CTN_E_INVAL;
-  return op_rc(launch_layernorm(x, static_cast<const _Float16*>(g), static_cast<const _Float16*>(b),
+  return op_rc(launch_layernorm(const_cast<float*>(x), static_cast<const _Float16*>(g), static_cast<const _Float16*>(b),
                                 static_cast<_Float16*>(out), rows, hidden, static_cast<hipStream_t>(stream)));
 }
 
