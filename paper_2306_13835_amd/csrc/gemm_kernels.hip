@@ -214,7 +214,7 @@ hipError_t launch_tiles(const GemmArgs& g, int epi, hipStream_t s) {
                          ((kWaves == 4 && 4 * (BM + BN) * (BK + 8) <= 80 * 1024) || kWaves == 8);
 #define CTN_GEMM(E)                                                                                  \
   do {                                                                                               \
-    if (kOcc2) hipLaunchKernelGGL((gemm_nt_kernel_occ2<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g); \
+    if constexpr (kOcc2) hipLaunchKernelGGL((gemm_nt_kernel_occ2<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g); \
     else hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g);          \
   } while (0)
   switch (epi) {

@@ -738,7 +738,7 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int3
   hipStream_t s = c->s_compute;
   if (c->s_wide && link_quiet(c)) s = c->s_wide;
   if (c->last_compute && c->last_compute != s) CTN_HIP(c, hipStreamWaitEvent(s, c->ev_compute_done, 0));
-  const int h = d.hidden, hl = L.hl(), fl = L.fl(), vl = L.vl();
+  const int vl = L.vl();
   CTN_HIP(c, hipMemcpyAsync(act.ids, ids_host, 4ull * M, hipMemcpyHostToDevice, s));
   float* logits = out_is_device ? static_cast<float*>(logits_out) : act.logits;
 
