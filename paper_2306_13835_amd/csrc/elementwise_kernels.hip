@@ -46,26 +46,42 @@ __device__ inline float wave_sum(float v) {
   return v;
 }
 
-// One 64-lane wavefront per row, the row held in registers (NV float4 per
-// lane): mean, then the mean of squared deviations (biased), both reduced
-// across the wavefront, then normalise, scale, shift, round to fp16.
-// FUSE: first finish a split-K product's residual update of this row (x += slices + bias, written
-// back to x), in the same order of additions as the stand-alone reduction.
-template <int NV, bool FUSE>
-__global__ __launch_bounds__(256) void layernorm_kernel(float* __restrict__ x, const _Float16* __restrict__ g,
-                                                        const _Float16* __restrict__ b,
-                                                        _Float16* __restrict__ out, int rows, int hidden,
-                                                        const PendingSum pend) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
+// One workgroup of WAVES wavefronts per row, the row held in registers (NV
+// float4 per lane): mean, then the mean of squared deviations (biased), each
+// reduced across the wavefront by shuffles and across wavefronts through LDS,
+// then normalise, scale, shift, round to fp16.  Several wavefronts per row
+// keep enough loads in flight per CU when there are only a few thousand rows.
+// FUSE: first finish a split-K product's residual update of this row (x +=
+// slices + bias, written back to x), in the same order of additions as the
+// stand-alone reduction.
+template <int WAVES>
+__device__ inline float block_sum(float v, float* scratch) {
+  v = wave_sum(v);
+  if (WAVES == 1) return v;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();                       // scratch may still be read from the previous reduction
+  if (lane == 0) scratch[wave] = v;
+  __syncthreads();
+  float t = 0.f;
+#pragma unroll
+  for (int w = 0; w < WAVES; ++w) t += scratch[w];    // same order in every thread
+  return t;
+}
+
+template <int NV, int WAVES, bool FUSE>
+__global__ __launch_bounds__(WAVES * 64) void layernorm_kernel(float* __restrict__ x, const _Float16* __restrict__ g,
+                                                               const _Float16* __restrict__ b,
+                                                               _Float16* __restrict__ out, int rows, int hidden,
+                                                               const PendingSum pend) {
+  __shared__ float scratch[WAVES];
+  const int row = blockIdx.x;
   float4v* xr = reinterpret_cast<float4v*>(x + static_cast<int64_t>(row) * hidden);
   const int nvec = hidden / 4;
   float4v v[NV];
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    const int c = lane + i * 64;
+    const int c = threadIdx.x + i * WAVES * 64;
     if (c < nvec) {
       v[i] = xr[c];
       if (FUSE) {
@@ -83,11 +99,11 @@ __global__ __launch_bounds__(256) void layernorm_kernel(float* __restrict__ x, c
       v[i] = float4v{0.f, 0.f, 0.f, 0.f};
     }
   }
-  const float mean = wave_sum(sum) / static_cast<float>(hidden);
+  const float mean = block_sum<WAVES>(sum, scratch) / static_cast<float>(hidden);
   float sq = 0.f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    const int c = lane + i * 64;
+    const int c = threadIdx.x + i * WAVES * 64;
     if (c < nvec) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -96,12 +112,12 @@ __global__ __launch_bounds__(256) void layernorm_kernel(float* __restrict__ x, c
       }
     }
   }
-  const float var = wave_sum(sq) / static_cast<float>(hidden);
+  const float var = block_sum<WAVES>(sq, scratch) / static_cast<float>(hidden);
   const float inv = 1.0f / sqrtf(var + 1e-5f);
   _Float16* orow = out + static_cast<int64_t>(row) * hidden;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    const int c = lane + i * 64;
+    const int c = threadIdx.x + i * WAVES * 64;
     if (c < nvec) {
       const half4 gg = reinterpret_cast<const half4*>(g)[c];
       const half4 bb = reinterpret_cast<const half4*>(b)[c];
@@ -127,21 +143,22 @@ hipError_t launch_embed(const int32_t* ids, const _Float16* tok, const _Float16*
 hipError_t launch_layernorm(float* x, const _Float16* g, const _Float16* b, _Float16* out, int rows, int hidden,
                             hipStream_t s, const PendingSum* pending) {
   if (rows <= 0) return hipSuccess;
-  if (hidden % 4 || hidden <= 0 || hidden > 64 * 4 * 32) return hipErrorInvalidValue;
-  const dim3 grid((rows + 3) / 4), block(256);
-  const int nv = (hidden / 4 + 63) / 64;
+  if (hidden % 4 || hidden <= 0 || hidden > 256 * 4 * 8) return hipErrorInvalidValue;
   const bool fuse = pending && pending->splits > 0;
   const PendingSum pend = fuse ? *pending : PendingSum{};
-#define CTN_LN(NV)                                                                                              \
-  do {                                                                                                          \
-    if (fuse) hipLaunchKernelGGL((layernorm_kernel<NV, true>), grid, block, 0, s, x, g, b, out, rows, hidden, pend);  \
-    else hipLaunchKernelGGL((layernorm_kernel<NV, false>), grid, block, 0, s, x, g, b, out, rows, hidden, pend); \
+  const dim3 grid(rows);
+  const int nvec = hidden / 4;
+#define CTN_LN(NV, WAVES)                                                                                     \
+  do {                                                                                                        \
+    if (fuse) hipLaunchKernelGGL((layernorm_kernel<NV, WAVES, true>), grid, dim3(WAVES * 64), 0, s, x, g, b, out, rows, hidden, pend);  \
+    else hipLaunchKernelGGL((layernorm_kernel<NV, WAVES, false>), grid, dim3(WAVES * 64), 0, s, x, g, b, out, rows, hidden, pend); \
   } while (0)
-  if (nv <= 4) CTN_LN(4);
-  else if (nv <= 8) CTN_LN(8);
-  else if (nv <= 16) CTN_LN(16);
-  else if (nv <= 20) CTN_LN(20);
-  else CTN_LN(32);
+  if (nvec <= 64) CTN_LN(1, 1);            // up to 256 columns: one wavefront
+  else if (nvec <= 256) CTN_LN(1, 4);      // up to 1024 columns
+  else if (nvec <= 512) CTN_LN(2, 4);      // 2048
+  else if (nvec <= 1024) CTN_LN(4, 4);     // 4096
+  else if (nvec <= 1536) CTN_LN(6, 4);     // 5120, 6144
+  else CTN_LN(8, 4);                       // up to 8192
 #undef CTN_LN
   return hipGetLastError();
 }
