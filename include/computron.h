@@ -96,6 +96,14 @@ typedef struct {
   int32_t copy_blocks;       /* workgroups of a copy kernel; 0 = library default */
   int32_t copy_cus;          /* library-owned streams only: compute units reserved per transfer
                                 direction, at least 8 (one per XCD); 0 = library default */
+  int32_t block_residency;   /* 0: a model is resident or not as a whole (the paper's demand paging,
+                                Section 3).  1: residency per transfer block: what stays of a model
+                                is a prefix of its blocks (embeddings, then layer by layer); a miss
+                                evicts only as many blocks as it needs, from the tail of the least
+                                recently used model, and a later use of that model reloads just the
+                                missing tail while its forward pass starts on the prefix.  Every
+                                block then occupies one slot of ctn_slot_bytes() in the arena. */
+  int32_t reserved;
 } ctn_config;
 
 typedef struct {
@@ -105,6 +113,9 @@ typedef struct {
   uint64_t n_infer;
   uint64_t resident_bytes, peak_resident_bytes;
   uint64_t budget_bytes;
+  uint64_t n_partial_miss;             /* misses that found a prefix of the model resident (block residency) */
+  uint64_t n_extra_evictions;          /* eviction steps taken because no arena hole was wide enough
+                                          although the budget had room (not part of the policy) */
 } ctn_stats;
 
 /* Residency event, in the order decisions were taken (Section 3: replacement
@@ -116,6 +127,17 @@ typedef struct {
   int32_t n_victims;
   int32_t victims[13];
 } ctn_event;
+
+/* Block-level record of the same decisions: blocks [first_block, end_block) of
+ * `model` were loaded (kind 0) or evicted (kind 1) by use number `use` (index
+ * into the ctn_event log).  Evictions of one use come before its load, victims
+ * least recently used first. */
+typedef struct {
+  int32_t kind;
+  int32_t model;
+  int32_t first_block, end_block;
+  uint64_t use;
+} ctn_block_event;
 
 /* ---- life cycle ---------------------------------------------------------- */
 
@@ -179,15 +201,23 @@ int ctn_infer(ctn_ctx* ctx, ctn_model m, const int32_t* token_ids_host, int32_t 
 uint64_t ctn_workspace_bytes(const ctn_model_desc* desc, int64_t max_tokens, int32_t n_models);
 /* Arena bytes one shard of this description occupies (tensors padded to 256 B). */
 uint64_t ctn_arena_bytes(const ctn_model_desc* desc);
+/* Block residency: bytes of the arena slot each of the shard's layers+1 transfer
+ * blocks occupies (the widest block, padded), so a shard takes (layers+1) slots. */
+uint64_t ctn_slot_bytes(const ctn_model_desc* desc);
 
 /* ---- introspection -------------------------------------------------------- */
 
+/* *out = 1 when every block of the model is resident (or on its way in). */
 int ctn_is_resident(ctn_ctx* ctx, ctn_model m, int32_t* out);
+/* Number of resident transfer blocks (a prefix) and the model's block count. */
+int ctn_resident_blocks(ctn_ctx* ctx, ctn_model m, int32_t* resident, int32_t* total);
 int ctn_get_stats(ctn_ctx* ctx, ctn_stats* out);
 /* Copies up to cap events starting at index first into out (host); *n_out
  * receives the number copied, *total the number recorded so far. */
 int ctn_get_events(ctn_ctx* ctx, uint64_t first, ctn_event* out, uint64_t cap, uint64_t* n_out,
                    uint64_t* total);
+int ctn_get_block_events(ctn_ctx* ctx, uint64_t first, ctn_block_event* out, uint64_t cap, uint64_t* n_out,
+                         uint64_t* total);
 /* Device-timeline duration (ms) of the model's last completed load and
  * offload, and the start-to-event time of each of its layer blocks
  * (block_ms: host array of cap floats or NULL; blocks = layers + 1:
@@ -215,6 +245,15 @@ const char* ctn_strerror(int code);
  * and writes one event per use to out (host, n entries). */
 int ctn_residency_replay(uint64_t budget_bytes, const uint64_t* sizes, int32_t n_models,
                          const int32_t* trace, uint64_t n, ctn_event* out);
+
+/* The same for block residency: model i has n_blocks[i] blocks whose parameter
+ * bytes follow each other in block_bytes (host, sum of n_blocks entries).
+ * out receives one event per use (victims: models that lost blocks, least
+ * recently used first), blocks_out up to cap block-level records (*n_blocks_out
+ * = number produced; CTN_E_INVAL when cap is too small). */
+int ctn_block_residency_replay(uint64_t budget_bytes, const int32_t* n_blocks, const uint64_t* block_bytes,
+                               int32_t n_models, const int32_t* trace, uint64_t n, ctn_event* out,
+                               ctn_block_event* blocks_out, uint64_t cap, uint64_t* n_blocks_out);
 
 /* ---- serving engine (Section 3.1: per-model request queues, oldest first;
  *      Section 5.2: maximum batch size) ----------------------------------------- */

@@ -20,6 +20,7 @@ DECLARED_SYMBOLS = [
     "ctn_residency_replay", "ctn_op_copy", "ctn_op_dma", "ctn_op_embed", "ctn_op_layernorm",
     "ctn_op_gemm", "ctn_op_gemm_ws", "ctn_op_attention", "ctn_debug_gemm_tile", "ctn_engine_create", "ctn_engine_destroy",
     "ctn_engine_submit", "ctn_engine_step", "ctn_engine_pending", "ctn_engine_replay",
+    "ctn_slot_bytes", "ctn_resident_blocks", "ctn_get_block_events", "ctn_block_residency_replay",
 ]
 
 
@@ -37,18 +38,23 @@ class Config(C.Structure):
                 ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_uint64),
                 ("stream_compute", C.c_void_p), ("stream_h2d", C.c_void_p), ("stream_d2h", C.c_void_p),
                 ("transfer_mode", C.c_int32), ("pipeline", C.c_int32), ("copy_blocks", C.c_int32),
-                ("copy_cus", C.c_int32)]
+                ("copy_cus", C.c_int32), ("block_residency", C.c_int32), ("reserved", C.c_int32)]
 
 
 class Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("bytes_h2d", "bytes_d2h", "n_swap_in", "n_swap_out", "n_hit",
                                           "n_miss", "n_infer", "resident_bytes", "peak_resident_bytes",
-                                          "budget_bytes")]
+                                          "budget_bytes", "n_partial_miss", "n_extra_evictions")]
 
 
 class Event(C.Structure):
     _fields_ = [("kind", C.c_int32), ("model", C.c_int32), ("n_victims", C.c_int32),
                 ("victims", C.c_int32 * 13)]
+
+
+class BlockEvent(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("model", C.c_int32), ("first_block", C.c_int32), ("end_block", C.c_int32),
+                ("use", C.c_uint64)]
 
 
 class BatchRecord(C.Structure):
@@ -94,6 +100,11 @@ def lib() -> C.CDLL:
         "ctn_workspace_bytes": (u64, [P(ModelDesc), i64, i32]),
         "ctn_arena_bytes": (u64, [P(ModelDesc)]),
         "ctn_is_resident": (C.c_int, [vp, i32, P(i32)]),
+        "ctn_slot_bytes": (u64, [P(ModelDesc)]),
+        "ctn_resident_blocks": (C.c_int, [vp, i32, P(i32), P(i32)]),
+        "ctn_get_block_events": (C.c_int, [vp, u64, P(BlockEvent), u64, P(u64), P(u64)]),
+        "ctn_block_residency_replay": (C.c_int, [u64, P(i32), P(u64), i32, P(i32), u64, P(Event), P(BlockEvent), u64,
+                                                 P(u64)]),
         "ctn_get_stats": (C.c_int, [vp, P(Stats)]),
         "ctn_get_events": (C.c_int, [vp, u64, P(Event), u64, P(u64), P(u64)]),
         "ctn_last_swap_ms": (C.c_int, [vp, i32, P(C.c_float), P(C.c_float), P(C.c_float), i32, P(i32)]),
@@ -137,6 +148,33 @@ def workspace_bytes(desc, max_tokens: int, n_models: int = 1) -> int:
 
 def arena_bytes(desc) -> int:
     return int(lib().ctn_arena_bytes(C.byref(_desc(desc))))
+
+
+def slot_bytes(desc) -> int:
+    return int(lib().ctn_slot_bytes(C.byref(_desc(desc))))
+
+
+def _block_events_to_list(evs, n) -> List[Tuple[str, int, int, int, int]]:
+    kinds = ("load", "evict")
+    return [(kinds[e.kind], e.model, e.first_block, e.end_block, int(e.use)) for e in evs[:n]]
+
+
+def block_residency_replay(budget: int, block_bytes: Sequence[Sequence[int]], trace: Sequence[int]):
+    """Host-only replay of the block-granular policy: (events, block events)."""
+    n = len(trace)
+    nb = (C.c_int32 * len(block_bytes))(*[len(b) for b in block_bytes])
+    flat = [int(x) for b in block_bytes for x in b]
+    bb = (C.c_uint64 * len(flat))(*flat)
+    tr = (C.c_int32 * max(n, 1))(*[int(t) for t in trace])
+    out = (Event * max(n, 1))()
+    cap = max(n * (len(block_bytes) + 1), 1)
+    blocks = (BlockEvent * cap)()
+    n_out = C.c_uint64()
+    rc = lib().ctn_block_residency_replay(int(budget), nb, bb, len(block_bytes), tr, n, out, blocks, cap,
+                                          C.byref(n_out))
+    if rc:
+        raise CtnError(rc, "ctn_block_residency_replay")
+    return _events_to_list(out, n), _block_events_to_list(blocks, int(n_out.value))
 
 
 def _events_to_list(evs, n) -> List[Tuple[str, int, Tuple[int, ...]]]:
@@ -266,7 +304,7 @@ class Context:
 
     def __init__(self, budget: int, arena, workspace, stream_compute=None, stream_h2d=None, stream_d2h=None,
                  transfer_mode: int = XFER_KERNEL, pipeline: bool = True, copy_blocks: int = 0,
-                 copy_cus: int = 0):
+                 copy_cus: int = 0, block_residency: bool = False):
         """With no streams given the library creates its own three (CU-partitioned); they are
         exposed as `stream_compute`, `stream_h2d`, `stream_d2h` (torch ExternalStream)."""
         import torch
@@ -274,7 +312,8 @@ class Context:
         sp = [s.cuda_stream if s is not None else None for s in (stream_compute, stream_h2d, stream_d2h)]
         cfg = Config(int(budget), arena.data_ptr(), arena.numel() * arena.element_size(),
                      workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                     sp[0], sp[1], sp[2], transfer_mode, int(bool(pipeline)), copy_blocks, copy_cus)
+                     sp[0], sp[1], sp[2], transfer_mode, int(bool(pipeline)), copy_blocks, copy_cus,
+                     int(bool(block_residency)), 0)
         h = C.c_void_p()
         rc = lib().ctn_create(C.byref(cfg), C.byref(h))
         if rc:
@@ -339,6 +378,20 @@ class Context:
         o = C.c_int32()
         self._check(lib().ctn_is_resident(self.h, m, C.byref(o)), "ctn_is_resident")
         return bool(o.value)
+
+    def resident_blocks(self, m: int) -> Tuple[int, int]:
+        k, n = C.c_int32(), C.c_int32()
+        self._check(lib().ctn_resident_blocks(self.h, m, C.byref(k), C.byref(n)), "ctn_resident_blocks")
+        return k.value, n.value
+
+    def block_events(self, first: int = 0):
+        n, total = C.c_uint64(), C.c_uint64()
+        self._check(lib().ctn_get_block_events(self.h, 0, None, 0, C.byref(n), C.byref(total)), "ctn_get_block_events")
+        cap = max(int(total.value) - first, 0)
+        buf = (BlockEvent * max(cap, 1))()
+        self._check(lib().ctn_get_block_events(self.h, first, buf, cap, C.byref(n), C.byref(total)),
+                    "ctn_get_block_events")
+        return _block_events_to_list(buf, int(n.value))
 
     def stats(self) -> dict:
         s = Stats()

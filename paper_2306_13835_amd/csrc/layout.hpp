@@ -11,6 +11,7 @@
 // caller who stores a layer's tensors back to back on the host gets a device
 // image with the same spacing, so neighbouring tensors can travel as one copy.
 #pragma once
+#include <algorithm>
 #include <cstdint>
 #include <vector>
 
@@ -40,6 +41,9 @@ struct ShardLayout {
   std::vector<int> block_of;              // per tensor
   std::vector<std::vector<int>> block_tensors;  // per block: tensor indices in arena order
   std::vector<uint64_t> block_bytes;      // per block: parameter bytes
+  std::vector<uint64_t> block_start;      // per block: offset of its first tensor in the range
+  std::vector<uint64_t> block_span;       // per block: padded bytes from its start to the next block's
+  uint64_t slot_bytes = 0;                // widest block span: the unit of block-by-block placement
 
   int hl() const { return d.hidden / d.tp; }
   int fl() const { return d.ffn / d.tp; }
@@ -47,6 +51,8 @@ struct ShardLayout {
   int local_heads() const { return d.heads / d.tp; }
   int head_dim() const { return d.hidden / d.heads; }
   int layer_tensor(int layer, int which) const { return 2 + kLayerTensors * layer + which; }
+  // Offset of tensor t from the start of its own block (blocks may be placed one by one).
+  uint64_t offset_in_block(int t) const { return offset[t] - block_start[block_of[t]]; }
 };
 
 inline bool desc_valid(const ctn_model_desc& d) {
@@ -88,6 +94,8 @@ inline ShardLayout make_layout(const ctn_model_desc& d) {
   L.block_of.assign(L.n_tensors, 0);
   L.block_tensors.assign(L.n_blocks, {});
   L.block_bytes.assign(L.n_blocks, 0);
+  L.block_start.assign(L.n_blocks, 0);
+  L.block_span.assign(L.n_blocks, 0);
   for (int i = 0; i < L.n_tensors; ++i) {
     int64_t r, c;
     expected_shape(d, i, r, c);
@@ -97,6 +105,7 @@ inline ShardLayout make_layout(const ctn_model_desc& d) {
   uint64_t cur = 0;
   auto place = [&](int block, int t) {
     cur = align_up(cur);
+    if (L.block_tensors[block].empty()) L.block_start[block] = cur;
     L.offset[t] = cur;
     cur += L.nbytes[t];
     L.block_of[t] = block;
@@ -110,6 +119,11 @@ inline ShardLayout make_layout(const ctn_model_desc& d) {
   for (int l = 0; l < d.layers; ++l)
     for (int w = 0; w < kLayerTensors; ++w) place(1 + l, L.layer_tensor(l, w));
   L.arena_bytes = align_up(cur);
+  for (int b = 0; b < L.n_blocks; ++b) {
+    const uint64_t end = b + 1 < L.n_blocks ? L.block_start[b + 1] : L.arena_bytes;
+    L.block_span[b] = end - L.block_start[b];
+    L.slot_bytes = std::max(L.slot_bytes, L.block_span[b]);
+  }
   return L;
 }
 

@@ -16,54 +16,113 @@ namespace ctn {
 
 // Least-recently-used residency under a byte budget.  A "use" stamps the
 // model with a strictly increasing counter, so the order is total.
+//
+// A model is a list of transfer blocks and what is resident of it is a prefix
+// of that list.  In whole-model mode (the paper's) the prefix is all or
+// nothing.  In block mode an eviction step takes one block from the tail of
+// the least recently used model, so a miss frees no more than it needs and
+// the victim later reloads only its missing tail.
 class Residency {
  public:
-  explicit Residency(uint64_t budget) : budget_(budget) {}
+  struct Move {        // blocks [b0, b1) of `model` leave (or enter) device memory
+    int model, b0, b1;
+  };
 
-  int add_model(uint64_t bytes) {
-    size_.push_back(bytes);
+  explicit Residency(uint64_t budget, bool block_mode = false) : budget_(budget), block_mode_(block_mode) {}
+
+  int add_model(std::vector<uint64_t> block_bytes) {
+    uint64_t total = 0;
+    for (uint64_t b : block_bytes) total += b;
+    blocks_.push_back(std::move(block_bytes));
+    size_.push_back(total);
+    k_.push_back(0);
     stamp_.push_back(0);
     return static_cast<int>(size_.size()) - 1;
   }
+  int add_model(uint64_t bytes) { return add_model(std::vector<uint64_t>{bytes}); }
+
   int n_models() const { return static_cast<int>(size_.size()); }
-  bool resident(int m) const { return stamp_[m] != 0; }
+  int n_blocks(int m) const { return static_cast<int>(blocks_[m].size()); }
+  int resident_blocks(int m) const { return k_[m]; }
+  bool resident(int m) const { return k_[m] == n_blocks(m); }      // completely resident
+  bool block_mode() const { return block_mode_; }
   uint64_t size(int m) const { return size_[m]; }
   uint64_t budget() const { return budget_; }
   uint64_t resident_bytes() const { return resident_bytes_; }
   uint64_t peak_bytes() const { return peak_; }
+  uint64_t missing_bytes(int m) const {
+    uint64_t n = 0;
+    for (int b = k_[m]; b < n_blocks(m); ++b) n += blocks_[m][b];
+    return n;
+  }
 
-  // A use of a resident model.
+  // A use of a completely resident model.
   void touch(int m) { stamp_[m] = ++clock_; }
 
-  // The resident model used longest ago, other than `except`; -1 if none.
+  // The model with resident blocks that was used longest ago, other than `except`; -1 if none.
   int oldest(int except) const {
     int best = -1;
     uint64_t best_stamp = std::numeric_limits<uint64_t>::max();
     for (int i = 0; i < n_models(); ++i)
-      if (i != except && stamp_[i] != 0 && stamp_[i] < best_stamp) {
+      if (i != except && k_[i] > 0 && stamp_[i] < best_stamp) {
         best_stamp = stamp_[i];
         best = i;
       }
     return best;
   }
 
-  // True while model m (not resident) does not fit next to what is resident.
-  bool over_budget_with(int m) const { return resident_bytes_ + size_[m] > budget_; }
+  // True while the missing blocks of m do not fit next to what is resident.
+  bool over_budget_with(int m) const { return resident_bytes_ + missing_bytes(m) > budget_; }
 
-  void mark_resident(int m) {
-    stamp_[m] = ++clock_;
-    resident_bytes_ += size_[m];
-    peak_ = std::max(peak_, resident_bytes_);
+  // One eviction step on behalf of m: the least recently used other model
+  // loses its last block (block mode) or everything (whole-model mode).
+  // The move is merged into `out` (one entry per victim, in eviction order).
+  // Returns the victim, -1 when nothing is left to evict.
+  int evict_step(int m, std::vector<Move>& out) {
+    const int v = oldest(m);
+    if (v < 0) return -1;
+    const int hi = k_[v];
+    const int lo = block_mode_ ? hi - 1 : 0;
+    drop(v, lo);
+    for (Move& mv : out)
+      if (mv.model == v) {
+        mv.b0 = lo;
+        return v;
+      }
+    out.push_back({v, lo, hi});
+    return v;
   }
-  void mark_evicted(int m) {
-    stamp_[m] = 0;
-    resident_bytes_ -= size_[m];
+
+  // Everything resident of m leaves (explicit swap-out).  Returns the move; b0 == b1 when nothing was resident.
+  Move evict_all(int m) {
+    const Move mv{m, 0, k_[m]};
+    drop(m, 0);
+    return mv;
+  }
+
+  // The missing blocks of m have been given room: m is completely resident and just used.
+  Move load_missing(int m) {
+    const Move mv{m, k_[m], n_blocks(m)};
+    resident_bytes_ += missing_bytes(m);
+    k_[m] = n_blocks(m);
+    stamp_[m] = ++clock_;
+    peak_ = std::max(peak_, resident_bytes_);
+    return mv;
   }
 
  private:
+  void drop(int m, int new_k) {
+    for (int b = new_k; b < k_[m]; ++b) resident_bytes_ -= blocks_[m][b];
+    k_[m] = new_k;
+    if (new_k == 0) stamp_[m] = 0;
+  }
+
   uint64_t budget_;
+  bool block_mode_;
   uint64_t clock_ = 0, resident_bytes_ = 0, peak_ = 0;
+  std::vector<std::vector<uint64_t>> blocks_;
   std::vector<uint64_t> size_, stamp_;
+  std::vector<int> k_;
 };
 
 // First-fit allocator over the caller's arena, in bytes, with coalescing.

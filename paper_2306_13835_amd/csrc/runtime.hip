@@ -26,10 +26,15 @@ using namespace ctn;
 
 namespace {
 
-struct PendingRelease {   // arena range given back by a swap-out that may still be copying
+struct PendingRelease {   // arena range given back by an eviction whose offload may still be copying
   uint64_t off, len;
-  hipEvent_t done;        // borrowed from the model that was swapped out
+  hipEvent_t done;        // borrowed from the model that was evicted
   int model;
+};
+
+struct Eviction {         // blocks [b0, b1) of a model: decided, arena given back, not yet copied to the host
+  int model, b0, b1;
+  std::vector<uint64_t> off;   // arena offset of each of those blocks
 };
 
 struct Model {
@@ -40,9 +45,14 @@ struct Model {
   // the host and in the arena image, so one copy can move a whole run.
   struct Run { int first; uint64_t bytes; };   // first tensor (list index) and total bytes
   std::vector<std::vector<Run>> runs;
-  bool resident = false;
-  uint64_t arena_off = 0;
-  uint64_t out_off = 0;              // range the current / last offload reads from
+  // Blocks [0, k) are resident (or on their way in), each at its own arena
+  // offset.  Whole-model residency places all blocks in one range and k is 0
+  // or the block count; block residency places every block in a slot of its own.
+  int k = 0;
+  std::vector<uint64_t> block_off;
+  bool full() const { return k == lay.n_blocks; }
+  uint64_t placement = 0;            // changes whenever blocks are placed: key of the captured graphs
+  int last_load_first = 0;           // first block the last load brought in
   bool fragmented = true;            // more than 4 runs per block on average
   bool offload_enqueued = true;      // false between the eviction decision and the offload's enqueue
   std::vector<hipEvent_t> ev_block;  // recorded on the h2d stream after each block
@@ -52,7 +62,7 @@ struct Model {
   bool pending_in = false, pending_out = false;
 
   // Captured forward passes of this placement (see forward_graph).
-  struct Graph { uint64_t arena_off; int batch, seq; float* logits; hipGraphExec_t exec; };
+  struct Graph { uint64_t placement; int batch, seq; float* logits; hipGraphExec_t exec; };
   std::vector<Graph> graphs;
   void drop_graphs() {   // only when none of them can still be running
     for (Graph& g : graphs) (void)hipGraphExecDestroy(g.exec);
@@ -102,7 +112,9 @@ struct ctn_ctx {
   RangeAllocator arena;
   std::vector<std::unique_ptr<Model>> models;
   std::vector<PendingRelease> pending;
-  std::vector<int> deferred;         // evicted models whose offload is not enqueued yet
+  std::vector<Eviction> deferred;    // evictions whose offload is not enqueued yet
+  uint64_t placements = 0;
+  std::vector<ctn_block_event> block_events;
   std::vector<RetiredGraphs> retired;
   int contended_misses = 0;          // > 0: recent misses found earlier offloads still running
   std::vector<ctn_event> events;
@@ -201,38 +213,69 @@ void purge_retired(ctn_ctx* c, bool all) {
   }
 }
 
+void log_blocks(ctn_ctx* c, int kind, const Residency::Move& mv, uint64_t use) {
+  if (mv.b0 >= mv.b1) return;
+  c->block_events.push_back(ctn_block_event{kind, mv.model, mv.b0, mv.b1, use});
+}
+
+// Bytes of arena a block occupies where it is placed.
+uint64_t block_footprint(const ctn_ctx* c, const ShardLayout& L, int b) {
+  return c->res.block_mode() ? L.slot_bytes : L.block_span[b];
+}
+
 // Eviction happens in two steps so that, on a miss, the load of the requested
 // model and its forward pass can be enqueued before the (latency-insensitive)
 // offload of the victims: evict_logical() updates the bookkeeping and frees
-// the arena range; enqueue_offload() issues the copies back to the host
-// tensors and records the completion event the freed range waits on.
-void evict_logical(ctn_ctx* c, int mi) {
-  Model* m = c->models[mi].get();
-  m->resident = false;
-  retire_graphs(c, m);               // they point into the range being given up
+// the blocks' arena ranges; enqueue_offload() issues the copies back to the
+// host tensors and records the completion event the freed ranges wait on.
+// The residency policy has already dropped the blocks named by `mv`.
+void evict_logical(ctn_ctx* c, const Residency::Move& mv) {
+  if (mv.b0 >= mv.b1) return;
+  Model* m = c->models[mv.model].get();
+  retire_graphs(c, m);               // they point into the blocks being given up
   m->offload_enqueued = false;
-  m->out_off = m->arena_off;
-  c->arena.release(m->arena_off, m->lay.arena_bytes);
-  c->pending.push_back({m->arena_off, m->lay.arena_bytes, m->ev_out_done, mi});
-  c->res.mark_evicted(mi);
-  c->deferred.push_back(mi);
+  Eviction ev{mv.model, mv.b0, mv.b1, {}};
+  uint64_t run_off = 0, run_len = 0;
+  auto give_back = [&]() {
+    if (!run_len) return;
+    c->arena.release(run_off, run_len);
+    c->pending.push_back({run_off, run_len, m->ev_out_done, mv.model});
+  };
+  for (int b = mv.b0; b < mv.b1; ++b) {
+    const uint64_t off = m->block_off[b], len = block_footprint(c, m->lay, b);
+    ev.off.push_back(off);
+    if (run_len && run_off + run_len == off) {
+      run_len += len;
+    } else {
+      give_back();
+      run_off = off;
+      run_len = len;
+    }
+  }
+  give_back();
+  m->k = mv.b0;
+  c->deferred.push_back(std::move(ev));
 }
 
-int enqueue_offload(ctn_ctx* c, int mi) {
-  Model* m = c->models[mi].get();
-  if (m->offload_enqueued) return CTN_OK;
-  char* arena = static_cast<char*>(c->cfg.arena_dev) + m->out_off;
-  // The offload must see the complete device copy and must not overtake an
-  // inference that is still reading it.
-  CTN_HIP(c, hipStreamWaitEvent(c->s_d2h, m->ev_block.back(), 0));
+int enqueue_offload(ctn_ctx* c, const Eviction& ev) {
+  Model* m = c->models[ev.model].get();
+  char* arena = static_cast<char*>(c->cfg.arena_dev);
+  // The offload must see the complete device copy (blocks are loaded in order on
+  // one stream, so the last block's event covers the others) and must not
+  // overtake an inference that is still reading it.
+  CTN_HIP(c, hipStreamWaitEvent(c->s_d2h, m->ev_block[ev.b1 - 1], 0));
   if (m->used_since_load) CTN_HIP(c, hipStreamWaitEvent(c->s_d2h, m->ev_last_use, 0));
   CTN_HIP(c, hipEventRecord(m->ev_out_start, c->s_d2h));
   const ShardLayout& L = m->lay;
-  for (int b = 0; b < L.n_blocks; ++b) {
+  uint64_t bytes = 0;
+  for (int b = ev.b0; b < ev.b1; ++b) {
+    char* base = arena + ev.off[b - ev.b0];
+    bytes += L.block_bytes[b];
+    if (m->runs[b].empty()) continue;
     if (c->cfg.transfer_mode == CTN_XFER_KERNEL) {
       CopyTable t{};
       for (const Model::Run& r : m->runs[b]) {
-        t.seg[t.n].src = arena + L.offset[r.first];
+        t.seg[t.n].src = base + L.offset_in_block(r.first);
         t.seg[t.n].dst = m->host_dev[r.first];
         t.seg[t.n].n16 = r.bytes / 16;
         ++t.n;
@@ -241,48 +284,50 @@ int enqueue_offload(ctn_ctx* c, int mi) {
       CTN_HIP(c, launch_copy_table(t, c->cfg.copy_blocks, c->s_d2h, kCopyD2H));
     } else if (c->cfg.transfer_mode == CTN_XFER_DMA) {   // one message per tensor (Section 5.1)
       for (int ti : L.block_tensors[b])
-        CTN_HIP(c, hipMemcpyAsync(m->host[ti], arena + L.offset[ti], L.nbytes[ti], hipMemcpyDeviceToHost,
+        CTN_HIP(c, hipMemcpyAsync(m->host[ti], base + L.offset_in_block(ti), L.nbytes[ti], hipMemcpyDeviceToHost,
                                   c->s_d2h));
     } else {                                             // one message per run of adjacent tensors
       for (const Model::Run& r : m->runs[b])
-        CTN_HIP(c, hipMemcpyAsync(m->host[r.first], arena + L.offset[r.first], r.bytes, hipMemcpyDeviceToHost,
-                                  c->s_d2h));
+        CTN_HIP(c, hipMemcpyAsync(m->host[r.first], base + L.offset_in_block(r.first), r.bytes,
+                                  hipMemcpyDeviceToHost, c->s_d2h));
     }
   }
   CTN_HIP(c, hipEventRecord(m->ev_out_done, c->s_d2h));
-  m->offload_enqueued = true;
   m->out_recorded = true;
   m->pending_out = true;
-  c->stats.bytes_d2h += L.param_bytes;
+  c->stats.bytes_d2h += bytes;
   c->stats.n_swap_out += 1;
   return CTN_OK;
 }
 
 // Issues every offload that was decided but not yet enqueued.
 int flush_deferred(ctn_ctx* c) {
-  for (int mi : c->deferred) {
-    int rc = enqueue_offload(c, mi);
+  for (const Eviction& ev : c->deferred) {
+    int rc = enqueue_offload(c, ev);
     if (rc) return rc;
   }
+  for (const Eviction& ev : c->deferred) c->models[ev.model]->offload_enqueued = true;
   c->deferred.clear();
   return CTN_OK;
 }
 
-// Make model mi resident (a use).  On a miss: evict least recently used
-// models while the budget (or the arena) has no room, then enqueue the load.
-// Offloads of the victims stay deferred (see flush_deferred) unless the load
-// has to reuse a victim's range.
+// Make model mi completely resident (a use).  On a miss: evict from the least
+// recently used models while the budget (or the arena) has no room for the
+// missing blocks, then enqueue their load.  Offloads of the victims stay
+// deferred (see flush_deferred) unless the load has to reuse a victim's range.
 int ensure_resident(ctn_ctx* c, int mi) {
   Model* m = c->models[mi].get();
   std::vector<int> victims;
-  if (m->resident) {
+  if (m->full()) {
     c->res.touch(mi);
     c->stats.n_hit += 1;
     log_event(c, 0, mi, victims);
     return CTN_OK;
   }
   const ShardLayout& L = m->lay;
-  if (L.param_bytes > c->res.budget() || L.arena_bytes > c->cfg.arena_bytes) return CTN_E_TOO_BIG;
+  const bool by_block = c->res.block_mode();
+  const uint64_t whole_footprint = by_block ? L.slot_bytes * L.n_blocks : L.arena_bytes;
+  if (L.param_bytes > c->res.budget() || whole_footprint > c->cfg.arena_bytes) return CTN_E_TOO_BIG;
   int rc = flush_deferred(c);
   if (rc) return rc;
   purge_retired(c, false);
@@ -301,41 +346,89 @@ int ensure_resident(ctn_ctx* c, int mi) {
   if (!c->pending.empty()) c->contended_misses = 3;
   const bool earlier_offload_running = c->contended_misses > 0;
   if (c->contended_misses > 0) c->contended_misses -= 1;
-  while (c->res.over_budget_with(mi)) {
-    int v = c->res.oldest(mi);
-    if (v < 0) return CTN_E_BUSY;
-    evict_logical(c, v);
-    victims.push_back(v);
-  }
+
+  const uint64_t use = c->events.size();
+  const int first = m->k;                       // blocks [first, n_blocks) are missing
+  std::vector<Residency::Move> moves;           // what this use evicts, one entry per victim, in order
+  while (c->res.over_budget_with(mi))
+    if (c->res.evict_step(mi, moves) < 0) return CTN_E_BUSY;   // (cannot happen: the model fits the budget alone)
+  for (const Residency::Move& mv : moves) evict_logical(c, mv);
   auto busy_ranges = [&]() {
     std::vector<RangeAllocator::Range> b;
     for (const PendingRelease& p : c->pending) b.push_back({p.off, p.len});
     return b;
   };
-  // Prefer a hole no offload is reading, so load and offload overlap on the
+  // The budget has room but no arena hole is wide enough: keep evicting.
+  auto evict_for_room = [&]() -> bool {
+    std::vector<Residency::Move> step;
+    if (c->res.evict_step(mi, step) < 0) return false;
+    evict_logical(c, step[0]);
+    c->stats.n_extra_evictions += 1;
+    for (Residency::Move& mv : moves)
+      if (mv.model == step[0].model) {
+        mv.b0 = step[0].b0;
+        return true;
+      }
+    moves.push_back(step[0]);
+    return true;
+  };
+  // Prefer holes no offload is reading, so load and offload overlap on the
   // two link directions (Section 3.2 / 5.1); otherwise the load waits.
-  uint64_t off = c->arena.alloc_avoiding(L.arena_bytes, busy_ranges());
-  while (off == UINT64_MAX) {   // budget has room but no hole is wide enough: keep evicting
-    int v = c->res.oldest(mi);
-    if (v < 0) return CTN_E_BUSY;
-    evict_logical(c, v);
-    victims.push_back(v);
-    off = c->arena.alloc_avoiding(L.arena_bytes, busy_ranges());
+  std::vector<RangeAllocator::Range> placed;    // arena ranges this load writes
+  auto undo = [&]() {
+    for (const RangeAllocator::Range& r : placed) c->arena.release(r.off, r.len);
+  };
+  if (!by_block) {
+    uint64_t off = c->arena.alloc_avoiding(L.arena_bytes, busy_ranges());
+    while (off == UINT64_MAX) {
+      if (!evict_for_room()) return CTN_E_BUSY;
+      off = c->arena.alloc_avoiding(L.arena_bytes, busy_ranges());
+    }
+    placed.push_back({off, L.arena_bytes});
+    for (int b = 0; b < L.n_blocks; ++b) m->block_off[b] = off + L.block_start[b];
+  } else {
+    const int n_missing = L.n_blocks - first;
+    // all missing blocks side by side when a hole allows it, else slot by slot
+    const uint64_t together = c->arena.alloc_avoiding(L.slot_bytes * n_missing, busy_ranges());
+    if (together != UINT64_MAX) {
+      placed.push_back({together, L.slot_bytes * n_missing});
+      for (int b = first; b < L.n_blocks; ++b) m->block_off[b] = together + L.slot_bytes * (b - first);
+    } else {
+      for (int b = first; b < L.n_blocks; ++b) {
+        uint64_t off = c->arena.alloc_avoiding(L.slot_bytes, busy_ranges());
+        while (off == UINT64_MAX) {
+          if (!evict_for_room()) {
+            undo();
+            return CTN_E_BUSY;
+          }
+          off = c->arena.alloc_avoiding(L.slot_bytes, busy_ranges());
+        }
+        placed.push_back({off, L.slot_bytes});
+        m->block_off[b] = off;
+      }
+    }
   }
-  m->arena_off = off;
+  m->placement = ++c->placements;
+  auto overlaps_load = [&](const PendingRelease& p) {
+    for (const RangeAllocator::Range& r : placed)
+      if (p.off < r.off + r.len && r.off < p.off + p.len) return true;
+    return false;
+  };
   bool reuses_victim_range = false;
   for (const PendingRelease& p : c->pending)
-    if (p.off < off + L.arena_bytes && off < p.off + p.len && !c->models[p.model]->offload_enqueued)
-      reuses_victim_range = true;
+    if (overlaps_load(p) && !c->models[p.model]->offload_enqueued) reuses_victim_range = true;
   if (reuses_victim_range) {     // the completion events the load must wait on have to exist first
     rc = flush_deferred(c);
-    if (rc) return rc;
+    if (rc) {
+      undo();
+      return rc;
+    }
   }
   for (const PendingRelease& p : c->pending)
-    if (p.off < off + L.arena_bytes && off < p.off + p.len) CTN_HIP(c, hipStreamWaitEvent(c->s_h2d, p.done, 0));
+    if (overlaps_load(p)) CTN_HIP(c, hipStreamWaitEvent(c->s_h2d, p.done, 0));
   // The load reads the host tensors this model's own offload may still be writing.
   if (m->pending_out) CTN_HIP(c, hipStreamWaitEvent(c->s_h2d, m->ev_out_done, 0));
-  char* arena = static_cast<char*>(c->cfg.arena_dev) + off;
+  char* arena = static_cast<char*>(c->cfg.arena_dev);
   // AUTO: a host list in many pieces is gathered by one kernel launch per block
   // (no per-piece cost, and the fastest load while only this call's victim is
   // being offloaded: 53.6 GB/s against a 38.9 GB/s offload).  When earlier
@@ -345,12 +438,15 @@ int ensure_resident(ctn_ctx* c, int mi) {
   const bool load_by_kernel = c->cfg.transfer_mode == CTN_XFER_KERNEL ||
                               (c->cfg.transfer_mode == CTN_XFER_AUTO && m->fragmented && !earlier_offload_running);
   CTN_HIP(c, hipEventRecord(m->ev_in_start, c->s_h2d));
-  for (int b = 0; b < L.n_blocks; ++b) {
-    if (load_by_kernel) {
+  for (int b = first; b < L.n_blocks; ++b) {
+    char* base = arena + m->block_off[b];
+    if (m->runs[b].empty()) {
+      // nothing to move
+    } else if (load_by_kernel) {
       CopyTable t{};
       for (const Model::Run& r : m->runs[b]) {
         t.seg[t.n].src = m->host_dev[r.first];
-        t.seg[t.n].dst = arena + L.offset[r.first];
+        t.seg[t.n].dst = base + L.offset_in_block(r.first);
         t.seg[t.n].n16 = r.bytes / 16;
         ++t.n;
       }
@@ -358,25 +454,31 @@ int ensure_resident(ctn_ctx* c, int mi) {
       CTN_HIP(c, launch_copy_table(t, c->cfg.copy_blocks, c->s_h2d, kCopyH2D));
     } else if (c->cfg.transfer_mode == CTN_XFER_DMA) {   // one message per tensor (Section 5.1)
       for (int ti : L.block_tensors[b])
-        CTN_HIP(c, hipMemcpyAsync(arena + L.offset[ti], m->host[ti], L.nbytes[ti], hipMemcpyHostToDevice,
+        CTN_HIP(c, hipMemcpyAsync(base + L.offset_in_block(ti), m->host[ti], L.nbytes[ti], hipMemcpyHostToDevice,
                                   c->s_h2d));
     } else {                                             // one message per run of adjacent tensors
       for (const Model::Run& r : m->runs[b])
-        CTN_HIP(c, hipMemcpyAsync(arena + L.offset[r.first], m->host[r.first], r.bytes, hipMemcpyHostToDevice,
-                                  c->s_h2d));
+        CTN_HIP(c, hipMemcpyAsync(base + L.offset_in_block(r.first), m->host[r.first], r.bytes,
+                                  hipMemcpyHostToDevice, c->s_h2d));
     }
     CTN_HIP(c, hipEventRecord(m->ev_block[b], c->s_h2d));
   }
-  m->resident = true;
+  m->k = L.n_blocks;
+  m->last_load_first = first;
   m->load_recorded = true;
   m->pending_in = true;
-  m->used_since_load = false;
-  c->res.mark_resident(mi);
-  c->stats.bytes_h2d += L.param_bytes;
+  c->stats.bytes_h2d += c->res.missing_bytes(mi);
+  const Residency::Move loaded = c->res.load_missing(mi);
   c->stats.n_swap_in += 1;
   c->stats.n_miss += 1;
+  if (first > 0) c->stats.n_partial_miss += 1;
   c->stats.resident_bytes = c->res.resident_bytes();
   c->stats.peak_resident_bytes = c->res.peak_bytes();
+  for (const Residency::Move& mv : moves) {
+    victims.push_back(mv.model);
+    log_blocks(c, 1, mv, use);
+  }
+  log_blocks(c, 0, loaded, use);
   log_event(c, 1, mi, victims);
   return CTN_OK;
 }
@@ -433,7 +535,9 @@ bool link_quiet(ctn_ctx* c) {
 
 template <typename T>
 T* dev_tensor(ctn_ctx* c, Model* m, int ti) {
-  return reinterpret_cast<T*>(static_cast<char*>(c->cfg.arena_dev) + m->arena_off + m->lay.offset[ti]);
+  const ShardLayout& L = m->lay;
+  return reinterpret_cast<T*>(static_cast<char*>(c->cfg.arena_dev) + m->block_off[L.block_of[ti]] +
+                              L.offset_in_block(ti));
 }
 
 // The launch sequence of one forward pass on stream s.  with_waits: wait for the
@@ -481,7 +585,7 @@ int forward_launches(ctn_ctx* c, Model* m, const Activations& act, int batch, in
 // Replays (capturing on first use) the forward pass of a completely resident model.
 int forward_graph(ctn_ctx* c, Model* m, const Activations& act, int batch, int seq, float* logits, hipStream_t s) {
   for (const Model::Graph& g : m->graphs)
-    if (g.arena_off == m->arena_off && g.batch == batch && g.seq == seq && g.logits == logits) {
+    if (g.placement == m->placement && g.batch == batch && g.seq == seq && g.logits == logits) {
       CTN_HIP(c, hipGraphLaunch(g.exec, s));
       return CTN_OK;
     }
@@ -512,7 +616,7 @@ int forward_graph(ctn_ctx* c, Model* m, const Activations& act, int batch, int s
     (void)hipGraphExecDestroy(m->graphs.front().exec);
     m->graphs.erase(m->graphs.begin());
   }
-  m->graphs.push_back({m->arena_off, batch, seq, logits, exec});
+  m->graphs.push_back({m->placement, batch, seq, logits, exec});
   CTN_HIP(c, hipGraphLaunch(exec, s));
   return CTN_OK;
 }
@@ -531,6 +635,7 @@ int ctn_create(const ctn_config* cfg, ctn_ctx** out) {
     return CTN_E_INVAL;
   if (cfg->hbm_budget_bytes == 0 || cfg->arena_bytes == 0) return CTN_E_INVAL;
   if (cfg->transfer_mode < CTN_XFER_DMA || cfg->transfer_mode > CTN_XFER_AUTO) return CTN_E_INVAL;
+  if (cfg->block_residency != 0 && cfg->block_residency != 1) return CTN_E_INVAL;
   if (!own_streams && (cfg->stream_h2d == cfg->stream_compute || cfg->stream_d2h == cfg->stream_compute ||
                        cfg->stream_h2d == cfg->stream_d2h))
     return CTN_E_INVAL;
@@ -551,7 +656,7 @@ int ctn_create(const ctn_config* cfg, ctn_ctx** out) {
     c->s_h2d = static_cast<hipStream_t>(cfg->stream_h2d);
     c->s_d2h = static_cast<hipStream_t>(cfg->stream_d2h);
   }
-  c->res = Residency(cfg->hbm_budget_bytes);
+  c->res = Residency(cfg->hbm_budget_bytes, cfg->block_residency != 0);
   c->arena.reset(cfg->arena_bytes / kAlign * kAlign);
   c->stats.budget_bytes = cfg->hbm_budget_bytes;
   *out = c;
@@ -623,7 +728,8 @@ int ctn_register_model(ctn_ctx* c, const ctn_model_desc* desc, const ctn_param* 
     }
     m->host.push_back(p.host_ptr);
   }
-  if (L.param_bytes > c->res.budget() || L.arena_bytes > c->cfg.arena_bytes) return CTN_E_TOO_BIG;
+  const uint64_t footprint = c->res.block_mode() ? L.slot_bytes * L.n_blocks : L.arena_bytes;
+  if (L.param_bytes > c->res.budget() || footprint > c->cfg.arena_bytes) return CTN_E_TOO_BIG;
   // the device must be able to dereference the host tensors (zero-copy path)
   for (int i = 0; i < L.n_tensors; ++i) {
     void* dp = nullptr;
@@ -659,7 +765,8 @@ int ctn_register_model(ctn_ctx* c, const ctn_model_desc* desc, const ctn_param* 
   CTN_HIP(c, hipEventCreate(&m->ev_out_start));
   CTN_HIP(c, hipEventCreate(&m->ev_out_done));
   CTN_HIP(c, hipEventCreateWithFlags(&m->ev_last_use, hipEventDisableTiming));
-  int idx = c->res.add_model(L.param_bytes);
+  m->block_off.assign(L.n_blocks, 0);
+  int idx = c->res.add_model(L.block_bytes);
   c->models.push_back(std::move(m));
   *out = idx;
   return CTN_OK;
@@ -676,9 +783,11 @@ int ctn_swap_out(ctn_ctx* c, ctn_model mi) {
   Model* m = get_model(c, mi);
   if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
   std::vector<int> victims;
-  if (m->resident) {
+  if (m->k > 0) {
     victims.push_back(mi);
-    evict_logical(c, mi);
+    const Residency::Move mv = c->res.evict_all(mi);
+    evict_logical(c, mv);
+    log_blocks(c, 1, mv, c->events.size());
   }
   int rc = flush_deferred(c);
   if (rc) return rc;
@@ -710,6 +819,11 @@ uint64_t ctn_workspace_bytes(const ctn_model_desc* desc, int64_t max_tokens, int
 uint64_t ctn_arena_bytes(const ctn_model_desc* desc) {
   if (!desc || !desc_valid(*desc)) return 0;
   return make_layout(*desc).arena_bytes;
+}
+
+uint64_t ctn_slot_bytes(const ctn_model_desc* desc) {
+  if (!desc || !desc_valid(*desc)) return 0;
+  return make_layout(*desc).slot_bytes;
 }
 
 static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int32_t batch, int32_t seq,
@@ -785,7 +899,25 @@ int ctn_is_resident(ctn_ctx* c, ctn_model mi, int32_t* out) {
   Model* m = get_model(c, mi);
   if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
   if (!out) return CTN_E_INVAL;
-  *out = m->resident ? 1 : 0;
+  *out = m->full() ? 1 : 0;
+  return CTN_OK;
+}
+
+int ctn_resident_blocks(ctn_ctx* c, ctn_model mi, int32_t* resident, int32_t* total) {
+  Model* m = get_model(c, mi);
+  if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
+  if (resident) *resident = m->k;
+  if (total) *total = m->lay.n_blocks;
+  return CTN_OK;
+}
+
+int ctn_get_block_events(ctn_ctx* c, uint64_t first, ctn_block_event* out, uint64_t cap, uint64_t* n_out,
+                         uint64_t* total) {
+  if (!c || !n_out || !total || (cap && !out)) return CTN_E_INVAL;
+  *total = c->block_events.size();
+  uint64_t n = 0;
+  for (uint64_t i = first; i < c->block_events.size() && n < cap; ++i) out[n++] = c->block_events[i];
+  *n_out = n;
   return CTN_OK;
 }
 
@@ -825,15 +957,17 @@ int ctn_last_swap_ms(ctn_ctx* c, ctn_model mi, float* in_ms, float* out_ms, floa
     }
   }
   if (block_ms && m->load_recorded)
-    for (int b = 0; b < m->lay.n_blocks && b < cap; ++b)
-      CTN_HIP(c, hipEventElapsedTime(&block_ms[b], m->ev_in_start, m->ev_block[b]));
+    for (int b = 0; b < m->lay.n_blocks && b < cap; ++b) {
+      block_ms[b] = 0.f;             // blocks that were already resident took no part in the last load
+      if (b >= m->last_load_first) CTN_HIP(c, hipEventElapsedTime(&block_ms[b], m->ev_in_start, m->ev_block[b]));
+    }
   return CTN_OK;
 }
 
 int ctn_debug_read_param(ctn_ctx* c, ctn_model mi, int32_t index, void* dst, uint64_t cap) {
   Model* m = get_model(c, mi);
   if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
-  if (!dst || index < 0 || index >= m->lay.n_tensors || !m->resident) return CTN_E_INVAL;
+  if (!dst || index < 0 || index >= m->lay.n_tensors || m->lay.block_of[index] >= m->k) return CTN_E_INVAL;
   if (cap < m->lay.nbytes[index]) return CTN_E_INVAL;
   int rc = ctn_wait(c, mi);
   if (rc) return rc;
@@ -897,17 +1031,63 @@ int ctn_residency_replay(uint64_t budget, const uint64_t* sizes, int32_t n_model
     } else {
       if (res.size(m) > budget) return CTN_E_TOO_BIG;
       e.kind = 1;
-      while (res.over_budget_with(m)) {
-        int v = res.oldest(m);
-        if (v < 0) return CTN_E_BUSY;
-        res.mark_evicted(v);
-        if (e.n_victims < 13) e.victims[e.n_victims] = v;
+      std::vector<Residency::Move> moves;
+      while (res.over_budget_with(m))
+        if (res.evict_step(m, moves) < 0) return CTN_E_BUSY;
+      for (const Residency::Move& mv : moves) {
+        if (e.n_victims < 13) e.victims[e.n_victims] = mv.model;
         e.n_victims += 1;
       }
-      res.mark_resident(m);
+      res.load_missing(m);
     }
     out[i] = e;
   }
+  return CTN_OK;
+}
+
+int ctn_block_residency_replay(uint64_t budget, const int32_t* n_blocks, const uint64_t* block_bytes, int32_t n_models,
+                               const int32_t* trace, uint64_t n, ctn_event* out, ctn_block_event* blocks_out,
+                               uint64_t cap, uint64_t* n_blocks_out) {
+  if (!n_blocks || !block_bytes || n_models <= 0 || !n_blocks_out || (n && (!trace || !out)) || (cap && !blocks_out))
+    return CTN_E_INVAL;
+  Residency res(budget, true);
+  uint64_t at = 0;
+  for (int i = 0; i < n_models; ++i) {
+    if (n_blocks[i] < 1) return CTN_E_INVAL;
+    res.add_model(std::vector<uint64_t>(block_bytes + at, block_bytes + at + n_blocks[i]));
+    at += n_blocks[i];
+  }
+  uint64_t nb = 0;
+  auto emit = [&](int kind, const Residency::Move& mv, uint64_t use) {
+    if (mv.b0 >= mv.b1) return true;
+    if (nb >= cap) return false;
+    blocks_out[nb++] = ctn_block_event{kind, mv.model, mv.b0, mv.b1, use};
+    return true;
+  };
+  for (uint64_t i = 0; i < n; ++i) {
+    const int m = trace[i];
+    if (m < 0 || m >= n_models) return CTN_E_NOMODEL;
+    ctn_event e{};
+    e.model = m;
+    if (res.resident(m)) {
+      res.touch(m);
+      e.kind = 0;
+    } else {
+      if (res.size(m) > budget) return CTN_E_TOO_BIG;
+      e.kind = 1;
+      std::vector<Residency::Move> moves;
+      while (res.over_budget_with(m))
+        if (res.evict_step(m, moves) < 0) return CTN_E_BUSY;
+      for (const Residency::Move& mv : moves) {
+        if (e.n_victims < 13) e.victims[e.n_victims] = mv.model;
+        e.n_victims += 1;
+        if (!emit(1, mv, i)) return CTN_E_INVAL;
+      }
+      if (!emit(0, res.load_missing(m), i)) return CTN_E_INVAL;
+    }
+    out[i] = e;
+  }
+  *n_blocks_out = nb;
   return CTN_OK;
 }
 
@@ -965,7 +1145,7 @@ int ctn_engine_step(ctn_engine* e, void* logits_out, int64_t* served, int32_t ca
   e->packed.clear();
   for (const QueuedRequest& r : batch) e->packed.insert(e->packed.end(), r.ids.begin(), r.ids.end());
   if (model) *model = m;
-  if (was_miss) *was_miss = e->ctx->models[m]->resident ? 0 : 1;
+  if (was_miss) *was_miss = e->ctx->models[m]->full() ? 0 : 1;
   const int rc = ctn_infer(e->ctx, m, e->packed.data(), static_cast<int32_t>(batch.size()), e->seq, logits_out, 1);
   if (rc) {   // put the requests back in order so nothing is lost
     for (auto it = batch.rbegin(); it != batch.rend(); ++it) e->queues.push_front(m, std::move(*it));
@@ -1007,12 +1187,10 @@ int ctn_engine_replay(int32_t n_models, int32_t max_batch, uint64_t budget, cons
     std::vector<QueuedRequest> batch = queues.pop(m, max_batch);
     bool miss = !res.resident(m);
     if (miss) {
-      while (res.over_budget_with(m)) {
-        const int v = res.oldest(m);
-        if (v < 0) return CTN_E_BUSY;
-        res.mark_evicted(v);
-      }
-      res.mark_resident(m);
+      std::vector<Residency::Move> moves;
+      while (res.over_budget_with(m))
+        if (res.evict_step(m, moves) < 0) return CTN_E_BUSY;
+      res.load_missing(m);
     } else {
       res.touch(m);
     }

@@ -73,18 +73,76 @@ int main() {
     for (auto& b : live) ra.release(b.off, b.len);
     assert(ra.largest_hole() == total);          // everything coalesced back into one hole
   }
-  // residency: budget never exceeded, oldest() is the least recently used
-  ctn::Residency r(100);
-  for (int i = 0; i < 5; ++i) r.add_model(30 + i);
-  std::vector<int> order;
-  for (int step = 0; step < 1000; ++step) {
-    const int m = rng() % 5;
-    if (r.resident(m)) { r.touch(m); }
-    else {
-      while (r.over_budget_with(m)) { int v = r.oldest(m); assert(v >= 0 && v != m); r.mark_evicted(v); }
-      r.mark_resident(m);
+  // residency, whole-model mode: budget never exceeded, victims leave completely, least recently used first
+  {
+    ctn::Residency r(100);
+    for (int i = 0; i < 5; ++i) r.add_model(30 + i);
+    std::vector<uint64_t> last(5, 0);
+    uint64_t clock = 0;
+    for (int step = 0; step < 1000; ++step) {
+      const int m = rng() % 5;
+      if (r.resident(m)) { r.touch(m); }
+      else {
+        std::vector<ctn::Residency::Move> moves;
+        while (r.over_budget_with(m)) {
+          int expect = -1;
+          for (int i = 0; i < 5; ++i)
+            if (i != m && r.resident(i) && (expect < 0 || last[i] < last[expect])) expect = i;
+          const int v = r.evict_step(m, moves);
+          assert(v >= 0 && v != m && v == expect && !r.resident(v) && r.resident_blocks(v) == 0);
+        }
+        r.load_missing(m);
+      }
+      last[m] = ++clock;
+      assert(r.resident(m) && r.resident_bytes() <= 100 && r.peak_bytes() <= 100);
     }
-    assert(r.resident_bytes() <= 100 && r.peak_bytes() <= 100);
+  }
+  // residency, block mode: prefixes only, one block per step from the tail of the oldest model,
+  // never more evicted than the missing blocks need
+  for (int round = 0; round < 200; ++round) {
+    const int n = 2 + rng() % 4;
+    std::vector<std::vector<uint64_t>> blocks(n);
+    uint64_t biggest = 0, all = 0;
+    for (auto& b : blocks) {
+      const int nb = 1 + rng() % 5;
+      uint64_t sum = 0;
+      for (int i = 0; i < nb; ++i) { b.push_back(1 + rng() % 8); sum += b.back(); }
+      biggest = std::max(biggest, sum);
+      all += sum;
+    }
+    const uint64_t budget = biggest + rng() % (all - biggest + 2);
+    ctn::Residency r(budget, true);
+    for (auto& b : blocks) r.add_model(b);
+    for (int step = 0; step < 100; ++step) {
+      const int m = rng() % n;
+      if (rng() % 10 == 0) {
+        const auto mv = r.evict_all(m);
+        assert(mv.b0 == 0 && r.resident_blocks(m) == 0);
+        continue;
+      }
+      if (r.resident(m)) { r.touch(m); continue; }
+      std::vector<ctn::Residency::Move> moves;
+      uint64_t last_dropped = 0;
+      while (r.over_budget_with(m)) {
+        const int v = r.evict_step(m, moves);
+        assert(v >= 0 && v != m);
+        last_dropped = blocks[v][r.resident_blocks(v)];
+      }
+      for (size_t i = 0; i < moves.size(); ++i) {
+        assert(moves[i].b0 < moves[i].b1 && r.resident_blocks(moves[i].model) == moves[i].b0);
+        for (size_t j = 0; j < i; ++j) assert(moves[j].model != moves[i].model);
+        if (i + 1 < moves.size()) assert(moves[i].b0 == 0);      // only the last victim keeps a prefix
+      }
+      const uint64_t need = r.missing_bytes(m);
+      if (!moves.empty()) assert(r.resident_bytes() + need + last_dropped > budget);   // minimal
+      const auto ld = r.load_missing(m);
+      assert(ld.model == m && ld.b1 == (int)blocks[m].size() && r.resident(m));
+      assert(r.resident_bytes() <= budget);
+      uint64_t sum = 0;
+      for (int i = 0; i < n; ++i)
+        for (int b = 0; b < r.resident_blocks(i); ++b) sum += blocks[i][b];
+      assert(sum == r.resident_bytes());
+    }
   }
   // request queues: oldest head first (ties: lower model), FIFO per model, pop respects the cap
   {

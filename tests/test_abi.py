@@ -111,3 +111,50 @@ def test_engine_replay_errors():
         P.engine_replay(2, 1, 10, [4, 4], [1.0, 0.5], [0, 1], 0.1, 0.1, 0.1)      # not sorted
     with pytest.raises(P.CtnError):
         P.engine_replay(2, 1, 10, [4, 4], [0.5, 1.0], [0, 2], 0.1, 0.1, 0.1)      # unknown model
+
+
+def _oracle_block_log(budget, blocks, trace):
+    """(events, block events) of the oracle in the library's record shapes."""
+    from oracle.partial_lru import PartialLruResidency
+    r = PartialLruResidency(budget, blocks)
+    events, block_events = [], []
+    for use, m in enumerate(trace):
+        kind, model, first, evictions = r.touch(m)
+        events.append((kind, model, tuple(v for v, _, _ in evictions)))
+        for v, lo, hi in evictions:
+            block_events.append(("evict", v, lo, hi, use))
+        if kind == "miss":
+            block_events.append(("load", model, first, len(blocks[model]), use))
+    return events, block_events
+
+
+def test_block_granular_policy_equals_oracle():
+    rng = np.random.default_rng(11)
+    for case in range(150):
+        n = int(rng.integers(2, 7))
+        blocks = [[int(rng.integers(1, 50)) for _ in range(int(rng.integers(1, 8)))] for _ in range(n)]
+        biggest, total = max(sum(b) for b in blocks), sum(sum(b) for b in blocks)
+        budget = int(rng.integers(biggest, total + 2))
+        trace = [int(x) for x in rng.integers(0, n, size=80)]
+        assert P.block_residency_replay(budget, blocks, trace) == _oracle_block_log(budget, blocks, trace)
+
+
+def test_block_granular_policy_on_the_serving_shapes():
+    """Eight 6.7B/TP2 shards under 20e9 bytes: the slack below a third model is used block by block."""
+    from synth import gamma_zipf_trace
+    c = CONFIGS["serve8x6.7b_tp2"]
+    d = c["desc"]
+    names = param_list(d)
+    nbytes = [2 * int(np.prod(s)) for _, s, _ in names]
+    head = nbytes[0] + nbytes[1] + nbytes[-2] + nbytes[-1]
+    layer = sum(nbytes[2:18])
+    blocks = [[head] + [layer] * d.layers] * c["n_models"]
+    assert sum(blocks[0]) == shard_bytes(d)
+    _, model_of = gamma_zipf_trace(c["n_models"], c["rate"], c["cv"], c["zipf"], c["n_requests"], c["trace_seed"])
+    trace = [int(m) for m in model_of]
+    got = P.block_residency_replay(c["budget"], blocks, trace)
+    assert got == _oracle_block_log(c["budget"], blocks, trace)
+    whole = replay(c["budget"], [shard_bytes(d)] * c["n_models"], trace)
+    loaded_blocks = sum(sum(blocks[m][lo:hi]) for kind, m, lo, hi, _ in got[1] if kind == "load")
+    loaded_whole = sum(shard_bytes(d) for e in whole if e[0] == "miss")
+    assert loaded_blocks < loaded_whole
