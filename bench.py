@@ -394,6 +394,8 @@ def main():
                     help="transfer mode of the timed region")
     ap.add_argument("--host-layout", choices=["separate", "packed"], default="separate",
                     help="how the parameter tensors lie in pinned host memory")
+    ap.add_argument("--block-residency", action="store_true",
+                    help="serve workload: residency per transfer block instead of per model")
     ap.add_argument("--copy-blocks", type=int, default=0, help="workgroups per copy kernel (0: library default)")
     ap.add_argument("--copy-cus", type=int, default=0, help="compute units reserved per transfer direction")
     args = ap.parse_args()

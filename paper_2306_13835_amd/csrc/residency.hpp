@@ -152,8 +152,9 @@ class RangeAllocator {
   // `busy` lists those ranges in the order their offloads complete (oldest
   // first).  Every hole is tried at its start and slid just past each busy
   // range; the cost of a placement is the position of the last busy range it
-  // overlaps (-1: none).  Lowest cost wins, then lowest offset.
-  uint64_t alloc_avoiding(uint64_t len, const std::vector<Range>& busy) {
+  // overlaps (-1: none).  Lowest cost wins, then lowest offset.  A placement
+  // whose cost exceeds max_cost is not taken (UINT64_MAX is returned).
+  uint64_t alloc_avoiding(uint64_t len, const std::vector<Range>& busy, int max_cost = INT32_MAX - 1) {
     int best_cost = INT32_MAX;
     uint64_t best_off = UINT64_MAX;
     auto consider = [&](const Range& hole, uint64_t off) {
@@ -170,7 +171,7 @@ class RangeAllocator {
       consider(hole, hole.off);
       for (const Range& b : busy) consider(hole, b.off + b.len);
     }
-    if (best_off == UINT64_MAX) return UINT64_MAX;
+    if (best_off == UINT64_MAX || best_cost > max_cost) return UINT64_MAX;
     alloc_at(best_off, len);
     return best_off;
   }

@@ -388,8 +388,8 @@ int ensure_resident(ctn_ctx* c, int mi) {
     for (int b = 0; b < L.n_blocks; ++b) m->block_off[b] = off + L.block_start[b];
   } else {
     const int n_missing = L.n_blocks - first;
-    // all missing blocks side by side when a hole allows it, else slot by slot
-    const uint64_t together = c->arena.alloc_avoiding(L.slot_bytes * n_missing, busy_ranges());
+    // all missing blocks side by side when a hole that no offload is reading allows it, else slot by slot
+    const uint64_t together = c->arena.alloc_avoiding(L.slot_bytes * n_missing, busy_ranges(), -1);
     if (together != UINT64_MAX) {
       placed.push_back({together, L.slot_bytes * n_missing});
       for (int b = first; b < L.n_blocks; ++b) m->block_off[b] = together + L.slot_bytes * (b - first);

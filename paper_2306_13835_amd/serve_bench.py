@@ -36,11 +36,15 @@ def run_serve(args):
     # more range so that a victim can still be streaming out of its range while the requested model
     # streams into another one, as the paper's overlapped offload and load do (Sections 3.2, 5.1).
     resident_max = budget // nbytes
-    arena = torch.empty((resident_max + 1) * P.arena_bytes(desc), dtype=torch.uint8, device="cuda")
+    blocks = bool(getattr(args, "block_residency", False))
+    # Block residency: every transfer block takes one slot; the slack of the budget below another whole
+    # model holds a prefix of one more model, so the arena gets one more range than the whole-model case.
+    one = P.slot_bytes(desc) * (desc.layers + 1) if blocks else P.arena_bytes(desc)
+    arena = torch.empty((resident_max + (2 if blocks else 1)) * one, dtype=torch.uint8, device="cuda")
     ws = torch.empty(P.workspace_bytes(desc, batch * seq), dtype=torch.uint8, device="cuda")
     logits = torch.empty(batch, seq, desc.vocab // desc.tp, dtype=torch.float32, device="cuda")
     ctx = P.Context(budget, arena, ws, transfer_mode={"dma": 0, "kernel": 1, "auto": 2}[args.transfer],
-                    pipeline=True)
+                    pipeline=True, block_residency=blocks)
     n_t = len(param_list(desc))
     pool = P.HostPool(n_models * (nbytes + n_t * (256 + gap)) + 8192)
     t0 = time.time()
@@ -61,6 +65,7 @@ def run_serve(args):
         ctx.swap_out(m)
     ctx.sync()
     ev0 = len(ctx.events())
+    bev0 = len(ctx.block_events())
     st0 = ctx.stats()
     last = [time.time()]
 
@@ -70,31 +75,49 @@ def run_serve(args):
             log(f"[serve] request {i + 1}/{n_req}")
 
     t0 = time.perf_counter()
-    lat, svc, miss = serve_trace(ctx, models, arr, mod, lambda i: ids[i], logits, progress=progress)
+    missing = []
+    lat, svc, miss = serve_trace(ctx, models, arr, mod, lambda i: ids[i], logits, progress=progress,
+                                 missing_blocks=missing)
+    missing = np.asarray(missing)
+    whole_miss = missing == desc.layers + 1
+    part_miss = (missing > 0) & ~whole_miss
     wall = time.perf_counter() - t0
     ctx.sync()
     st = ctx.stats()
     events = ctx.events()[ev0:]
     # the decisions taken on the GPU path must be the ones the policy takes on the bare trace
-    replay = P.residency_replay(budget, [nbytes] * n_models, [int(x) for x in mod])
-    decisions_match = [(e[0], e[1], e[2]) for e in events] == replay
+    if blocks:
+        n = [2 * int(np.prod(shape)) for _, shape, _ in param_list(desc)]
+        bb = [n[0] + n[1] + n[-2] + n[-1]] + [sum(n[2 + 16 * l:18 + 16 * l]) for l in range(desc.layers)]
+        replay, block_replay = P.block_residency_replay(budget, [bb] * n_models, [int(x) for x in mod])
+        got_blocks = [(k, m, lo, hi, use - ev0) for k, m, lo, hi, use in ctx.block_events()[bev0:]]
+        decisions_match = [(e[0], e[1], e[2]) for e in events] == replay and got_blocks == block_replay
+    else:
+        replay = P.residency_replay(budget, [nbytes] * n_models, [int(x) for x in mod])
+        decisions_match = [(e[0], e[1], e[2]) for e in events] == replay
     n_miss = st["n_miss"] - st0["n_miss"]
     res = {
-        "metric": "p99 request latency under swap (8 models, 2 resident, Gamma CV=4 / Zipf 1.5 arrivals)",
+        "metric": "p99 request latency under swap (8 models, budget 20e9 B, Gamma CV=4 / Zipf 1.5 arrivals)",
         "value": round(float(np.percentile(lat, 99)), 4), "unit": "s", "n_gpus": 1, "steps": n_req, "warmup": 3,
         "ms_per_step": round(wall / n_req * 1e3, 3), "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"serve8x6.7b_tp2: {n_models} shards x {nbytes} B, budget {budget} B, {n_req} requests "
                                f"batch {batch} x seq {seq}, serial oldest-first engine, LRU",
                    "transfer": args.transfer, "host_layout": args.host_layout,
+                   "residency": "per transfer block (prefix kept)" if blocks else "whole models (2 resident)",
                    "arena_bytes": int(arena.numel()), "arena_note": "budget + one transit range"},
         "latency_s": {"mean": round(float(lat.mean()), 4), "p50": round(float(np.percentile(lat, 50)), 4),
                       "p90": round(float(np.percentile(lat, 90)), 4), "p99": round(float(np.percentile(lat, 99)), 4),
                       "max": round(float(lat.max()), 4)},
         "service_ms": {"hit_p50": round(float(np.median(svc[~miss]) * 1e3), 3) if (~miss).any() else None,
                        "miss_p50": round(float(np.median(svc[miss]) * 1e3), 3) if miss.any() else None,
-                       "miss_max": round(float(svc[miss].max() * 1e3), 3) if miss.any() else None},
+                       "miss_max": round(float(svc[miss].max() * 1e3), 3) if miss.any() else None,
+                       "whole_miss_p50": round(float(np.median(svc[whole_miss]) * 1e3), 3) if whole_miss.any() else None,
+                       "partial_miss_p50": round(float(np.median(svc[part_miss]) * 1e3), 3) if part_miss.any() else None,
+                       "partial_miss_blocks_p50": float(np.median(missing[part_miss])) if part_miss.any() else None},
         "misses": int(n_miss), "hit_ratio": round(1 - n_miss / n_req, 4),
+        "partial_misses": st["n_partial_miss"] - st0["n_partial_miss"],
+        "extra_evictions": st["n_extra_evictions"] - st0["n_extra_evictions"],
         "bytes_swapped_in": st["bytes_h2d"] - st0["bytes_h2d"], "trace_seconds": round(float(arr[-1]), 2),
         "wall_seconds": round(wall, 2), "peak_resident_bytes": st["peak_resident_bytes"],
         "decisions_equal_policy_replay": bool(decisions_match),

@@ -16,8 +16,9 @@ import numpy as np
 
 def serve_trace(ctx, models: Sequence[int], arrival_s: np.ndarray, model_of: np.ndarray,
                 ids_of: Callable[[int], np.ndarray], out, time_scale: float = 1.0,
-                progress: Callable[[int], None] = None):
-    """Replays the trace; returns (latency_s, service_s, was_miss) arrays.
+                progress: Callable[[int], None] = None, missing_blocks: list = None):
+    """Replays the trace; returns (latency_s, service_s, was_miss) arrays.  `missing_blocks`, if
+    given, receives per request the number of transfer blocks that had to be loaded.
 
     `out` is a device tensor receiving the logits of each request (overwritten every time);
     a request is complete when its logits are complete on the compute stream.
@@ -35,6 +36,9 @@ def serve_trace(ctx, models: Sequence[int], arrival_s: np.ndarray, model_of: np.
         m = models[int(model_of[i])]
         start = time.perf_counter() - t0
         miss[i] = not ctx.is_resident(m)
+        if missing_blocks is not None:
+            k, nb = ctx.resident_blocks(m)
+            missing_blocks.append(nb - k)
         ctx.infer(m, ids_of(i), out=out)
         ctx.stream_compute.synchronize()
         end = time.perf_counter() - t0

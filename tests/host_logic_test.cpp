@@ -37,6 +37,13 @@ int main() {
           for (auto& b : busy) ok &= !overlaps(o, len, b.off, b.len);
           clean |= ok;
         }
+        {   // a placement that must not touch a busy range exists exactly when brute force finds one
+          RangeAllocator probe = ra;
+          const uint64_t o = probe.alloc_avoiding(len, busy, -1);
+          assert((o != UINT64_MAX) == clean);
+          if (o != UINT64_MAX)
+            for (auto& b : busy) assert(!overlaps(o, len, b.off, b.len));
+        }
         const bool used_avoiding = rng() % 2;
         const uint64_t off = used_avoiding ? ra.alloc_avoiding(len, busy) : (busy.clear(), ra.alloc(len));
         if (!any) { assert(off == UINT64_MAX); continue; }
