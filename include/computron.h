@@ -116,6 +116,7 @@ typedef struct {
   uint64_t n_partial_miss;             /* misses that found a prefix of the model resident (block residency) */
   uint64_t n_extra_evictions;          /* eviction steps taken because no arena hole was wide enough
                                           although the budget had room (not part of the policy) */
+  uint64_t n_prefetch;                 /* swap-ins started ahead of a request by ctn_engine_idle */
 } ctn_stats;
 
 /* Residency event, in the order decisions were taken (Section 3: replacement
@@ -285,6 +286,22 @@ int ctn_engine_submit(ctn_engine* eng, ctn_model m, const int32_t* ids_host, dou
 int ctn_engine_step(ctn_engine* eng, void* logits_out, int64_t* served_ids, int32_t cap, int32_t* n_served,
                     ctn_model* model, int32_t* was_miss);
 int ctn_engine_pending(ctn_engine* eng, int64_t* n);
+/* Loading ahead (the paper's closing section: speculative loads for request
+ * streams with structure).  The engine keeps a first-order transition table
+ * over its dispatches; after a dispatch of model a it predicts the model that
+ * most often followed a (ties: lowest handle) if that was seen at least
+ * min_count times and is at least min_share_percent per cent of the
+ * transitions out of a.  enable == 0 switches it off (the default). */
+int ctn_engine_set_prefetch(ctn_engine* eng, int32_t enable, int32_t min_count, int32_t min_share_percent);
+/* To be called when the caller has nothing to submit.  If no request is
+ * queued, loading ahead is on and the predicted model is not completely
+ * resident, it is swapped in (an ordinary ctn_swap_in: asynchronous, a use
+ * for the replacement policy, victims evicted as needed).  *loaded receives
+ * that model's handle, -1 when nothing was done. */
+int ctn_engine_idle(ctn_engine* eng, ctn_model* loaded);
+/* Host only: the prediction after each of n dispatches (host arrays; -1 = none). */
+int ctn_predictor_replay(int32_t n_models, int32_t min_count, int32_t min_share_percent,
+                         const int32_t* dispatches, uint64_t n, int32_t* predictions);
 /* Host only, simulated clock: replays a trace (arrival times ascending, host
  * arrays of n entries) through the same queues, batch selection and
  * replacement policy; a batch of b requests takes t_base + b * t_per_request

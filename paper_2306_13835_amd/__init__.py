@@ -7,8 +7,8 @@ raises if it has not been built (there is no CPU fallback).
 """
 from .binding import (lib, Context, Engine, engine_replay, HostPool, CtnError, XFER_DMA, XFER_KERNEL, XFER_AUTO, EPI_BIAS_F16,
                       EPI_BIAS_RELU_F16, EPI_BIAS_RESID_F32, EPI_F32, residency_replay,
-                      workspace_bytes, arena_bytes, slot_bytes, block_residency_replay, LIB_PATH, DECLARED_SYMBOLS)
+                      workspace_bytes, arena_bytes, slot_bytes, block_residency_replay, predictor_replay, LIB_PATH, DECLARED_SYMBOLS)
 
 __all__ = ["lib", "Context", "Engine", "engine_replay", "HostPool", "CtnError", "XFER_DMA", "XFER_KERNEL", "XFER_AUTO", "EPI_BIAS_F16",
            "EPI_BIAS_RELU_F16", "EPI_BIAS_RESID_F32", "EPI_F32", "residency_replay",
-           "workspace_bytes", "arena_bytes", "slot_bytes", "block_residency_replay", "LIB_PATH", "DECLARED_SYMBOLS"]
+           "workspace_bytes", "arena_bytes", "slot_bytes", "block_residency_replay", "predictor_replay", "LIB_PATH", "DECLARED_SYMBOLS"]

@@ -21,6 +21,7 @@ DECLARED_SYMBOLS = [
     "ctn_op_gemm", "ctn_op_gemm_ws", "ctn_op_attention", "ctn_debug_gemm_tile", "ctn_engine_create", "ctn_engine_destroy",
     "ctn_engine_submit", "ctn_engine_step", "ctn_engine_pending", "ctn_engine_replay",
     "ctn_slot_bytes", "ctn_resident_blocks", "ctn_get_block_events", "ctn_block_residency_replay",
+    "ctn_engine_set_prefetch", "ctn_engine_idle", "ctn_predictor_replay",
 ]
 
 
@@ -44,7 +45,7 @@ class Config(C.Structure):
 class Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("bytes_h2d", "bytes_d2h", "n_swap_in", "n_swap_out", "n_hit",
                                           "n_miss", "n_infer", "resident_bytes", "peak_resident_bytes",
-                                          "budget_bytes", "n_partial_miss", "n_extra_evictions")]
+                                          "budget_bytes", "n_partial_miss", "n_extra_evictions", "n_prefetch")]
 
 
 class Event(C.Structure):
@@ -128,6 +129,9 @@ def lib() -> C.CDLL:
         "ctn_engine_submit": (C.c_int, [vp, i32, vp, C.c_double, P(i64)]),
         "ctn_engine_step": (C.c_int, [vp, vp, P(i64), i32, P(i32), P(i32), P(i32)]),
         "ctn_engine_pending": (C.c_int, [vp, P(i64)]),
+        "ctn_engine_set_prefetch": (C.c_int, [vp, i32, i32, i32]),
+        "ctn_engine_idle": (C.c_int, [vp, P(i32)]),
+        "ctn_predictor_replay": (C.c_int, [i32, i32, i32, P(i32), u64, P(i32)]),
         "ctn_engine_replay": (C.c_int, [i32, i32, u64, P(u64), P(C.c_double), P(i32), u64, C.c_double, C.c_double,
                                         C.c_double, P(BatchRecord), u64, P(u64), P(u64)]),
     }
@@ -194,6 +198,17 @@ def residency_replay(budget: int, sizes: Sequence[int], trace: Sequence[int]):
     return _events_to_list(out, n)
 
 
+def predictor_replay(n_models: int, dispatches: Sequence[int], min_count: int = 2, min_share_percent: int = 50):
+    """Host-only replay of the load-ahead predictor: prediction (or None) after each dispatch."""
+    n = len(dispatches)
+    d = (C.c_int32 * max(n, 1))(*[int(x) for x in dispatches])
+    out = (C.c_int32 * max(n, 1))()
+    rc = lib().ctn_predictor_replay(n_models, min_count, min_share_percent, d, n, out)
+    if rc:
+        raise CtnError(rc, "ctn_predictor_replay")
+    return [None if out[i] < 0 else int(out[i]) for i in range(n)]
+
+
 def engine_replay(n_models: int, max_batch: int, budget: int, sizes: Sequence[int], arrival, model_of,
                   t_base: float, t_per_request: float, t_miss: float):
     """Host-only replay of the scheduler; returns [(start, finish, model, request indices, miss)]."""
@@ -244,6 +259,20 @@ class Engine:
         if n.value == 0:
             return None
         return [int(self._served[i]) for i in range(n.value)], m.value, bool(miss.value)
+
+    def set_prefetch(self, enable: bool, min_count: int = 2, min_share_percent: int = 50):
+        rc = lib().ctn_engine_set_prefetch(self.h, int(bool(enable)), min_count, min_share_percent)
+        if rc:
+            raise CtnError(rc, "ctn_engine_set_prefetch")
+
+    def idle(self) -> Optional[int]:
+        """Nothing to submit right now: lets the engine load the predicted next model ahead.
+        Returns that model's handle, or None when nothing was started."""
+        m = C.c_int32(-1)
+        rc = lib().ctn_engine_idle(self.h, C.byref(m))
+        if rc:
+            raise CtnError(rc, "ctn_engine_idle", lib().ctn_last_hip_error(self.ctx.h) if rc == -5 else 0)
+        return None if m.value < 0 else m.value
 
     def pending(self) -> int:
         n = C.c_int64()

@@ -52,4 +52,46 @@ class RequestQueues {
   std::vector<std::deque<QueuedRequest>> q_;
 };
 
+// Which model to load ahead of its next request.  The paper's closing section
+// proposes speculative loading for request streams with structure (a model
+// requested repeatedly, models requested in a fixed order); this is a
+// first-order transition table over the dispatches: after a dispatch of model
+// a the prediction is the model that most often followed a (ties: lowest
+// index) if it was seen at least min_count times and makes up at least
+// min_share_percent per cent of the transitions out of a; -1 otherwise.
+class TransitionPredictor {
+ public:
+  void configure(int min_count, int min_share_percent) {
+    min_count_ = min_count;
+    min_share_percent_ = min_share_percent;
+  }
+  void observe(int m) {
+    const int n = static_cast<int>(count_.size());
+    if (m >= n) {
+      for (auto& row : count_) row.resize(m + 1, 0);
+      count_.resize(m + 1, std::vector<int64_t>(m + 1, 0));
+    }
+    if (last_ >= 0) count_[last_][m] += 1;
+    last_ = m;
+  }
+  int predict() const {
+    if (last_ < 0) return -1;
+    const std::vector<int64_t>& row = count_[last_];
+    int best = 0;
+    int64_t total = 0;
+    for (int b = 0; b < static_cast<int>(row.size()); ++b) {
+      total += row[b];
+      if (row[b] > row[best]) best = b;
+    }
+    if (row[best] == 0 || row[best] < min_count_) return -1;
+    if (100 * row[best] < static_cast<int64_t>(min_share_percent_) * total) return -1;
+    return best;
+  }
+
+ private:
+  std::vector<std::vector<int64_t>> count_;
+  int last_ = -1;
+  int min_count_ = 2, min_share_percent_ = 50;
+};
+
 }  // namespace ctn

@@ -1099,11 +1099,13 @@ struct ctn_engine {
   RequestQueues queues;
   int64_t next_id = 0;
   std::vector<int32_t> packed;   // ids of the batch being dispatched
+  TransitionPredictor predictor;
+  bool prefetch = false;
 };
 
 int ctn_engine_create(ctn_ctx* c, int32_t max_batch, int32_t seq, ctn_engine** out) {
   if (!c || !out || max_batch < 1 || seq < 1) return CTN_E_INVAL;
-  ctn_engine* e = new (std::nothrow) ctn_engine{c, max_batch, seq, RequestQueues(), 0, {}};
+  ctn_engine* e = new (std::nothrow) ctn_engine{c, max_batch, seq, RequestQueues(), 0, {}, {}, false};
   if (!e) return CTN_E_NOMEM;
   *out = e;
   return CTN_OK;
@@ -1153,6 +1155,43 @@ int ctn_engine_step(ctn_engine* e, void* logits_out, int64_t* served, int32_t ca
   }
   for (size_t i = 0; i < batch.size(); ++i) served[i] = batch[i].id;
   *n_served = static_cast<int32_t>(batch.size());
+  e->predictor.observe(m);
+  return CTN_OK;
+}
+
+int ctn_engine_set_prefetch(ctn_engine* e, int32_t enable, int32_t min_count, int32_t min_share_percent) {
+  if (!e || min_count < 1 || min_share_percent < 0 || min_share_percent > 100) return CTN_E_INVAL;
+  e->prefetch = enable != 0;
+  e->predictor.configure(min_count, min_share_percent);
+  return CTN_OK;
+}
+
+int ctn_engine_idle(ctn_engine* e, ctn_model* loaded) {
+  if (!e || !loaded) return CTN_E_INVAL;
+  *loaded = -1;
+  if (!e->prefetch || e->queues.pending() > 0) return CTN_OK;
+  const int p = e->predictor.predict();
+  Model* m = get_model(e->ctx, p);
+  if (!m || m->full()) return CTN_OK;
+  const int rc = ctn_swap_in(e->ctx, p);
+  if (rc) return rc;
+  e->ctx->stats.n_prefetch += 1;
+  *loaded = p;
+  return CTN_OK;
+}
+
+int ctn_predictor_replay(int32_t n_models, int32_t min_count, int32_t min_share_percent, const int32_t* dispatches,
+                         uint64_t n, int32_t* predictions) {
+  if (n_models <= 0 || min_count < 1 || min_share_percent < 0 || min_share_percent > 100 ||
+      (n && (!dispatches || !predictions)))
+    return CTN_E_INVAL;
+  TransitionPredictor p;
+  p.configure(min_count, min_share_percent);
+  for (uint64_t i = 0; i < n; ++i) {
+    if (dispatches[i] < 0 || dispatches[i] >= n_models) return CTN_E_NOMODEL;
+    p.observe(dispatches[i]);
+    predictions[i] = p.predict();
+  }
   return CTN_OK;
 }
 

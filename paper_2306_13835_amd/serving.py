@@ -72,6 +72,7 @@ def serve_engine(ctx, engine, models: Sequence[int], arrival_s: np.ndarray, mode
         start = time.perf_counter() - t0
         r = engine.step(out)
         if r is None:
+            engine.idle()            # nothing queued: the engine may load the predicted next model ahead
             pause = arrival_s[nxt] - (time.perf_counter() - t0)
             if pause > 0:
                 time.sleep(pause)

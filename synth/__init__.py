@@ -8,10 +8,10 @@ the HIP binding.
 """
 from .shapes import ShardDesc, CONFIGS, param_list, shard_bytes, shard_params, forward_flop
 from .weights import fill_shard, token_ids
-from .arrivals import gamma_zipf_trace, gamma_rates_trace
+from .arrivals import gamma_zipf_trace, gamma_rates_trace, cyclic_trace
 
 __all__ = [
     "ShardDesc", "CONFIGS", "param_list", "shard_bytes", "shard_params",
     "forward_flop", "fill_shard", "token_ids", "gamma_zipf_trace",
-    "gamma_rates_trace",
+    "gamma_rates_trace", "cyclic_trace",
 ]

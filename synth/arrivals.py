@@ -61,3 +61,14 @@ def gamma_zipf_trace(n_models: int, total_rate: float, cv: float, zipf_s: float,
         if t.size >= n_requests:
             return t[:n_requests].copy(), m[:n_requests].copy()
         horizon *= 1.5
+
+
+def cyclic_trace(n_models: int, period_s: float, n_requests: int, jitter: float = 0.0,
+                 seed: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """Models requested in a fixed order (0, 1, ..., n-1, 0, ...), one request every `period_s`
+    seconds, each arrival shifted by a uniform draw from [0, jitter * period_s).  The kind of
+    structured stream the paper's closing section gives as a case for loading ahead."""
+    rng = np.random.Generator(np.random.Philox(key=[seed, 0]))
+    t = period_s * (np.arange(n_requests, dtype=np.float64) + jitter * rng.random(n_requests))
+    m = (np.arange(n_requests) % n_models).astype(np.int32)
+    return t, m

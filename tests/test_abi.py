@@ -158,3 +158,21 @@ def test_block_granular_policy_on_the_serving_shapes():
     loaded_blocks = sum(sum(blocks[m][lo:hi]) for kind, m, lo, hi, _ in got[1] if kind == "load")
     loaded_whole = sum(shard_bytes(d) for e in whole if e[0] == "miss")
     assert loaded_blocks < loaded_whole
+
+
+def test_load_ahead_predictor_equals_oracle():
+    from oracle.prefetch import replay as predict_replay
+    rng = np.random.default_rng(21)
+    for case in range(100):
+        n = int(rng.integers(1, 7))
+        if case % 3 == 0:                      # a noisy cycle, the structure the predictor is for
+            cycle = list(rng.permutation(n))
+            seq = [int(cycle[i % n]) if rng.random() < 0.8 else int(rng.integers(0, n)) for i in range(80)]
+        else:
+            seq = [int(x) for x in rng.integers(0, n, size=80)]
+        mc, share = int(rng.integers(1, 4)), int(rng.integers(0, 101))
+        assert P.predictor_replay(n, seq, mc, share) == predict_replay(n, seq, mc, share)
+    with pytest.raises(P.CtnError):
+        P.predictor_replay(2, [0, 2])
+    with pytest.raises(P.CtnError):
+        P.predictor_replay(2, [0, 1], min_count=0)

@@ -240,3 +240,58 @@ def test_engine_batches_rows_match_oracle_forward():
     finally:
         eng.close()
         rig.close()
+
+
+def test_engine_loads_ahead_on_a_cyclic_stream():
+    """Three models requested in a fixed order with room for two: LRU alone misses every time; with
+    loading ahead the engine, once it has seen the cycle twice, has the next model on its way in
+    before the request comes.  Predictions equal the oracle's, logits stay right, bytes survive."""
+    from oracle import opt_shard as O
+    from oracle.prefetch import TransitionPredictor
+    from synth import token_ids
+    desc = ShardDesc(2, 256, 1024, 4, vocab=1000, max_pos=64)
+    size = shard_bytes(desc)
+    rig = Rig([desc] * 3, budget=2 * size, arena_bytes=3 * P.arena_bytes(desc), max_tokens=8, mode=P.XFER_AUTO)
+    eng = P.Engine(rig.ctx, max_batch=1, seq=8)
+    try:
+        ms = [rig.add(desc, seed=110 + i) for i in range(3)]
+        orig = [[t.copy() for t in rig.tensors[m]] for m in ms]
+        ids = [token_ids(400 + i, 1, 8, desc.vocab) for i in range(3)]
+        want = [O.forward(rig.tensors[m], ids[m], layers=desc.layers, heads=desc.heads) for m in ms]
+        out = torch.empty(1, 8, desc.vocab, dtype=torch.float32, device="cuda")
+        assert eng.idle() is None                       # off by default
+        eng.set_prefetch(True, min_count=2, min_share_percent=50)
+        ref = TransitionPredictor(3, 2, 50)
+        misses, loaded_ahead = [], []
+        for i in range(15):
+            m = i % 3
+            eng.submit(ms[m], ids[m], float(i))
+            served, model, miss = eng.step(out)
+            rig.ctx.stream_compute.synchronize()
+            assert model == m and served == [i]
+            got = out.cpu().numpy()
+            assert np.abs(got - want[m]).max() <= 2e-2
+            ref.observe(m)
+            misses.append(miss)
+            p = eng.idle()                              # nothing queued: the prediction may be loaded
+            expect = ref.predict()
+            if expect is not None and not rig.ctx.is_resident(expect) and p is None:
+                raise AssertionError("a confident prediction of a non-resident model was not loaded")
+            if p is not None:
+                assert p == expect
+                rig.ctx.wait(p)
+            loaded_ahead.append(p)
+        # the cycle's three transitions have each been seen twice after 7 dispatches
+        assert misses[:7] == [True] * 7 and misses[7:] == [False] * 8
+        assert loaded_ahead[6:14] == [(i + 1) % 3 for i in range(6, 14)]
+        assert rig.ctx.stats()["n_prefetch"] == sum(p is not None for p in loaded_ahead)
+        eng.submit(ms[0], ids[0], 99.0)
+        assert eng.idle() is None                       # a request is queued: no speculation
+        eng.step(out)
+        rig.ctx.sync()
+        for m in ms:
+            for t, o in zip(rig.tensors[m], orig[m]):
+                assert np.array_equal(as_bytes(t), as_bytes(o))
+    finally:
+        eng.close()
+        rig.close()
