@@ -112,8 +112,9 @@ def decoder_layer(x: np.ndarray, w: Dict[str, np.ndarray], heads: int,
     return x
 
 
-def layer_weights(params: Sequence[np.ndarray], layer: int, dtype) -> Dict[str, np.ndarray]:
-    base = 2 + TENSORS_PER_LAYER * layer
+def layer_weights(params: Sequence[np.ndarray], layer: int, dtype, first: int = 2) -> Dict[str, np.ndarray]:
+    """The 16 tensors of the `layer`-th layer held in `params`, whose layer tensors start at index `first`."""
+    base = first + TENSORS_PER_LAYER * layer
     return {k: np.asarray(params[base + i]).astype(dtype) for i, k in enumerate(_LAYER_KEYS)}
 
 
@@ -141,3 +142,42 @@ def forward(params: Sequence[np.ndarray], ids: np.ndarray, *, layers: int, heads
             taps.append(x.copy())
     y = layer_norm(x, np.asarray(params[-2]).astype(dtype), np.asarray(params[-1]).astype(dtype))
     return y @ np.asarray(params[0]).astype(dtype).T
+
+
+def forward_stage(params: Sequence[np.ndarray], inp: np.ndarray, *, layers: int, heads: int,
+                  tp: int = 1, rank: int = 0, pp: int = 1, stage: int = 0, dtype=np.float32,
+                  hook: Optional[Callable[[np.ndarray], np.ndarray]] = None) -> np.ndarray:
+    """One pipeline stage of one rank.
+
+    The paper splits models by tensor *and* pipeline parallelism (Section 5.1:
+    swapping gets faster with either).  A pipeline stage owns a contiguous
+    range of decoder layers: stage p of `pp` holds layers [p*L/pp, (p+1)*L/pp).
+    Stage 0 also holds the embeddings and starts from token ids; the last
+    stage also holds the final LayerNorm and its own copy of the (tied) head
+    matrix and ends in logits; every other boundary carries the residual
+    stream [b, s, h].  `layers` is the whole model's layer count and `params`
+    the stage's list: [embed_tokens, embed_positions] if stage 0, 16 tensors
+    per local layer, [final_ln.w, final_ln.b] if last, then lm_head if last
+    and pp > 1 (with pp == 1 the head is embed_tokens, as in `forward`).
+    """
+    if layers % pp or not 0 <= stage < pp:
+        raise ValueError("layers must divide evenly into stages")
+    local = layers // pp
+    is_first, is_last = stage == 0, stage == pp - 1
+    n_front = 2 if is_first else 0
+    n_back = (3 if pp > 1 else 2) if is_last else 0
+    if len(params) != n_front + TENSORS_PER_LAYER * local + n_back:
+        raise ValueError("parameter list has the wrong length for this stage")
+    hook = hook or (lambda z: z)
+    if is_first:
+        x = embed(inp, params[0], params[1], rank, dtype, hook)
+    else:
+        x = np.asarray(inp).astype(dtype)
+    for l in range(local):
+        x = decoder_layer(x, layer_weights(params, l, dtype, first=n_front), heads // tp, hook)
+    if not is_last:
+        return x
+    at = n_front + TENSORS_PER_LAYER * local
+    y = layer_norm(x, np.asarray(params[at]).astype(dtype), np.asarray(params[at + 1]).astype(dtype))
+    head = params[at + 2] if pp > 1 else params[0]
+    return y @ np.asarray(head).astype(dtype).T

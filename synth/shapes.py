@@ -29,11 +29,35 @@ class ShardDesc:
     max_pos: int = 2048
     tp: int = 1
     rank: int = 0
+    pp: int = 1      # pipeline stages the model is cut into (Section 5.1 evaluates TP x PP splits)
+    stage: int = 0   # this shard's stage: layers [stage*L/pp, (stage+1)*L/pp)
 
     def __post_init__(self):
         if self.hidden % self.heads or self.heads % self.tp or self.ffn % self.tp \
-                or self.vocab % self.tp or not (0 <= self.rank < self.tp):
+                or self.vocab % self.tp or not (0 <= self.rank < self.tp) \
+                or self.pp < 1 or self.layers % self.pp or not (0 <= self.stage < self.pp):
             raise ValueError(f"inconsistent shard description {self}")
+
+    @property
+    def local_layers(self) -> int:
+        return self.layers // self.pp
+
+    @property
+    def first_layer(self) -> int:
+        return self.stage * self.local_layers
+
+    @property
+    def has_embed(self) -> bool:
+        return self.stage == 0
+
+    @property
+    def has_head(self) -> bool:
+        return self.stage == self.pp - 1
+
+    @property
+    def out_features(self) -> int:
+        """Width of what one inference emits: a vocabulary slice of logits, or the residual stream."""
+        return self.local_vocab if self.has_head else self.hidden
 
     @property
     def head_dim(self) -> int:
@@ -71,13 +95,19 @@ EXTRA_TENSORS = 4
 
 
 def param_list(d: ShardDesc) -> List[ParamSpec]:
-    """Canonical `16*L + 4` tensor list of one rank, forward order."""
+    """Canonical tensor list of one rank (and pipeline stage), forward order.
+
+    Whole model on the rank (pp == 1): `16*L + 4` tensors.  With pipeline
+    stages: the embeddings only on stage 0, the stage's own layers, the final
+    LayerNorm only on the last stage, followed there by that stage's copy of
+    the tied head matrix (`lm_head`).
+    """
     h, hl, fl = d.hidden, d.local_hidden, d.local_ffn
-    out: List[ParamSpec] = [
-        ("embed_tokens", (d.local_vocab, h), "normal"),
-        ("embed_positions", (d.pos_rows, h), "normal"),
-    ]
-    for i in range(d.layers):
+    out: List[ParamSpec] = []
+    if d.has_embed:
+        out += [("embed_tokens", (d.local_vocab, h), "normal"),
+                ("embed_positions", (d.pos_rows, h), "normal")]
+    for i in range(d.first_layer, d.first_layer + d.local_layers):
         p = f"layers.{i}."
         out += [
             (p + "ln1.w", (h,), "gain"), (p + "ln1.b", (h,), "normal"),
@@ -89,8 +119,12 @@ def param_list(d: ShardDesc) -> List[ParamSpec]:
             (p + "fc1.w", (fl, h), "normal"), (p + "fc1.b", (fl,), "normal"),
             (p + "fc2.w", (h, fl), "normal"), (p + "fc2.b", (h,), "normal"),
         ]
-    out += [("final_ln.w", (h,), "gain"), ("final_ln.b", (h,), "normal")]
-    assert len(out) == LAYER_TENSORS * d.layers + EXTRA_TENSORS
+    if d.has_head:
+        out += [("final_ln.w", (h,), "gain"), ("final_ln.b", (h,), "normal")]
+        if d.pp > 1:
+            out += [("lm_head", (d.local_vocab, h), "normal")]
+    if d.pp == 1:
+        assert len(out) == LAYER_TENSORS * d.layers + EXTRA_TENSORS
     return out
 
 
@@ -115,8 +149,8 @@ def forward_flop(d: ShardDesc, batch: int, seq: int) -> int:
     h, hl, fl = d.hidden, d.local_hidden, d.local_ffn
     per_layer = 2 * m * (3 * hl * h + h * hl + 2 * fl * h)
     attn = 4 * batch * d.local_heads * seq * seq * d.head_dim
-    head = 2 * m * h * d.local_vocab
-    return d.layers * (per_layer + attn) + head
+    head = 2 * m * h * d.local_vocab if d.has_head else 0
+    return d.local_layers * (per_layer + attn) + head
 
 
 # The five workloads.  `batch`/`seq` are the forward shapes; seeds follow the
@@ -126,6 +160,9 @@ CONFIGS: Dict[str, dict] = {
     "opt1.3b_tp1": dict(desc=ShardDesc(24, 2048, 8192, 32), batch=8, seq=128, wseed=2, idseed=102),
     "opt6.7b_tp2": dict(desc=ShardDesc(32, 4096, 16384, 32, tp=2, rank=0), batch=4, seq=256, wseed=3, idseed=103),
     "opt13b_tp4": dict(desc=ShardDesc(40, 5120, 20480, 40, tp=4, rank=0), batch=16, seq=128, wseed=4, idseed=104),
+    # the paper's hybrid split of OPT-13B (Section 5.1: TP = 2 x PP = 2 on four GPUs): one GPU's share
+    "opt13b_tp2_pp2": dict(desc=ShardDesc(40, 5120, 20480, 40, tp=2, rank=0, pp=2, stage=0), batch=16, seq=128,
+                           wseed=6, idseed=106),
     "serve8x6.7b_tp2": dict(desc=ShardDesc(32, 4096, 16384, 32, tp=2, rank=0), batch=1, seq=64,
                             n_models=8, wseed=50, budget=20_000_000_000, n_requests=2000,
                             rate=20.0, cv=4.0, zipf=1.5, trace_seed=500, idseed=1000),

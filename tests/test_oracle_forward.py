@@ -209,3 +209,53 @@ def test_out_of_range_ids_use_zero_token_row():
     assert np.array_equal(x[0, 2], pos[4])
     assert np.array_equal(x[0, 1], full[0][20].astype(np.float64) + pos[3])
     assert np.array_equal(x[0, 3], full[0][16].astype(np.float64) + pos[5])
+
+
+def _tiny4(seed=13):
+    d = ShardDesc(layers=4, hidden=16, ffn=64, heads=4, vocab=32, max_pos=16)
+    p = fill_shard(d, seed, threads=1)
+    return d, [(a.astype(np.float32) * 8.0 if not (a.ndim == 1 and abs(float(a.astype(np.float32).mean()) - 1.0) < 0.2)
+                else 1.0 + (a.astype(np.float32) - 1.0) * 8.0).astype(np.float16) for a in p]
+
+
+@pytest.mark.parametrize("t", [1, 2])
+@pytest.mark.parametrize("pp", [1, 2, 4])
+def test_pipeline_stages_chain_to_the_brute_force_model(pp, t):
+    """Stage after stage, fed with the previous stage's residual stream, must end in the logits the
+    index-by-index brute force computes for the whole rank; every boundary equals the residual
+    stream the whole-model oracle records after that layer."""
+    from pp_split import stage_params
+    d, full = _tiny4()
+    ids = token_ids(17, 2, 5, d.vocab)
+    for r in range(t):
+        shard = split(full, d.layers, t, r)
+        want = np.array(brute_forward(tolist(shard), ids.tolist(), d.layers, d.heads, t, r))
+        taps = []
+        O.forward(shard, ids, layers=d.layers, heads=d.heads, tp=t, rank=r, dtype=np.float64, taps=taps)
+        x = ids
+        for stage in range(pp):
+            sp = stage_params(shard, d.layers, pp, stage)
+            x = O.forward_stage(sp, x, layers=d.layers, heads=d.heads, tp=t, rank=r, pp=pp, stage=stage,
+                                dtype=np.float64)
+            if stage < pp - 1:
+                assert x.shape == (2, 5, d.hidden)
+                assert np.array_equal(x, taps[(stage + 1) * d.layers // pp])
+        assert x.shape == (2, 5, d.vocab // t)
+        assert np.abs(x - want).max() < 1e-11
+
+
+def test_pipeline_stage_argument_checks():
+    from pp_split import stage_params
+    d, full = _tiny4()
+    ids = token_ids(17, 1, 3, d.vocab)
+    with pytest.raises(ValueError):
+        O.forward_stage(full, ids, layers=4, heads=4, pp=3, stage=0)                 # 4 layers, 3 stages
+    with pytest.raises(ValueError):
+        O.forward_stage(stage_params(full, 4, 2, 0), ids, layers=4, heads=4, pp=2, stage=1)   # wrong list
+    # a wrong head matrix or a skipped embedding must show: the last stage uses its own copy
+    sp = stage_params(full, 4, 2, 1)
+    x = np.random.default_rng(1).standard_normal((1, 3, d.hidden))
+    a = O.forward_stage(sp, x, layers=4, heads=4, pp=2, stage=1, dtype=np.float64)
+    sp[-1] = sp[-1] * 2
+    b = O.forward_stage(sp, x, layers=4, heads=4, pp=2, stage=1, dtype=np.float64)
+    assert np.allclose(b, 2 * a)
