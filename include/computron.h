@@ -49,13 +49,19 @@ enum {
 
 enum { CTN_XFER_DMA = 0, CTN_XFER_KERNEL = 1, CTN_XFER_AUTO = 2 };
 
-/* One rank's share of an OPT decoder.  heads, ffn and vocab are those of the
- * whole model; the rank owns heads/tp heads, ffn/tp hidden units, vocab/tp
- * token rows.  Requirements: hidden % heads == 0, head size 64 or 128,
- * heads % tp == 0, ffn % tp == 0, vocab % tp == 0, (hidden/tp) % 8 == 0,
- * (ffn/tp) % 8 == 0, 0 <= rank < tp, max_pos >= 1. */
+/* One rank's share of an OPT decoder.  layers, heads, ffn and vocab are those
+ * of the whole model; the rank owns heads/tp heads, ffn/tp hidden units,
+ * vocab/tp token rows.  pp > 1 (Section 5.1: models are split by tensor and by
+ * pipeline parallelism): the shard is pipeline stage `stage` of pp and holds
+ * the layers [stage*layers/pp, (stage+1)*layers/pp); stage 0 also holds the
+ * embeddings, the last stage the final LayerNorm and its own copy of the tied
+ * head matrix.  pp of 0 or 1: all layers.  Requirements: hidden % heads == 0,
+ * head size 64 or 128, heads % tp == 0, ffn % tp == 0, vocab % tp == 0,
+ * (hidden/tp) % 8 == 0, (ffn/tp) % 8 == 0, 0 <= rank < tp, max_pos >= 1,
+ * layers % pp == 0, 0 <= stage < pp. */
 typedef struct {
   int32_t layers, hidden, ffn, heads, vocab, max_pos, tp, rank;
+  int32_t pp, stage;
 } ctn_model_desc;
 
 /* One parameter tensor, fp16, C-contiguous.  host_ptr (host, also readable
@@ -161,6 +167,9 @@ int ctn_host_free(void* p);
  *              o.w[hidden, hidden/tp] o.b[hidden] ln2.w ln2.b
  *              fc1.w[ffn/tp, hidden] fc1.b fc2.w[hidden, ffn/tp] fc2.b[hidden],
  *   final_ln.w, final_ln.b                       (n == 16*layers + 4).
+ * A pipeline stage (desc->pp > 1) lists: the two embeddings only on stage 0;
+ * its own layers; final_ln.w, final_ln.b and then lm_head[vocab/tp, hidden]
+ * (the stage's copy of the tied head matrix) only on the last stage.
  * Weight matrices are [out, in] row major.  hbm_budget_bytes is the manager
  * wide budget: 0 keeps the context's value, any other value must equal it.
  * The model starts swapped out.  Errors: CTN_E_INVAL, CTN_E_TOO_BIG. */
@@ -196,6 +205,15 @@ int ctn_sync(ctn_ctx* ctx);
  * workspace cannot hold batch*seq tokens (see ctn_workspace_bytes). */
 int ctn_infer(ctn_ctx* ctx, ctn_model m, const int32_t* token_ids_host, int32_t batch, int32_t seq,
               void* logits_out, int32_t out_is_device);
+/* The same for any pipeline stage.  Stage 0 starts from token_ids_host
+ * (hidden_in must be NULL); later stages start from hidden_in, the residual
+ * stream fp32 [batch, seq, hidden] the previous stage emitted (device pointer
+ * when in_is_device != 0, else host; token_ids_host is ignored).  out receives
+ * fp32 [batch, seq, hidden] (the residual stream after the stage's last
+ * layer) or, on the last stage, the logits fp32 [batch, seq, vocab/tp].
+ * ctn_infer(m, ids, ...) is ctn_infer_stage(m, ids, NULL, 0, ...). */
+int ctn_infer_stage(ctn_ctx* ctx, ctn_model m, const int32_t* token_ids_host, const void* hidden_in,
+                    int32_t in_is_device, int32_t batch, int32_t seq, void* out, int32_t out_is_device);
 
 /* Workspace bytes a context needs for models of this description at up to
  * max_tokens = batch*seq tokens per inference and n_models registrations. */

@@ -21,12 +21,13 @@ DECLARED_SYMBOLS = [
     "ctn_op_gemm", "ctn_op_gemm_ws", "ctn_op_attention", "ctn_debug_gemm_tile", "ctn_engine_create", "ctn_engine_destroy",
     "ctn_engine_submit", "ctn_engine_step", "ctn_engine_pending", "ctn_engine_replay",
     "ctn_slot_bytes", "ctn_resident_blocks", "ctn_get_block_events", "ctn_block_residency_replay",
-    "ctn_engine_set_prefetch", "ctn_engine_idle", "ctn_predictor_replay",
+    "ctn_engine_set_prefetch", "ctn_engine_idle", "ctn_predictor_replay", "ctn_infer_stage",
 ]
 
 
 class ModelDesc(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("layers", "hidden", "ffn", "heads", "vocab", "max_pos", "tp", "rank")]
+    _fields_ = [(n, C.c_int32) for n in ("layers", "hidden", "ffn", "heads", "vocab", "max_pos", "tp", "rank",
+                                         "pp", "stage")]
 
 
 class Param(C.Structure):
@@ -98,6 +99,7 @@ def lib() -> C.CDLL:
         "ctn_wait": (C.c_int, [vp, i32]),
         "ctn_sync": (C.c_int, [vp]),
         "ctn_infer": (C.c_int, [vp, i32, vp, i32, i32, vp, i32]),
+        "ctn_infer_stage": (C.c_int, [vp, i32, vp, vp, i32, i32, i32, vp, i32]),
         "ctn_workspace_bytes": (u64, [P(ModelDesc), i64, i32]),
         "ctn_arena_bytes": (u64, [P(ModelDesc)]),
         "ctn_is_resident": (C.c_int, [vp, i32, P(i32)]),
@@ -143,7 +145,8 @@ def lib() -> C.CDLL:
 
 
 def _desc(d) -> ModelDesc:
-    return ModelDesc(d.layers, d.hidden, d.ffn, d.heads, d.vocab, d.max_pos, d.tp, d.rank)
+    return ModelDesc(d.layers, d.hidden, d.ffn, d.heads, d.vocab, d.max_pos, d.tp, d.rank,
+                     getattr(d, "pp", 1), getattr(d, "stage", 0))
 
 
 def workspace_bytes(desc, max_tokens: int, n_models: int = 1) -> int:
@@ -353,6 +356,7 @@ class Context:
             torch.cuda.ExternalStream(p.value) for p in (a, b, c))
         self.h = h
         self._params = []
+        self._out_features = []
 
     def _check(self, rc: int, what: str):
         if rc:
@@ -365,7 +369,7 @@ class Context:
             if rc:
                 raise CtnError(rc, "ctn_destroy")
 
-    def register_model(self, desc, tensors: Sequence[np.ndarray], budget: int = 0) -> int:
+    def _register(self, desc, tensors: Sequence[np.ndarray], budget: int = 0) -> int:
         arr = (Param * len(tensors))()
         for i, t in enumerate(tensors):
             arr[i].host_ptr = t.ctypes.data
@@ -391,6 +395,13 @@ class Context:
     def sync(self):
         self._check(lib().ctn_sync(self.h), "ctn_sync")
 
+    def register_model(self, desc, tensors: Sequence[np.ndarray], budget: int = 0) -> int:
+        m = self._register(desc, tensors, budget)
+        pp = getattr(desc, "pp", 1)
+        last = getattr(desc, "stage", 0) == pp - 1
+        self._out_features.append(desc.vocab // desc.tp if last else desc.hidden)
+        return m
+
     def infer(self, m: int, ids: np.ndarray, out=None):
         """ids int32 [batch, seq] (host).  `out`: None -> new numpy fp32 array (blocking);
         a numpy array -> filled (blocking); a torch CUDA tensor -> enqueued only."""
@@ -398,9 +409,22 @@ class Context:
         b, s = ids.shape
         is_dev = out is not None and not isinstance(out, np.ndarray)
         if out is None:
-            vl = self._params[m][0].shape[0]
-            out = np.empty((b, s, vl), dtype=np.float32)
+            out = np.empty((b, s, self._out_features[m]), dtype=np.float32)
         self._check(lib().ctn_infer(self.h, m, ids.ctypes.data, b, s, _addr(out), int(is_dev)), "ctn_infer")
+        return out
+
+    def infer_stage(self, m: int, hidden, out=None):
+        """A pipeline stage after the first: `hidden` fp32 [batch, seq, hidden], a numpy array (host)
+        or a torch CUDA tensor; `out` as for infer()."""
+        in_dev = not isinstance(hidden, np.ndarray)
+        if not in_dev:
+            hidden = np.ascontiguousarray(hidden, dtype=np.float32)
+        b, s = int(hidden.shape[0]), int(hidden.shape[1])
+        is_dev = out is not None and not isinstance(out, np.ndarray)
+        if out is None:
+            out = np.empty((b, s, self._out_features[m]), dtype=np.float32)
+        self._check(lib().ctn_infer_stage(self.h, m, None, _addr(hidden), int(in_dev), b, s, _addr(out), int(is_dev)),
+                    "ctn_infer_stage")
         return out
 
     def is_resident(self, m: int) -> bool:

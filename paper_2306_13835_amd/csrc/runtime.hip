@@ -558,9 +558,12 @@ int forward_launches(ctn_ctx* c, Model* m, const Activations& act, int batch, in
 
   // A split-K row-parallel product leaves its residual update to the LayerNorm that follows it.
   PendingSum pend;
-  const _Float16* tok = dev_tensor<_Float16>(c, m, 0);
-  CTN_HIP(c, launch_embed(act.ids, tok, dev_tensor<_Float16>(c, m, 1), act.x, M, seq, h, vl, d.rank, s));
-  for (int l = 0; l < d.layers; ++l) {
+  // Stage 0 builds the residual stream from the token ids; later pipeline stages were handed it.
+  if (L.has_embed())
+    CTN_HIP(c, launch_embed(act.ids, dev_tensor<_Float16>(c, m, L.idx_tok()), dev_tensor<_Float16>(c, m, L.idx_pos()),
+                            act.x, M, seq, h, vl, d.rank, s));
+  const int n_layers = L.local_layers();
+  for (int l = 0; l < n_layers; ++l) {
     if (with_waits && c->cfg.pipeline) CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block[1 + l], 0));
     auto T = [&](int w) { return dev_tensor<_Float16>(c, m, L.layer_tensor(l, w)); };
     CTN_HIP(c, launch_layernorm(act.x, T(LN1_W), T(LN1_B), act.a, M, h, s, &pend));
@@ -574,11 +577,15 @@ int forward_launches(ctn_ctx* c, Model* m, const Activations& act, int batch, in
     CTN_HIP(c, launch_gemm(act.attn, T(O_W), T(O_B), act.x, M, h, hl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats, &pend));
     CTN_HIP(c, launch_layernorm(act.x, T(LN2_W), T(LN2_B), act.a, M, h, s, &pend));
     CTN_HIP(c, launch_gemm(act.a, T(FC1_W), T(FC1_B), act.u, M, fl, h, CTN_EPI_BIAS_RELU_F16, s, act.partial, act.partial_floats));
-    CTN_HIP(c, launch_gemm(act.u, T(FC2_W), T(FC2_B), act.x, M, h, fl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats, &pend));
+    // (a stage that ends without a final LayerNorm has nobody to finish a deferred update for it)
+    PendingSum* after_fc2 = (l + 1 < n_layers || L.has_head()) ? &pend : nullptr;
+    CTN_HIP(c, launch_gemm(act.u, T(FC2_W), T(FC2_B), act.x, M, h, fl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats, after_fc2));
   }
-  CTN_HIP(c, launch_layernorm(act.x, dev_tensor<_Float16>(c, m, L.n_tensors - 2),
-                              dev_tensor<_Float16>(c, m, L.n_tensors - 1), act.a, M, h, s, &pend));
-  CTN_HIP(c, launch_gemm(act.a, tok, nullptr, logits, M, vl, h, CTN_EPI_F32, s));   // tied head, vocabulary slice
+  if (!L.has_head()) return CTN_OK;            // the stage emits the residual stream act.x
+  CTN_HIP(c, launch_layernorm(act.x, dev_tensor<_Float16>(c, m, L.idx_final_w()),
+                              dev_tensor<_Float16>(c, m, L.idx_final_b()), act.a, M, h, s, &pend));
+  // head: the token matrix (tied), or the last pipeline stage's own copy of it; vocabulary slice
+  CTN_HIP(c, launch_gemm(act.a, dev_tensor<_Float16>(c, m, L.idx_head()), nullptr, logits, M, vl, h, CTN_EPI_F32, s));
   return CTN_OK;
 }
 
@@ -826,21 +833,27 @@ uint64_t ctn_slot_bytes(const ctn_model_desc* desc) {
   return make_layout(*desc).slot_bytes;
 }
 
-static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int32_t batch, int32_t seq,
-                         void* logits_out, int32_t out_is_device, float** logits_dev, uint64_t* logits_bytes) {
+// Enqueues one inference.  *result_dev / *result_bytes describe where the result stands on the
+// device when the caller asked for it in host memory (the caller copies it down).
+static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, const void* hidden_in, int32_t in_is_device,
+                         int32_t batch, int32_t seq, void* logits_out, int32_t out_is_device, float** logits_dev,
+                         uint64_t* logits_bytes) {
   Model* m = get_model(c, mi);
   if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
-  if (!ids_host || !logits_out) return CTN_E_INVAL;
+  if (!logits_out) return CTN_E_INVAL;
   const ShardLayout& L = m->lay;
   const ctn_model_desc& d = L.d;
+  // stage 0 starts from token ids, every later pipeline stage from the residual stream
+  if (L.has_embed() ? (!ids_host || hidden_in) : !hidden_in) return CTN_E_INVAL;
   if (batch <= 0 || seq <= 0 || seq > d.max_pos || (int64_t)batch * seq > (1 << 24)) return CTN_E_SHAPE;
   const int M = batch * seq;
-  const bool own_logits = !out_is_device;
+  const bool own_logits = !out_is_device && L.has_head();
   Activations act{};
   if (activation_bytes(d, M, own_logits, &act, static_cast<char*>(c->cfg.workspace_dev)) > c->cfg.workspace_bytes)
     return CTN_E_SHAPE;
-  for (int i = 0; i < M; ++i)
-    if (ids_host[i] < 0 || ids_host[i] >= d.vocab) return CTN_E_INVAL;
+  if (L.has_embed())
+    for (int i = 0; i < M; ++i)
+      if (ids_host[i] < 0 || ids_host[i] >= d.vocab) return CTN_E_INVAL;
 
   int rc = ensure_resident(c, mi);
   if (rc) return rc;
@@ -852,8 +865,12 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int3
   hipStream_t s = c->s_compute;
   if (c->s_wide && link_quiet(c)) s = c->s_wide;
   if (c->last_compute && c->last_compute != s) CTN_HIP(c, hipStreamWaitEvent(s, c->ev_compute_done, 0));
-  const int vl = L.vl();
-  CTN_HIP(c, hipMemcpyAsync(act.ids, ids_host, 4ull * M, hipMemcpyHostToDevice, s));
+  const uint64_t x_bytes = 4ull * M * d.hidden;
+  if (L.has_embed()) {
+    CTN_HIP(c, hipMemcpyAsync(act.ids, ids_host, 4ull * M, hipMemcpyHostToDevice, s));
+  } else {
+    CTN_HIP(c, hipMemcpyAsync(act.x, hidden_in, x_bytes, in_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, s));
+  }
   float* logits = out_is_device ? static_cast<float*>(logits_out) : act.logits;
 
   // A resident model on an idle link needs no event waits: the whole launch
@@ -866,6 +883,10 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int3
     rc = forward_launches(c, m, act, batch, seq, logits, s, true);
   }
   if (rc) return rc;
+  if (!L.has_head()) {       // the stage's result is the residual stream
+    if (out_is_device) CTN_HIP(c, hipMemcpyAsync(logits_out, act.x, x_bytes, hipMemcpyDeviceToDevice, s));
+    logits = act.x;
+  }
   CTN_HIP(c, hipEventRecord(m->ev_last_use, s));
   m->used_since_load = true;
   if (c->s_wide) {
@@ -875,15 +896,21 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int3
     if (s != c->s_compute) CTN_HIP(c, hipStreamWaitEvent(c->s_compute, c->ev_compute_done, 0));
   }
   *logits_dev = logits;
-  *logits_bytes = 4ull * M * vl;
+  *logits_bytes = 4ull * M * L.out_features();
   return CTN_OK;
 }
 
 int ctn_infer(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, int32_t batch, int32_t seq, void* logits_out,
               int32_t out_is_device) {
+  return ctn_infer_stage(c, mi, ids_host, nullptr, 0, batch, seq, logits_out, out_is_device);
+}
+
+int ctn_infer_stage(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, const void* hidden_in, int32_t in_is_device,
+                    int32_t batch, int32_t seq, void* logits_out, int32_t out_is_device) {
   float* logits = nullptr;
   uint64_t nbytes = 0;
-  const int rc = infer_enqueue(c, mi, ids_host, batch, seq, logits_out, out_is_device, &logits, &nbytes);
+  const int rc = infer_enqueue(c, mi, ids_host, hidden_in, in_is_device, batch, seq, logits_out, out_is_device,
+                               &logits, &nbytes);
   // the victims' offloads go out after the load and the forward pass are in their queues
   const int rc2 = c ? flush_deferred(c) : CTN_OK;
   if (rc || rc2) return rc ? rc : rc2;
@@ -1120,6 +1147,7 @@ int ctn_engine_submit(ctn_engine* e, ctn_model m, const int32_t* ids, double tim
   if (!e || !ids) return CTN_E_INVAL;
   Model* mod = get_model(e->ctx, m);
   if (!mod) return CTN_E_NOMODEL;
+  if (!mod->lay.has_embed()) return CTN_E_INVAL;   // the queues hold token ids: stage 0 shards only
   if (e->seq > mod->lay.d.max_pos) return CTN_E_SHAPE;
   for (int i = 0; i < e->seq; ++i)
     if (ids[i] < 0 || ids[i] >= mod->lay.d.vocab) return CTN_E_INVAL;

@@ -15,7 +15,7 @@ class Rig:
         self.dev = torch.device("cuda:0")
         torch.cuda.set_device(0)
         streams = [torch.cuda.Stream() for _ in range(3)] if torch_streams else [None] * 3
-        need = [P.slot_bytes(d) * (d.layers + 1) if block_residency else P.arena_bytes(d) for d in descs]
+        need = [P.slot_bytes(d) * (d.local_layers + 1) if block_residency else P.arena_bytes(d) for d in descs]
         arena_bytes = arena_bytes or sum(need)
         budget = budget or sum(shard_bytes(d) for d in descs)
         ws = max(P.workspace_bytes(d, max_tokens) for d in descs)
