@@ -119,7 +119,7 @@ def run_swap(args):
     a_bytes = P.arena_bytes(desc)
     arena = torch.empty(2 * a_bytes, dtype=torch.uint8, device="cuda")
     ws = torch.empty(P.workspace_bytes(desc, M), dtype=torch.uint8, device="cuda")
-    logits = torch.empty(batch, seq, desc.vocab // desc.tp, dtype=torch.float32, device="cuda")
+    logits = torch.empty(batch, seq, desc.out_features, dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
     # library-owned streams: one hardware queue and a private set of compute units per direction
     ctx = P.Context(nbytes, arena, ws, transfer_mode=P.XFER_KERNEL, pipeline=True,
@@ -219,9 +219,9 @@ def run_swap(args):
     # library records on the h2d stream after every transfer block (last load of each model)
     specs = param_list(desc)
     sizes = [2 * int(np.prod(sh)) for _, sh, _ in specs]
-    b0 = sizes[0] + sizes[1] + sizes[-2] + sizes[-1]        # block 0: embeddings + final LayerNorm
-    per_layer = sum(sizes[2:18])                            # then one equal block per layer
-    block_bytes = [b0] + [per_layer] * desc.layers
+    n_front = 2 if desc.has_embed else 0                    # block 0: the tensors outside the layers
+    per_layer = sum(sizes[n_front:n_front + 16])            # then one equal block per layer
+    block_bytes = [sum(sizes) - per_layer * desc.local_layers] + [per_layer] * desc.local_layers
     timed_blocks = []
     for k in range(2):
         i_ms, o_ms, blocks = ctx.last_swap_ms(models[k])
@@ -332,7 +332,7 @@ def run_counters(args):
     nbytes, M = shard_bytes(desc), batch * seq
     arena = torch.empty(P.arena_bytes(desc), dtype=torch.uint8, device="cuda")
     ws = torch.empty(P.workspace_bytes(desc, M), dtype=torch.uint8, device="cuda")
-    logits = torch.empty(batch, seq, desc.vocab // desc.tp, dtype=torch.float32, device="cuda")
+    logits = torch.empty(batch, seq, desc.out_features, dtype=torch.float32, device="cuda")
     ctx = P.Context(nbytes, arena, ws, transfer_mode=P.XFER_KERNEL, pipeline=False)
     pool = P.HostPool(nbytes + len(param_list(desc)) * (256 + GAP) + 8192)
     tensors = fill_shard(desc, cfg["wseed"], alloc=lambda s: pool.take(s, gap=GAP), threads=16)
@@ -362,15 +362,17 @@ def cpu_baseline(tensors, ids, desc, nbytes):
     cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
     img = DeviceImage([t.nbytes for t in tensors])
     t = time.perf_counter(); img.swap_in(tensors); t_in = time.perf_counter() - t
-    scratch = [np.empty_like(x) for x in tensors[2:18]]
+    first = 2 if desc.has_embed else 0                      # the first decoder layer's 16 tensors
+    scratch = [np.empty_like(x) for x in tensors[first:first + 16]]
     t = time.perf_counter()
-    img2 = DeviceImage([x.nbytes for x in scratch]); img2.swap_in(tensors[2:18]); img2.swap_out(scratch)
+    img2 = DeviceImage([x.nbytes for x in scratch]); img2.swap_in(tensors[first:first + 16]); img2.swap_out(scratch)
     t_layer = (time.perf_counter() - t) / 2
     t_out = t_layer * nbytes / sum(x.nbytes for x in scratch)      # swap-out extrapolated from one layer block
     del img, img2, scratch
     rows = [0]
     t = time.perf_counter()
-    O.forward(tensors, ids[rows], layers=desc.layers, heads=desc.heads, tp=desc.tp, rank=desc.rank)
+    O.forward_stage(tensors, ids[rows], layers=desc.layers, heads=desc.heads, tp=desc.tp, rank=desc.rank,
+                    pp=desc.pp, stage=desc.stage)
     t_fwd = (time.perf_counter() - t) * ids.shape[0] / len(rows)
     step = t_in + t_fwd + t_out
     return {"value": round(nbytes / step / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
