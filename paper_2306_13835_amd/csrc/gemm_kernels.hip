@@ -468,10 +468,7 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
     }
     return launch_skinny_any(g, epi, s, n_total >= 6144 ? 1 : 0);
   }
-  const int t_big = ((g.M + 255) / 256) * ((g.N + 127) / 128) * g.parts;
-  if (t_big >= 512 && g.K <= 4096) return launch_config(2, g, epi, s);   // plenty of work: 256x128 tiles, 128x64 per wave
-                                                                          // (measured slower than 128x128 at K = 8192)
-  // Tile choice by how the tile count fills 256 CUs (2 workgroups of 128x128x64 each, 3 of 128x128x32):
+  // Tile choice by how the tile count fills 256 CUs (two workgroups per CU for the big tiles):
   const int t0 = ((g.M + 127) / 128) * ((g.N + 127) / 128) * g.parts;
   if (g.partial && t0 <= 256 && g.K >= 4096) {
     // at most one 128x128 tile per CU and a long K: two to four K slices fill the second workgroup
@@ -484,10 +481,14 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
   }
   if (t0 <= 128) return launch_config(6, g, epi, s);               // few tiles: 64x64
   if (t0 <= 320) return launch_config(1, g, epi, s);               // under one round: 128x64 doubles the count
-  // 128x128x64 runs two workgroups per CU (512 per round), 128x128x32 three (768 per round, each
-  // round about 1.25 times as long): take the one with the cheaper last, partly filled round
-  const int rounds64 = (t0 + 511) / 512, rounds32 = (t0 + 767) / 768;
-  if (4 * rounds64 > 5 * rounds32) return launch_config(5, g, epi, s);
+  // Plenty of tiles: 128x128x64 (4 wavefronts) or 256x128x32 (8 wavefronts of 64x64), both two
+  // workgroups per CU, i.e. 512 per round.  The wide tile moves 1.15 times the flops per unit time
+  // when its rounds are full (measured at 1500-3000 tiles); what decides is the last, partly
+  // filled round, so compare rounds x work per tile: (M=2048, N=10240) 3 rounds of 128x128 beat 2
+  // rounds of 256x128, (M=4096, N=8192) 2 wide rounds beat 4 narrow ones.
+  const int t_wide = ((g.M + 255) / 256) * ((g.N + 127) / 128) * g.parts;
+  const int rounds_narrow = (t0 + 511) / 512, rounds_wide = (t_wide + 511) / 512;
+  if (173 * rounds_wide < 100 * rounds_narrow) return launch_config(13, g, epi, s);
   return launch_config(0, g, epi, s);
 }
 
