@@ -261,3 +261,87 @@ def run_cyclic(args):
     del keep
     pool.close()
     print(json.dumps(res), flush=True)
+
+
+SPLITS = [(1, 1), (2, 1), (4, 1), (1, 2), (1, 4), (2, 2)]     # (TP, PP) of the paper's Section 5.1 sweeps
+
+
+def run_scaling(args):
+    """Section 5.1 of the paper on one GPU's share: OPT-13B split TP x PP ways, two models, room for
+    one, alternating blocking requests of 2 input tokens; the share of GPU 0 (rank 0, stage 0) is
+    what this GPU swaps.  Reports, per split, the swap and request latency next to the link bound
+    for that many bytes (the paper's own figures for this experiment are not in its text)."""
+    import torch
+    import paper_2306_13835_amd as P
+    from synth import ShardDesc, fill_shard, token_ids, shard_bytes, param_list
+
+    torch.cuda.set_device(0)
+    torch.zeros(1, device="cuda")
+    gap = 4096 if args.host_layout == "separate" else 0
+    seq, steps, warmup = 2, args.steps, args.warmup
+    rows = []
+    link = None
+    for tp, pp in SPLITS:
+        desc = ShardDesc(40, 5120, 20480, 40, tp=tp, rank=0, pp=pp, stage=0)
+        nbytes, n_t = shard_bytes(desc), len(param_list(desc))
+        arena = torch.empty(2 * P.arena_bytes(desc), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(P.workspace_bytes(desc, seq), dtype=torch.uint8, device="cuda")
+        out = torch.empty(1, seq, desc.out_features, dtype=torch.float32, device="cuda")
+        ctx = P.Context(nbytes, arena, ws, transfer_mode={"dma": 0, "kernel": 1, "auto": 2}[args.transfer], pipeline=True)
+        pool = P.HostPool(2 * (nbytes + n_t * (256 + gap)) + 8192)
+        t0 = time.time()
+        keep = [fill_shard(desc, 200 + 10 * tp + pp + k, alloc=lambda s: pool.take(s, gap=gap), threads=16) for k in range(2)]
+        models = [ctx.register_model(desc, t) for t in keep]
+        ids = [token_ids(210 + k, 1, seq, desc.vocab) for k in range(2)]
+        log(f"[scaling] TP={tp} PP={pp}: shard {nbytes / 1e9:.2f} GB x 2 ready in {time.time() - t0:.1f}s")
+        if link is None:                                       # the link peak, once: one 1 GiB DMA copy
+            from paper_2306_13835_amd import binding as B
+            cal = P.HostPool(1 << 30)
+            dev = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+            ts = []
+            for _ in range(5):
+                ctx.stream_h2d.synchronize()
+                t = time.perf_counter()
+                B.op_dma(dev, cal.ptr, 1 << 30, ctx.stream_h2d)
+                ctx.stream_h2d.synchronize()
+                ts.append(time.perf_counter() - t)
+            link = (1 << 30) / float(np.median(ts)) / 1e9
+            cal.close()
+            del dev
+        # isolated swap-in / swap-out of one shard
+        ins, outs = [], []
+        for _ in range(3):
+            ctx.swap_in(models[0]); ctx.wait(models[0])
+            ctx.swap_out(models[0]); ctx.wait(models[0])
+            i_ms, o_ms, _ = ctx.last_swap_ms(models[0])
+            ins.append(i_ms); outs.append(o_ms)
+        # the paper's workload: alternating blocking requests, every one swaps
+        lat = []
+        for i in range(warmup + steps):
+            t = time.perf_counter()
+            ctx.infer(models[i % 2], ids[i % 2], out=out)
+            ctx.stream_compute.synchronize()
+            if i >= warmup:
+                lat.append((time.perf_counter() - t) * 1e3)
+        ctx.sync()
+        rows.append({"tp": tp, "pp": pp, "ways": tp * pp, "shard_bytes": nbytes, "tensors": n_t,
+                     "swap_in_ms": round(float(np.median(ins)), 2), "swap_out_ms": round(float(np.median(outs)), 2),
+                     "link_bound_ms": round(nbytes / link / 1e6, 2),
+                     "request_latency_ms": round(float(np.median(lat)), 2),
+                     "swap_in_gbps": round(nbytes / float(np.median(ins)) / 1e6, 2)})
+        log(f"[scaling] {rows[-1]}")
+        ctx.close()
+        del keep, arena, ws, out
+        pool.close()
+    base = rows[0]
+    for r in rows:
+        r["speedup_vs_one_gpu"] = round(base["request_latency_ms"] / r["request_latency_ms"], 3)
+    res = {"metric": "swap and request latency of one GPU's share of OPT-13B vs the (TP, PP) split (Section 5.1 workload)",
+           "value": rows[-1]["request_latency_ms"], "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": warmup,
+           "higher_is_better": False, "data": "synthetic", "dtype": "f16", "vs_baseline": None,
+           "config": {"workload": "OPT-13B, 2 models, 1 resident, alternating blocking requests of 2 tokens; GPU 0's share "
+                                  "(rank 0, stage 0) per split", "transfer": args.transfer, "host_layout": args.host_layout},
+           "link_peak_measured_gbps": round(link, 2),
+           "paper_context": "24 GB / 32 GB/s = 0.75 s lower bound on one A100 (Section 5.1); measured figures not in the text",
+           "results": rows}
+    print(json.dumps(res), flush=True)
