@@ -78,19 +78,22 @@ __global__ __launch_bounds__(WAVES * 64) void layernorm_kernel(float* __restrict
   float4v* xr = reinterpret_cast<float4v*>(x + static_cast<int64_t>(row) * hidden);
   const int nvec = hidden / 4;
   float4v v[NV];
+  half4 gg[NV], bb[NV];      // gain and bias travel together with the row: one memory round trip, not two
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int c = threadIdx.x + i * WAVES * 64;
     if (c < nvec) {
       v[i] = xr[c];
+      gg[i] = reinterpret_cast<const half4*>(g)[c];
+      bb[i] = reinterpret_cast<const half4*>(b)[c];
       if (FUSE) {
         float4v t = {0.f, 0.f, 0.f, 0.f};
         for (int sl = 0; sl < pend.splits; ++sl)
           t += reinterpret_cast<const float4v*>(pend.partial + (static_cast<int64_t>(sl) * rows + row) * hidden)[c];
-        const half4 bb = reinterpret_cast<const half4*>(pend.bias)[c];
+        const half4 pb = reinterpret_cast<const half4*>(pend.bias)[c];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) t[e] += static_cast<float>(bb[e]);
+        for (int e = 0; e < 4; ++e) t[e] += static_cast<float>(pb[e]);
         v[i] += t;
         xr[c] = v[i];
       }
@@ -119,12 +122,10 @@ __global__ __launch_bounds__(WAVES * 64) void layernorm_kernel(float* __restrict
   for (int i = 0; i < NV; ++i) {
     const int c = threadIdx.x + i * WAVES * 64;
     if (c < nvec) {
-      const half4 gg = reinterpret_cast<const half4*>(g)[c];
-      const half4 bb = reinterpret_cast<const half4*>(b)[c];
       half4 o;
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        o[e] = static_cast<_Float16>(v[i][e] * inv * static_cast<float>(gg[e]) + static_cast<float>(bb[e]));
+        o[e] = static_cast<_Float16>(v[i][e] * inv * static_cast<float>(gg[i][e]) + static_cast<float>(bb[i][e]));
       reinterpret_cast<half4*>(orow)[c] = o;
     }
   }
