@@ -672,6 +672,8 @@ int ctn_create(const ctn_config* cfg, ctn_ctx** out) {
 
 int ctn_sync(ctn_ctx* c) {
   if (!c) return CTN_E_INVAL;
+  const int rc = flush_deferred(c);       // nothing decided may stay unissued behind a full synchronisation
+  if (rc) return rc;
   CTN_HIP(c, hipStreamSynchronize(c->s_h2d));
   CTN_HIP(c, hipStreamSynchronize(c->s_d2h));
   CTN_HIP(c, hipStreamSynchronize(c->s_compute));
