@@ -211,3 +211,60 @@ def test_graph_replay_equals_direct_launches_across_evictions():
         assert rig.ctx.stats()["n_miss"] > 6               # the models really moved between rounds
     finally:
         rig.close()
+
+
+@pytest.mark.parametrize("block_residency", [False, True])
+def test_serving_shapes_full_size_decisions_logits_determinism(block_residency):
+    """The serving workload's shapes at full size (opt6.7b TP=2 shards, 1 x 64 requests, a budget of
+    two shards and a bit), four models instead of eight: every decision equals the policy oracle's,
+    the first answer of each model meets the bar against the fp32 oracle, and a repeated
+    (model, ids) pair gives bit-identical logits whatever was swapped in between."""
+    from oracle.lru import LruResidency
+    from oracle.partial_lru import PartialLruResidency
+    from paper_2306_13835_amd.serving import serve_trace
+    from synth import gamma_zipf_trace
+    from gpu_util import block_bytes
+    c = CONFIGS["serve8x6.7b_tp2"]
+    desc, n_models, n_req = c["desc"], 4, 40
+    size = shard_bytes(desc)
+    budget = 2 * size + size // 3
+    footprint = P.slot_bytes(desc) * (desc.layers + 1) if block_residency else P.arena_bytes(desc)
+    rig = Rig([desc] * n_models, budget=budget, arena_bytes=4 * footprint, max_tokens=c["batch"] * c["seq"],
+              mode=P.XFER_AUTO, block_residency=block_residency, gap=4096)
+    try:
+        ms = [rig.add(desc, seed=c["wseed"] + k) for k in range(n_models)]
+        _, mod = gamma_zipf_trace(c["n_models"], c["rate"], c["cv"], c["zipf"], 400, c["trace_seed"])
+        mod = np.array([m for m in mod if m < n_models][:n_req] + [0, 1, 2, 3, 0, 1, 2, 3])   # every model at least twice
+        arr = np.zeros(len(mod))                                # back to back: the order is what matters here
+        ids = [token_ids(c["idseed"] + int(m), c["batch"], c["seq"], desc.vocab) for m in mod]   # one prompt per model
+        out = torch.empty(c["batch"], c["seq"], desc.vocab // desc.tp, dtype=torch.float32, device="cuda")
+        first = {}
+
+        def check(i):
+            m = int(mod[i])
+            got = out.cpu().numpy().copy()
+            if m in first:
+                assert np.array_equal(first[m], got), f"request {i}: model {m} answered differently"
+            else:
+                first[m] = got
+        serve_trace(rig.ctx, ms, arr, mod, lambda i: ids[i], out, progress=check)
+        rig.ctx.sync()
+        if block_residency:
+            ref = PartialLruResidency(budget, [block_bytes(desc)] * n_models)
+            for m in mod:
+                ref.touch(int(m))
+            assert rig.ctx.events() == [(k, m, tuple(v for v, _, _ in ev)) for k, m, _, ev in ref.events]
+            assert rig.ctx.stats()["n_partial_miss"] > 0 and rig.ctx.stats()["n_extra_evictions"] == 0
+        else:
+            ref = LruResidency(budget, [size] * n_models)
+            for m in mod:
+                ref.touch(int(m))
+            assert rig.ctx.events() == ref.events
+        assert len(first) == n_models
+        for m in range(n_models):
+            t0 = time.time()
+            want = oracle_logits(rig, ms[m], desc, token_ids(c["idseed"] + m, c["batch"], c["seq"], desc.vocab))
+            print(f"oracle for model {m} in {time.time() - t0:.1f}s", flush=True)
+            assert_close(first[m], want, f"serving model {m}")
+    finally:
+        rig.close()
