@@ -21,6 +21,22 @@ Time is simulated: the caller supplies `service(model, batch, miss)`, the
 duration of one batch.  Everything else is deterministic bookkeeping, which is
 what the library's scheduler is compared with.
 
+`simulate_async` is the engine of Section 3.2 proper: load entries are
+asynchronous, so "a later batch entry [can] proceed without waiting for a
+previous load entry involving another model".  On one GPU this becomes two
+lanes that run side by side:
+  * the hit lane executes batches of models that are completely loaded, one
+    batch at a time;
+  * the load lane takes one miss at a time: the swap-in of the model followed
+    by that model's batch (a batch is only evaluated on loaded parameters);
+  * a model whose miss is in flight on the load lane is not dispatched again
+    until that batch has completed;
+  * at every decision time the non-empty queues are scanned oldest head first
+    (ties: lower model index) and the first one that can be dispatched (its
+    lane is free, its model is not loading) is; the scan repeats until nothing
+    more can be dispatched; the clock then moves to the next arrival or
+    completion.
+
 Parity status: pinned by invariants (every request served exactly once, in
 arrival order within its model, batches single-model and within the cap,
 oldest-head-first at every dispatch, no dispatch before arrival) and by
@@ -63,6 +79,58 @@ def simulate(arrival: Sequence[float], model_of: Sequence[int], n_models: int, m
         batches.append((now, finish, m, take, miss))
         served += len(take)
         now = finish
+    return batches, lru
+
+
+# one dispatched batch of the two-lane engine: (dispatch, finish, model, requests, was_miss, lane)
+AsyncBatch = Tuple[float, float, int, Tuple[int, ...], bool, int]
+HIT_LANE, LOAD_LANE = 0, 1
+
+
+def simulate_async(arrival: Sequence[float], model_of: Sequence[int], n_models: int, max_batch: int,
+                   budget: int, sizes: Sequence[int],
+                   service: Callable[[int, int, bool], float]) -> Tuple[List[AsyncBatch], LruResidency]:
+    """The two-lane engine over a trace sorted by arrival time (see the module text)."""
+    n = len(arrival)
+    queues: List[List[int]] = [[] for _ in range(n_models)]
+    lru = LruResidency(budget, sizes)
+    batches: List[AsyncBatch] = []
+    lane_free = [0.0, 0.0]
+    loading = {}                 # model -> time its batch on the load lane completes
+    now, nxt, dispatched = 0.0, 0, 0
+    while dispatched < n:
+        while nxt < n and arrival[nxt] <= now:
+            queues[model_of[nxt]].append(nxt)
+            nxt += 1
+        for m in [m for m, t in loading.items() if t <= now]:
+            del loading[m]
+        progress = True
+        while progress:
+            progress = False
+            for _, m in sorted((arrival[q[0]], m) for m, q in enumerate(queues) if q):
+                if m in loading:
+                    continue
+                hit = lru.is_resident(m)
+                lane = HIT_LANE if hit else LOAD_LANE
+                if lane_free[lane] > now:
+                    continue
+                take = tuple(queues[m][:max_batch])
+                del queues[m][:len(take)]
+                lru.touch(m)
+                finish = now + service(m, len(take), not hit)
+                lane_free[lane] = finish
+                if not hit:
+                    loading[m] = finish
+                batches.append((now, finish, m, take, not hit, lane))
+                dispatched += len(take)
+                progress = True
+                break
+        if dispatched == n:
+            break
+        ahead = [t for t in lane_free if t > now]
+        if nxt < n:
+            ahead.append(arrival[nxt])
+        now = min(ahead)
     return batches, lru
 
 
