@@ -398,6 +398,8 @@ def main():
                     help="how the parameter tensors lie in pinned host memory")
     ap.add_argument("--block-residency", action="store_true",
                     help="serve workload: residency per transfer block instead of per model")
+    ap.add_argument("--two-lane", action="store_true",
+                    help="serve / grid workloads: the asynchronous engine (batches of loaded models go on while another loads)")
     ap.add_argument("--copy-blocks", type=int, default=0, help="workgroups per copy kernel (0: library default)")
     ap.add_argument("--copy-cus", type=int, default=0, help="compute units reserved per transfer direction")
     args = ap.parse_args()

@@ -304,6 +304,27 @@ int ctn_engine_submit(ctn_engine* eng, ctn_model m, const int32_t* ids_host, dou
 int ctn_engine_step(ctn_engine* eng, void* logits_out, int64_t* served_ids, int32_t cap, int32_t* n_served,
                     ctn_model* model, int32_t* was_miss);
 int ctn_engine_pending(ctn_engine* eng, int64_t* n);
+
+/* The two-lane engine (Section 3.2: load entries are asynchronous, "a later
+ * batch entry [can] proceed without waiting for a previous load entry
+ * involving another model").  Lane 0 runs batches of completely loaded
+ * models, one at a time; lane 1 takes one miss at a time, the model's swap-in
+ * followed, block by block, by its batch; a model whose miss is in flight is
+ * not dispatched again until that batch has completed.  Needs a context with
+ * library-owned streams and twice the workspace of ctn_workspace_bytes() (each
+ * lane works in its own half).  ctn_engine_step is not available on it. */
+int ctn_engine_create_async(ctn_ctx* ctx, int32_t max_batch, int32_t seq, ctn_engine** out);
+/* Dispatches at most one batch: the non-empty queues are scanned oldest head
+ * first and the first whose lane is free and whose model is not loading goes.
+ * logits_out[lane] (device, fp32 [max_batch, seq, vocab/tp], one buffer per
+ * lane) receives the batch's logits; the call returns with the work enqueued.
+ * *n_served == 0 when nothing can be dispatched now (queues empty, lanes busy
+ * or models loading).  *lane tells where the batch runs (0 hit lane, 1 load lane). */
+int ctn_engine_dispatch(ctn_engine* eng, void* const logits_out[2], int64_t* served_ids, int32_t cap,
+                        int32_t* n_served, ctn_model* model, int32_t* was_miss, int32_t* lane);
+/* busy[l] = 1 while the batch last dispatched on lane l has not completed
+ * (host array of 2).  Does not block. */
+int ctn_engine_lanes(ctn_engine* eng, int32_t* busy);
 /* Loading ahead (the paper's closing section: speculative loads for request
  * streams with structure).  The engine keeps a first-order transition table
  * over its dispatches; after a dispatch of model a it predicts the model that
@@ -330,6 +351,13 @@ int ctn_engine_replay(int32_t n_models, int32_t max_batch, uint64_t budget_bytes
                       const double* arrival, const int32_t* model_of, uint64_t n, double t_base,
                       double t_per_request, double t_miss, ctn_batch_record* batches, uint64_t cap,
                       uint64_t* n_batches, uint64_t* requests);
+/* The same for the two-lane engine (ctn_engine_dispatch's rule on a simulated
+ * clock: each lane runs one batch at a time, a miss occupies lane 1 for
+ * t_base + b * t_per_request + t_miss); batches[i].reserved holds the lane. */
+int ctn_engine_replay_async(int32_t n_models, int32_t max_batch, uint64_t budget_bytes, const uint64_t* sizes,
+                            const double* arrival, const int32_t* model_of, uint64_t n, double t_base,
+                            double t_per_request, double t_miss, ctn_batch_record* batches, uint64_t cap,
+                            uint64_t* n_batches, uint64_t* requests);
 
 /* ---- single operations (each enqueues on `stream`, a hipStream_t; all data
  *      pointers are device pointers unless stated) --------------------------- */

@@ -22,6 +22,7 @@ DECLARED_SYMBOLS = [
     "ctn_engine_submit", "ctn_engine_step", "ctn_engine_pending", "ctn_engine_replay",
     "ctn_slot_bytes", "ctn_resident_blocks", "ctn_get_block_events", "ctn_block_residency_replay",
     "ctn_engine_set_prefetch", "ctn_engine_idle", "ctn_predictor_replay", "ctn_infer_stage",
+    "ctn_engine_create_async", "ctn_engine_dispatch", "ctn_engine_lanes", "ctn_engine_replay_async",
 ]
 
 
@@ -136,6 +137,11 @@ def lib() -> C.CDLL:
         "ctn_predictor_replay": (C.c_int, [i32, i32, i32, P(i32), u64, P(i32)]),
         "ctn_engine_replay": (C.c_int, [i32, i32, u64, P(u64), P(C.c_double), P(i32), u64, C.c_double, C.c_double,
                                         C.c_double, P(BatchRecord), u64, P(u64), P(u64)]),
+        "ctn_engine_replay_async": (C.c_int, [i32, i32, u64, P(u64), P(C.c_double), P(i32), u64, C.c_double,
+                                              C.c_double, C.c_double, P(BatchRecord), u64, P(u64), P(u64)]),
+        "ctn_engine_create_async": (C.c_int, [vp, i32, i32, P(vp)]),
+        "ctn_engine_dispatch": (C.c_int, [vp, P(vp), P(i64), i32, P(i32), P(i32), P(i32), P(i32)]),
+        "ctn_engine_lanes": (C.c_int, [vp, P(i32)]),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
@@ -213,8 +219,9 @@ def predictor_replay(n_models: int, dispatches: Sequence[int], min_count: int = 
 
 
 def engine_replay(n_models: int, max_batch: int, budget: int, sizes: Sequence[int], arrival, model_of,
-                  t_base: float, t_per_request: float, t_miss: float):
-    """Host-only replay of the scheduler; returns [(start, finish, model, request indices, miss)]."""
+                  t_base: float, t_per_request: float, t_miss: float, two_lanes: bool = False):
+    """Host-only replay of the scheduler; returns [(start, finish, model, request indices, miss)],
+    with the lane appended to every tuple for the two-lane engine."""
     n = len(arrival)
     sz = (C.c_uint64 * len(sizes))(*[int(x) for x in sizes])
     arr = (C.c_double * max(n, 1))(*[float(x) for x in arrival])
@@ -222,23 +229,29 @@ def engine_replay(n_models: int, max_batch: int, budget: int, sizes: Sequence[in
     rec = (BatchRecord * max(n, 1))()
     req = (C.c_uint64 * max(n, 1))()
     nb = C.c_uint64()
-    rc = lib().ctn_engine_replay(n_models, max_batch, int(budget), sz, arr, mod, n, t_base, t_per_request, t_miss,
-                                 rec, n, C.byref(nb), req)
+    fn = lib().ctn_engine_replay_async if two_lanes else lib().ctn_engine_replay
+    rc = fn(n_models, max_batch, int(budget), sz, arr, mod, n, t_base, t_per_request, t_miss, rec, n, C.byref(nb), req)
     if rc:
         raise CtnError(rc, "ctn_engine_replay")
-    return [(r.start, r.finish, r.model, tuple(int(req[r.offset + k]) for k in range(r.count)), bool(r.miss))
-            for r in rec[:nb.value]]
+    out = [(r.start, r.finish, r.model, tuple(int(req[r.offset + k]) for k in range(r.count)), bool(r.miss))
+           for r in rec[:nb.value]]
+    if two_lanes:
+        out = [b + (int(r.reserved),) for b, r in zip(out, rec[:nb.value])]
+    return out
 
 
 class Engine:
     """ctn_engine: per-model FIFO queues over a Context, oldest-first batches of at most max_batch."""
 
-    def __init__(self, ctx: "Context", max_batch: int, seq: int):
-        self.ctx, self.max_batch, self.seq = ctx, max_batch, seq
+    def __init__(self, ctx: "Context", max_batch: int, seq: int, two_lanes: bool = False):
+        """two_lanes: the asynchronous engine (hits go on while another model loads); it is driven
+        with dispatch() / lanes_busy() instead of step() and needs twice the workspace."""
+        self.ctx, self.max_batch, self.seq, self.two_lanes = ctx, max_batch, seq, two_lanes
         h = C.c_void_p()
-        rc = lib().ctn_engine_create(ctx.h, max_batch, seq, C.byref(h))
+        create = lib().ctn_engine_create_async if two_lanes else lib().ctn_engine_create
+        rc = create(ctx.h, max_batch, seq, C.byref(h))
         if rc:
-            raise CtnError(rc, "ctn_engine_create")
+            raise CtnError(rc, "ctn_engine_create_async" if two_lanes else "ctn_engine_create")
         self.h = h
         self._served = (C.c_int64 * max_batch)()
 
@@ -262,6 +275,26 @@ class Engine:
         if n.value == 0:
             return None
         return [int(self._served[i]) for i in range(n.value)], m.value, bool(miss.value)
+
+    def dispatch(self, logits_hit, logits_load):
+        """Two-lane engine: dispatches at most one batch; returns (request ids, model, was_miss, lane)
+        or None when nothing can go right now.  The batch's logits land in the buffer of its lane."""
+        n, m, miss, lane = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32()
+        bufs = (C.c_void_p * 2)(_addr(logits_hit), _addr(logits_load))
+        rc = lib().ctn_engine_dispatch(self.h, bufs, self._served, self.max_batch, C.byref(n), C.byref(m),
+                                       C.byref(miss), C.byref(lane))
+        if rc:
+            raise CtnError(rc, "ctn_engine_dispatch", lib().ctn_last_hip_error(self.ctx.h) if rc == -5 else 0)
+        if n.value == 0:
+            return None
+        return [int(self._served[i]) for i in range(n.value)], m.value, bool(miss.value), lane.value
+
+    def lanes_busy(self) -> Tuple[bool, bool]:
+        busy = (C.c_int32 * 2)()
+        rc = lib().ctn_engine_lanes(self.h, busy)
+        if rc:
+            raise CtnError(rc, "ctn_engine_lanes")
+        return bool(busy[0]), bool(busy[1])
 
     def set_prefetch(self, enable: bool, min_count: int = 2, min_share_percent: int = 50):
         rc = lib().ctn_engine_set_prefetch(self.h, int(bool(enable)), min_count, min_share_percent)

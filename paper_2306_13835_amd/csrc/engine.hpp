@@ -5,6 +5,7 @@
 // packs them into one batch entry.  Section 4: batches are scheduled by the
 // oldest timestamp.  Section 5.2: the maximum batch size is a parameter (8, 32).
 #pragma once
+#include <algorithm>
 #include <cstdint>
 #include <deque>
 #include <vector>
@@ -37,6 +38,15 @@ class RequestQueues {
       if (!q_[m].empty() && (best < 0 || q_[m].front().timestamp < q_[best].front().timestamp)) best = m;
     return best;
   }
+  // Models with waiting requests, the one whose oldest request is oldest first (ties: lower index).
+  std::vector<int> by_oldest_head() const {
+    std::vector<int> order;
+    for (int m = 0; m < static_cast<int>(q_.size()); ++m)
+      if (!q_[m].empty()) order.push_back(m);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int a, int b) { return q_[a].front().timestamp < q_[b].front().timestamp; });
+    return order;
+  }
   // Pops up to max_batch oldest requests of that model.
   std::vector<QueuedRequest> pop(int model, int max_batch) {
     std::vector<QueuedRequest> out;
@@ -51,6 +61,28 @@ class RequestQueues {
  private:
   std::vector<std::deque<QueuedRequest>> q_;
 };
+
+// Dispatch rule of the two-lane engine (Section 3.2: load entries are
+// asynchronous, so a later batch entry proceeds without waiting for a load
+// entry of another model).  Lane 0 runs batches of completely loaded models,
+// lane 1 one miss at a time (the model's swap-in followed by its batch); a
+// model whose miss is in flight is not dispatched again until that batch is
+// done.  The queues are scanned oldest head first and the first one that can
+// go (its lane is free, its model is not loading) does.  Returns the model and
+// sets *lane, or -1 when nothing can be dispatched now.
+constexpr int kHitLane = 0, kLoadLane = 1;
+template <class IsResident, class IsLoading>
+int pick_two_lane(const RequestQueues& q, IsResident is_resident, IsLoading is_loading, const bool lane_free[2],
+                  int* lane) {
+  for (int m : q.by_oldest_head()) {
+    if (is_loading(m)) continue;
+    const int l = is_resident(m) ? kHitLane : kLoadLane;
+    if (!lane_free[l]) continue;
+    *lane = l;
+    return m;
+  }
+  return -1;
+}
 
 // Which model to load ahead of its next request.  The paper's closing section
 // proposes speculative loading for request streams with structure (a model

@@ -56,8 +56,9 @@ struct Model {
   bool fragmented = true;            // more than 4 runs per block on average
   bool offload_enqueued = true;      // false between the eviction decision and the offload's enqueue
   std::vector<hipEvent_t> ev_block;  // recorded on the h2d stream after each block
-  hipEvent_t ev_in_start = nullptr, ev_out_start = nullptr, ev_out_done = nullptr, ev_last_use = nullptr;
-  bool used_since_load = false;      // ev_last_use recorded since the last swap-in
+  hipEvent_t ev_in_start = nullptr, ev_out_start = nullptr, ev_out_done = nullptr;
+  hipEvent_t ev_last_use[2] = {nullptr, nullptr};   // last inference on each of the two inference lanes
+  bool used[2] = {false, false};                    // that event has been recorded at least once
   bool load_recorded = false, out_recorded = false;
   bool pending_in = false, pending_out = false;
 
@@ -76,7 +77,7 @@ struct Model {
     drop_graphs();
     for (hipEvent_t e : ev_block)
       if (e) (void)hipEventDestroy(e);
-    for (hipEvent_t e : {ev_in_start, ev_out_start, ev_out_done, ev_last_use})
+    for (hipEvent_t e : {ev_in_start, ev_out_start, ev_out_done, ev_last_use[0], ev_last_use[1]})
       if (e) (void)hipEventDestroy(e);
   }
 };
@@ -105,6 +106,10 @@ struct ctn_ctx {
   // Library-owned streams only: an unmasked compute stream for inferences that
   // start while the link is quiet (all compute units, no copy wavefronts to avoid).
   hipStream_t s_wide = nullptr;
+  // Second inference lane (two-lane engine): a model that is still loading runs its batch here,
+  // behind its transfer blocks' events, while batches of loaded models go on as before.
+  hipStream_t s_lane1 = nullptr;
+  bool two_lanes = false;            // each lane then works in its own half of the workspace
   hipStream_t last_compute = nullptr;
   bool use_graphs = false;           // replay captured forward passes on the unmasked stream
   hipEvent_t ev_compute_done = nullptr;
@@ -264,7 +269,8 @@ int enqueue_offload(ctn_ctx* c, const Eviction& ev) {
   // one stream, so the last block's event covers the others) and must not
   // overtake an inference that is still reading it.
   CTN_HIP(c, hipStreamWaitEvent(c->s_d2h, m->ev_block[ev.b1 - 1], 0));
-  if (m->used_since_load) CTN_HIP(c, hipStreamWaitEvent(c->s_d2h, m->ev_last_use, 0));
+  for (int lane = 0; lane < 2; ++lane)
+    if (m->used[lane]) CTN_HIP(c, hipStreamWaitEvent(c->s_d2h, m->ev_last_use[lane], 0));
   CTN_HIP(c, hipEventRecord(m->ev_out_start, c->s_d2h));
   const ShardLayout& L = m->lay;
   uint64_t bytes = 0;
@@ -508,6 +514,7 @@ int create_partitioned_streams(ctn_ctx* c, int copy_cus) {
   CTN_HIP(c, make(0, copy_cus, &c->s_h2d));
   CTN_HIP(c, make(copy_cus, 2 * copy_cus, &c->s_d2h));
   CTN_HIP(c, make(2 * copy_cus, n_cu, &c->s_compute));
+  CTN_HIP(c, make(2 * copy_cus, n_cu, &c->s_lane1));
   CTN_HIP(c, hipStreamCreateWithFlags(&c->s_wide, hipStreamNonBlocking));
   CTN_HIP(c, hipEventCreateWithFlags(&c->ev_compute_done, hipEventDisableTiming));
   c->own_streams = true;
@@ -678,6 +685,7 @@ int ctn_sync(ctn_ctx* c) {
   CTN_HIP(c, hipStreamSynchronize(c->s_d2h));
   CTN_HIP(c, hipStreamSynchronize(c->s_compute));
   if (c->s_wide) CTN_HIP(c, hipStreamSynchronize(c->s_wide));
+  if (c->s_lane1) CTN_HIP(c, hipStreamSynchronize(c->s_lane1));
   purge_retired(c, true);
   for (auto& m : c->models) m->pending_in = m->pending_out = false;
   c->pending.clear();
@@ -689,7 +697,7 @@ int ctn_destroy(ctn_ctx* c) {
   int rc = ctn_sync(c);
   c->models.clear();   // destroys every model's events
   if (c->own_streams) {
-    for (hipStream_t st : {c->s_compute, c->s_h2d, c->s_d2h, c->s_wide})
+    for (hipStream_t st : {c->s_compute, c->s_h2d, c->s_d2h, c->s_wide, c->s_lane1})
       if (st) (void)hipStreamDestroy(st);
     if (c->ev_compute_done) (void)hipEventDestroy(c->ev_compute_done);
   }
@@ -773,7 +781,7 @@ int ctn_register_model(ctn_ctx* c, const ctn_model_desc* desc, const ctn_param* 
   CTN_HIP(c, hipEventCreate(&m->ev_in_start));
   CTN_HIP(c, hipEventCreate(&m->ev_out_start));
   CTN_HIP(c, hipEventCreate(&m->ev_out_done));
-  CTN_HIP(c, hipEventCreateWithFlags(&m->ev_last_use, hipEventDisableTiming));
+  for (hipEvent_t& e : m->ev_last_use) CTN_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   m->block_off.assign(L.n_blocks, 0);
   int idx = c->res.add_model(L.block_bytes);
   c->models.push_back(std::move(m));
@@ -839,7 +847,7 @@ uint64_t ctn_slot_bytes(const ctn_model_desc* desc) {
 // device when the caller asked for it in host memory (the caller copies it down).
 static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, const void* hidden_in, int32_t in_is_device,
                          int32_t batch, int32_t seq, void* logits_out, int32_t out_is_device, float** logits_dev,
-                         uint64_t* logits_bytes) {
+                         uint64_t* logits_bytes, int lane = 0) {
   Model* m = get_model(c, mi);
   if (!m) return c ? CTN_E_NOMODEL : CTN_E_INVAL;
   if (!logits_out) return CTN_E_INVAL;
@@ -851,8 +859,12 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, cons
   const int M = batch * seq;
   const bool own_logits = !out_is_device && L.has_head();
   Activations act{};
-  if (activation_bytes(d, M, own_logits, &act, static_cast<char*>(c->cfg.workspace_dev)) > c->cfg.workspace_bytes)
-    return CTN_E_SHAPE;
+  // with two lanes each works in its own half of the workspace
+  const uint64_t ws_half = c->cfg.workspace_bytes / 2 / kAlign * kAlign;
+  const uint64_t ws_cap = c->two_lanes ? ws_half : c->cfg.workspace_bytes;
+  char* ws_base = static_cast<char*>(c->cfg.workspace_dev) + (lane == 1 ? ws_half : 0);
+  if (lane < 0 || lane > 1 || (lane == 1 && !c->two_lanes)) return CTN_E_INVAL;
+  if (activation_bytes(d, M, own_logits, &act, ws_base) > ws_cap) return CTN_E_SHAPE;
   if (L.has_embed())
     for (int i = 0; i < M; ++i)
       if (ids_host[i] < 0 || ids_host[i] >= d.vocab) return CTN_E_INVAL;
@@ -865,8 +877,12 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, cons
   // off the copy kernels' compute units; when nothing is moving, the unmasked
   // stream gives it the whole chip.  Both orders of use are chained by an event.
   hipStream_t s = c->s_compute;
-  if (c->s_wide && link_quiet(c)) s = c->s_wide;
-  if (c->last_compute && c->last_compute != s) CTN_HIP(c, hipStreamWaitEvent(s, c->ev_compute_done, 0));
+  if (lane == 1) {
+    s = c->s_lane1;
+  } else {
+    if (c->s_wide && link_quiet(c)) s = c->s_wide;
+    if (c->last_compute && c->last_compute != s) CTN_HIP(c, hipStreamWaitEvent(s, c->ev_compute_done, 0));
+  }
   const uint64_t x_bytes = 4ull * M * d.hidden;
   if (L.has_embed()) {
     CTN_HIP(c, hipMemcpyAsync(act.ids, ids_host, 4ull * M, hipMemcpyHostToDevice, s));
@@ -878,7 +894,7 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, cons
   // A resident model on an idle link needs no event waits: the whole launch
   // sequence is captured once per (model placement, shape, output) as a HIP
   // graph and replayed, which removes the per-launch host cost of ~400 small kernels.
-  const bool replayable = c->use_graphs && s == c->s_wide && !m->pending_in;
+  const bool replayable = c->use_graphs && lane == 0 && s == c->s_wide && !m->pending_in;
   if (replayable) {
     rc = forward_graph(c, m, act, batch, seq, logits, s);
   } else {
@@ -889,9 +905,9 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, cons
     if (out_is_device) CTN_HIP(c, hipMemcpyAsync(logits_out, act.x, x_bytes, hipMemcpyDeviceToDevice, s));
     logits = act.x;
   }
-  CTN_HIP(c, hipEventRecord(m->ev_last_use, s));
-  m->used_since_load = true;
-  if (c->s_wide) {
+  CTN_HIP(c, hipEventRecord(m->ev_last_use[lane], s));
+  m->used[lane] = true;
+  if (c->s_wide && lane == 0) {
     CTN_HIP(c, hipEventRecord(c->ev_compute_done, s));
     c->last_compute = s;
     // whoever synchronises the primary compute stream also waits for this inference
@@ -1130,6 +1146,10 @@ struct ctn_engine {
   std::vector<int32_t> packed;   // ids of the batch being dispatched
   TransitionPredictor predictor;
   bool prefetch = false;
+  // two-lane engine: the batch in flight on each lane (model -1: none) and its completion event
+  bool two_lanes = false;
+  int lane_model[2] = {-1, -1};
+  hipEvent_t lane_done[2] = {nullptr, nullptr};
 };
 
 int ctn_engine_create(ctn_ctx* c, int32_t max_batch, int32_t seq, ctn_engine** out) {
@@ -1140,8 +1160,85 @@ int ctn_engine_create(ctn_ctx* c, int32_t max_batch, int32_t seq, ctn_engine** o
   return CTN_OK;
 }
 
+int ctn_engine_create_async(ctn_ctx* c, int32_t max_batch, int32_t seq, ctn_engine** out) {
+  if (!c || !out || max_batch < 1 || seq < 1) return CTN_E_INVAL;
+  if (!c->own_streams || !c->s_lane1) return CTN_E_INVAL;     // the second lane needs the library's own streams
+  ctn_engine* e = new (std::nothrow) ctn_engine{c, max_batch, seq, RequestQueues(), 0, {}, {}, false};
+  if (!e) return CTN_E_NOMEM;
+  e->two_lanes = true;
+  for (hipEvent_t& ev : e->lane_done)
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
+      c->last_hip = (int)hipGetLastError();
+      for (hipEvent_t x : e->lane_done)
+        if (x) (void)hipEventDestroy(x);
+      delete e;
+      return CTN_E_HIP;
+    }
+  c->two_lanes = true;          // from now on every inference stays inside its lane's half of the workspace
+  *out = e;
+  return CTN_OK;
+}
+
 int ctn_engine_destroy(ctn_engine* e) {
+  if (!e) return CTN_OK;
+  for (hipEvent_t ev : e->lane_done)
+    if (ev) (void)hipEventDestroy(ev);
   delete e;
+  return CTN_OK;
+}
+
+// Refreshes which lanes still have a batch in flight.
+static void refresh_lanes(ctn_engine* e) {
+  for (int l = 0; l < 2; ++l)
+    if (e->lane_model[l] >= 0 && hipEventQuery(e->lane_done[l]) == hipSuccess) e->lane_model[l] = -1;
+  (void)hipGetLastError();      // "not ready" is an answer
+}
+
+int ctn_engine_lanes(ctn_engine* e, int32_t* busy) {
+  if (!e || !busy || !e->two_lanes) return CTN_E_INVAL;
+  refresh_lanes(e);
+  for (int l = 0; l < 2; ++l) busy[l] = e->lane_model[l] >= 0 ? 1 : 0;
+  return CTN_OK;
+}
+
+int ctn_engine_dispatch(ctn_engine* e, void* const logits_out[2], int64_t* served, int32_t cap, int32_t* n_served,
+                        ctn_model* model, int32_t* was_miss, int32_t* lane_out) {
+  if (!e || !e->two_lanes || !logits_out || !logits_out[0] || !logits_out[1] || !served || !n_served ||
+      cap < e->max_batch)
+    return CTN_E_INVAL;
+  *n_served = 0;
+  ctn_ctx* c = e->ctx;
+  refresh_lanes(e);
+  const bool lane_free[2] = {e->lane_model[0] < 0, e->lane_model[1] < 0};
+  int lane = 0;
+  const int m = pick_two_lane(
+      e->queues, [&](int k) { return c->models[k]->full(); },
+      [&](int k) { return e->lane_model[kLoadLane] == k; }, lane_free, &lane);
+  if (m < 0) return CTN_OK;
+  std::vector<QueuedRequest> batch = e->queues.pop(m, e->max_batch);
+  e->packed.clear();
+  for (const QueuedRequest& r : batch) e->packed.insert(e->packed.end(), r.ids.begin(), r.ids.end());
+  float* result = nullptr;
+  uint64_t nbytes = 0;
+  int rc = infer_enqueue(c, m, e->packed.data(), nullptr, 0, static_cast<int32_t>(batch.size()), e->seq,
+                         logits_out[lane], 1, &result, &nbytes, lane);
+  const int rc2 = flush_deferred(c);
+  if (!rc) rc = rc2;
+  if (!rc && hipEventRecord(e->lane_done[lane], lane == kLoadLane ? c->s_lane1 : (c->last_compute ? c->last_compute : c->s_compute)) != hipSuccess) {
+    c->last_hip = (int)hipGetLastError();
+    rc = CTN_E_HIP;
+  }
+  if (rc) {   // put the requests back in order so nothing is lost
+    for (auto it = batch.rbegin(); it != batch.rend(); ++it) e->queues.push_front(m, std::move(*it));
+    return rc;
+  }
+  e->lane_model[lane] = m;
+  for (size_t i = 0; i < batch.size(); ++i) served[i] = batch[i].id;
+  *n_served = static_cast<int32_t>(batch.size());
+  if (model) *model = m;
+  if (was_miss) *was_miss = lane == kLoadLane ? 1 : 0;
+  if (lane_out) *lane_out = lane;
+  e->predictor.observe(m);
   return CTN_OK;
 }
 
@@ -1169,7 +1266,7 @@ int ctn_engine_pending(ctn_engine* e, int64_t* n) {
 
 int ctn_engine_step(ctn_engine* e, void* logits_out, int64_t* served, int32_t cap, int32_t* n_served,
                     ctn_model* model, int32_t* was_miss) {
-  if (!e || !logits_out || !served || !n_served || cap < e->max_batch) return CTN_E_INVAL;
+  if (!e || e->two_lanes || !logits_out || !served || !n_served || cap < e->max_batch) return CTN_E_INVAL;
   *n_served = 0;
   const int m = e->queues.pick();
   if (m < 0) return CTN_OK;
@@ -1274,6 +1371,72 @@ int ctn_engine_replay(int32_t n_models, int32_t max_batch, uint64_t budget, cons
     b.offset = served;
     for (const QueuedRequest& r : batch) requests[served++] = static_cast<uint64_t>(r.id);
     now = b.finish;
+  }
+  *n_batches = nb;
+  return CTN_OK;
+}
+
+int ctn_engine_replay_async(int32_t n_models, int32_t max_batch, uint64_t budget, const uint64_t* sizes,
+                            const double* arrival, const int32_t* model_of, uint64_t n, double t_base,
+                            double t_per_request, double t_miss, ctn_batch_record* batches, uint64_t cap,
+                            uint64_t* n_batches, uint64_t* requests) {
+  if (n_models <= 0 || max_batch < 1 || !sizes || !n_batches || (n && (!arrival || !model_of || !batches || !requests)))
+    return CTN_E_INVAL;
+  for (uint64_t i = 0; i < n; ++i) {
+    if (model_of[i] < 0 || model_of[i] >= n_models) return CTN_E_NOMODEL;
+    if (i && arrival[i] < arrival[i - 1]) return CTN_E_INVAL;
+  }
+  Residency res(budget);
+  for (int i = 0; i < n_models; ++i) {
+    if (sizes[i] > budget) return CTN_E_TOO_BIG;
+    res.add_model(sizes[i]);
+  }
+  RequestQueues queues(n_models);
+  double now = 0.0, lane_until[2] = {0.0, 0.0};
+  int loading = -1;                       // model whose miss occupies lane 1
+  uint64_t nxt = 0, served = 0, nb = 0;
+  while (served < n) {
+    while (nxt < n && arrival[nxt] <= now) {
+      queues.push(model_of[nxt], QueuedRequest{static_cast<int64_t>(nxt), arrival[nxt], {}});
+      ++nxt;
+    }
+    if (lane_until[kLoadLane] <= now) loading = -1;
+    for (;;) {
+      const bool lane_free[2] = {lane_until[0] <= now, lane_until[1] <= now};
+      int lane = 0;
+      const int m = pick_two_lane(
+          queues, [&](int k) { return res.resident(k); }, [&](int k) { return loading == k; }, lane_free, &lane);
+      if (m < 0) break;
+      std::vector<QueuedRequest> batch = queues.pop(m, max_batch);
+      const bool miss = lane == kLoadLane;
+      if (miss) {
+        std::vector<Residency::Move> moves;
+        while (res.over_budget_with(m))
+          if (res.evict_step(m, moves) < 0) return CTN_E_BUSY;
+        res.load_missing(m);
+        loading = m;
+      } else {
+        res.touch(m);
+      }
+      if (nb >= cap) return CTN_E_INVAL;
+      ctn_batch_record& b = batches[nb++];
+      b.start = now;
+      b.finish = now + t_base + t_per_request * static_cast<double>(batch.size()) + (miss ? t_miss : 0.0);
+      b.model = m;
+      b.count = static_cast<int32_t>(batch.size());
+      b.miss = miss ? 1 : 0;
+      b.reserved = lane;
+      b.offset = served;
+      for (const QueuedRequest& r : batch) requests[served++] = static_cast<uint64_t>(r.id);
+      lane_until[lane] = b.finish;
+    }
+    if (served == n) break;
+    double next = -1.0;
+    for (double t : lane_until)
+      if (t > now && (next < 0 || t < next)) next = t;
+    if (nxt < n && (next < 0 || arrival[nxt] < next)) next = arrival[nxt];
+    if (next < 0) return CTN_E_BUSY;      // cannot happen: requests wait only for lanes or arrivals
+    now = next;
   }
   *n_batches = nb;
   return CTN_OK;

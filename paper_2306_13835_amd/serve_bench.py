@@ -41,8 +41,10 @@ def run_serve(args):
     # model holds a prefix of one more model, so the arena gets one more range than the whole-model case.
     one = P.slot_bytes(desc) * (desc.layers + 1) if blocks else P.arena_bytes(desc)
     arena = torch.empty((resident_max + (2 if blocks else 1)) * one, dtype=torch.uint8, device="cuda")
-    ws = torch.empty(P.workspace_bytes(desc, batch * seq), dtype=torch.uint8, device="cuda")
+    two_lanes = bool(getattr(args, "two_lane", False))
+    ws = torch.empty(P.workspace_bytes(desc, batch * seq) * (2 if two_lanes else 1) + 512, dtype=torch.uint8, device="cuda")
     logits = torch.empty(batch, seq, desc.vocab // desc.tp, dtype=torch.float32, device="cuda")
+    logits2 = torch.empty_like(logits)
     ctx = P.Context(budget, arena, ws, transfer_mode={"dma": 0, "kernel": 1, "auto": 2}[args.transfer],
                     pipeline=True, block_residency=blocks)
     n_t = len(param_list(desc))
@@ -76,9 +78,30 @@ def run_serve(args):
 
     t0 = time.perf_counter()
     missing = []
-    lat, svc, miss = serve_trace(ctx, models, arr, mod, lambda i: ids[i], logits, progress=progress,
-                                 missing_blocks=missing)
-    missing = np.asarray(missing)
+    if two_lanes:
+        # the asynchronous engine of Section 3.2 (batch size 1 as in this workload): hits go on while a model loads
+        from paper_2306_13835_amd.serving import serve_engine_async
+        eng = P.Engine(ctx, batch, seq, two_lanes=True)
+        miss = np.zeros(n_req, dtype=bool)
+        count = [0]
+
+        def on_batch(served, m, was_miss, lane, intact):
+            miss[served] = was_miss
+            count[0] += len(served)
+            progress(count[0] - 1)
+        lat, batches = serve_engine_async(ctx, eng, models, arr, mod, lambda i: ids[i], logits, logits2, on_batch)
+        eng.close()
+        # time from dispatch to completion of each request's batch (requests are batches of one here)
+        svc_hit = np.array([b[3] for b in batches if not b[2]])
+        svc_miss = np.array([b[3] for b in batches if b[2]])
+        svc = np.zeros(n_req)
+        svc[~miss] = np.resize(svc_hit, int((~miss).sum())) if svc_hit.size else 0.0
+        svc[miss] = np.resize(svc_miss, int(miss.sum())) if svc_miss.size else 0.0
+        missing = np.where(miss, desc.layers + 1, 0)
+    else:
+        lat, svc, miss = serve_trace(ctx, models, arr, mod, lambda i: ids[i], logits, progress=progress,
+                                     missing_blocks=missing)
+        missing = np.asarray(missing)
     whole_miss = missing == desc.layers + 1
     part_miss = (missing > 0) & ~whole_miss
     wall = time.perf_counter() - t0
@@ -86,7 +109,17 @@ def run_serve(args):
     st = ctx.stats()
     events = ctx.events()[ev0:]
     # the decisions taken on the GPU path must be the ones the policy takes on the bare trace
-    if blocks:
+    if two_lanes:
+        # requests overtake one another, so the policy is replayed on the order of dispatch
+        order = [e[1] for e in events]
+        if blocks:
+            n = [2 * int(np.prod(shape)) for _, shape, _ in param_list(desc)]
+            bb = [n[0] + n[1] + n[-2] + n[-1]] + [sum(n[2 + 16 * l:18 + 16 * l]) for l in range(desc.layers)]
+            replay = P.block_residency_replay(budget, [bb] * n_models, order)[0]
+        else:
+            replay = P.residency_replay(budget, [nbytes] * n_models, order)
+        decisions_match = [(e[0], e[1], e[2]) for e in events] == replay
+    elif blocks:
         n = [2 * int(np.prod(shape)) for _, shape, _ in param_list(desc)]
         bb = [n[0] + n[1] + n[-2] + n[-1]] + [sum(n[2 + 16 * l:18 + 16 * l]) for l in range(desc.layers)]
         replay, block_replay = P.block_residency_replay(budget, [bb] * n_models, [int(x) for x in mod])
@@ -102,7 +135,9 @@ def run_serve(args):
         "ms_per_step": round(wall / n_req * 1e3, 3), "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"serve8x6.7b_tp2: {n_models} shards x {nbytes} B, budget {budget} B, {n_req} requests "
-                               f"batch {batch} x seq {seq}, serial oldest-first engine, LRU",
+                               f"batch {batch} x seq {seq}, "
+                               + ("two-lane engine (hits go on while a model loads)" if two_lanes else "serial oldest-first engine")
+                               + ", LRU",
                    "transfer": args.transfer, "host_layout": args.host_layout,
                    "residency": "per transfer block (prefix kept)" if blocks else "whole models (2 resident)",
                    "arena_bytes": int(arena.numel()), "arena_note": "budget + one transit range"},
@@ -169,11 +204,14 @@ def run_grid(args):
     for name, n_models, resident, max_batch, skews in GRIDS:
         budget = resident * nbytes
         arena = torch.empty((resident + 1) * P.arena_bytes(desc), dtype=torch.uint8, device="cuda")
-        ws = torch.empty(P.workspace_bytes(desc, max_batch * seq), dtype=torch.uint8, device="cuda")
+        two_lanes = bool(getattr(args, "two_lane", False))
+        ws = torch.empty(P.workspace_bytes(desc, max_batch * seq) * (2 if two_lanes else 1) + 512, dtype=torch.uint8,
+                         device="cuda")
         logits = torch.empty(max_batch, seq, desc.vocab // desc.tp, dtype=torch.float32, device="cuda")
+        logits2 = torch.empty_like(logits)
         ctx = P.Context(budget, arena, ws, transfer_mode={"dma": 0, "kernel": 1, "auto": 2}[args.transfer], pipeline=True)
         models = [ctx.register_model(desc, keep[k]) for k in range(n_models)]
-        eng = P.Engine(ctx, max_batch, seq)
+        eng = P.Engine(ctx, max_batch, seq, two_lanes=two_lanes)
         table = {}
         for skew in skews:
             row = []
@@ -182,10 +220,18 @@ def run_grid(args):
                 ids = [token_ids(2000 + i, 1, seq, desc.vocab) for i in range(len(arr))]
                 for k in range(min(resident, n_models)):       # warm-up requests, not recorded (Section 5.2)
                     eng.submit(models[k], ids[0], 0.0)
-                    eng.step(logits)
+                    if two_lanes:
+                        eng.dispatch(logits, logits2)
+                        ctx.sync()
+                    else:
+                        eng.step(logits)
                 ctx.sync()
                 st0 = ctx.stats()
-                lat, batches = serve_engine(ctx, eng, models, arr, mod, lambda i: ids[i], logits)
+                if two_lanes:
+                    from paper_2306_13835_amd.serving import serve_engine_async
+                    lat, batches = serve_engine_async(ctx, eng, models, arr, mod, lambda i: ids[i], logits, logits2)
+                else:
+                    lat, batches = serve_engine(ctx, eng, models, arr, mod, lambda i: ids[i], logits)
                 ctx.sync()
                 st = ctx.stats()
                 row.append({"cv": cv, "requests": len(arr), "mean_s": round(float(lat.mean()), 4),
@@ -202,7 +248,9 @@ def run_grid(args):
     out = {"metric": "average end-to-end request latency per (rates, CV), the paper's Section 5.2 grids on one worker's shard",
            "unit": "s", "n_gpus": 1, "higher_is_better": False, "data": "synthetic", "dtype": "f16",
            "config": {"workload": f"opt13b_tp4 shard ({nbytes} B) x 3 and x 6 models, {args.duration:.0f} s Gamma arrivals, "
-                                  f"{seq} tokens per request, oldest-first batching, LRU", "transfer": args.transfer,
+                                  f"{seq} tokens per request, oldest-first batching, LRU, "
+                                  + ("two-lane engine" if getattr(args, "two_lane", False) else "serial engine"),
+                      "transfer": args.transfer,
                       "host_layout": args.host_layout},
            "results": results, "paper_tables_context": PAPER_TABLES}
     del keep

@@ -88,3 +88,63 @@ def serve_engine(ctx, engine, models: Sequence[int], arrival_s: np.ndarray, mode
         if on_batch is not None:
             on_batch(served, m, miss)
     return lat, batches
+
+
+def serve_engine_async(ctx, engine, models: Sequence[int], arrival_s: np.ndarray, model_of: np.ndarray,
+                       ids_of: Callable[[int], np.ndarray], out_hit, out_load, on_batch: Callable = None):
+    """Real-time replay through the two-lane engine (Section 3.2: batches of loaded models go on
+    while another model loads).  The loop submits requests as they arrive, dispatches whatever can
+    go, and notes a batch's completion when its lane reports idle.
+    Returns (latency_s per request, list of (n_requests, model, was_miss, service_s, lane) per batch).
+    `on_batch(request indices, model, was_miss, lane, logits_intact)` is called at every completion."""
+    n = len(arrival_s)
+    lat = np.zeros(n)
+    batches = []
+    nxt = done = 0
+    base = None
+    flying = [None, None]            # per lane: (request indices, model, miss, start time)
+    t0 = time.perf_counter()
+
+    def finished(lane, intact=True):
+        """The batch that was in flight on `lane` has completed; `intact`: its logits are still in
+        the lane's buffer (no newer batch has been dispatched there)."""
+        nonlocal done
+        end = time.perf_counter() - t0
+        served, m, miss, start = flying[lane]
+        flying[lane] = None
+        for rid in served:
+            lat[rid] = end - arrival_s[rid]
+        done += len(served)
+        batches.append((len(served), m, miss, end - start, lane))
+        if on_batch is not None:
+            on_batch(served, m, miss, lane, intact)
+
+    while done < n:
+        now = time.perf_counter() - t0
+        while nxt < n and arrival_s[nxt] <= now:
+            rid = engine.submit(models[int(model_of[nxt])], ids_of(nxt), float(arrival_s[nxt]))
+            if base is None:
+                base = rid
+            assert rid - base == nxt
+            nxt += 1
+        if flying[0] is not None or flying[1] is not None:
+            busy = engine.lanes_busy()
+            for lane in (0, 1):
+                if flying[lane] is not None and not busy[lane]:
+                    finished(lane)
+        if done == n:
+            break
+        start = time.perf_counter() - t0
+        r = engine.dispatch(out_hit, out_load)
+        if r is not None:
+            served, m, miss, lane = r
+            if flying[lane] is not None:     # the engine saw that lane's batch complete just now and reused the lane
+                finished(lane, intact=False)
+            flying[lane] = ([rid - base for rid in served], m, miss, start)
+            continue
+        if flying[0] is None and flying[1] is None and nxt < n:
+            engine.idle()
+            pause = arrival_s[nxt] - (time.perf_counter() - t0)
+            if pause > 0:
+                time.sleep(min(pause, 0.002))
+    return lat, batches

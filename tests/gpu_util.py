@@ -11,14 +11,14 @@ class Rig:
     """A context with its arena, workspace, streams and pinned host pool."""
 
     def __init__(self, descs, budget=None, max_tokens=64, arena_bytes=None, mode=P.XFER_KERNEL,
-                 pipeline=True, host_bytes=None, torch_streams=False, gap=0, block_residency=False):
+                 pipeline=True, host_bytes=None, torch_streams=False, gap=0, block_residency=False, two_lanes=False):
         self.dev = torch.device("cuda:0")
         torch.cuda.set_device(0)
         streams = [torch.cuda.Stream() for _ in range(3)] if torch_streams else [None] * 3
         need = [P.slot_bytes(d) * (d.local_layers + 1) if block_residency else P.arena_bytes(d) for d in descs]
         arena_bytes = arena_bytes or sum(need)
         budget = budget or sum(shard_bytes(d) for d in descs)
-        ws = max(P.workspace_bytes(d, max_tokens) for d in descs)
+        ws = max(P.workspace_bytes(d, max_tokens) for d in descs) * (2 if two_lanes else 1) + 512
         self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device=self.dev)
         self.workspace = torch.empty(ws, dtype=torch.uint8, device=self.dev)
         torch.cuda.synchronize()

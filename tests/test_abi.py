@@ -176,3 +176,19 @@ def test_load_ahead_predictor_equals_oracle():
         P.predictor_replay(2, [0, 2])
     with pytest.raises(P.CtnError):
         P.predictor_replay(2, [0, 1], min_count=0)
+
+
+@given(st.lists(st.tuples(st.integers(0, 60), st.integers(0, 3)), min_size=1, max_size=40), st.integers(1, 4),
+       st.integers(1, 3))
+@settings(max_examples=150, deadline=None)
+def test_two_lane_engine_schedule_equals_oracle(reqs, max_batch, capacity):
+    from oracle.engine import simulate_async
+    reqs = sorted(reqs, key=lambda r: r[0])
+    arrival = [float(a) for a, _ in reqs]
+    model_of = [m for _, m in reqs]
+    t_base, t_per, t_miss = 0.5, 0.25, 3.0
+    got = P.engine_replay(4, max_batch, capacity * 10, [10] * 4, arrival, model_of, t_base, t_per, t_miss,
+                          two_lanes=True)
+    want, _ = simulate_async(arrival, model_of, 4, max_batch, capacity * 10, [10] * 4,
+                             lambda m, b, miss: t_base + t_per * b + (t_miss if miss else 0.0))
+    assert [(a, b, m, tuple(r), x, l) for a, b, m, r, x, l in got] == [tuple(w) for w in want]

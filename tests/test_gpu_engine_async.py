@@ -1,0 +1,131 @@
+"""The two-lane engine through the C ABI: batches of loaded models go on while another model loads
+(Section 3.2 of the paper).  Every request is answered once and correctly, order within a model is
+kept, the residency decisions equal the LRU oracle's on the order of dispatch."""
+import time
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+import paper_2306_13835_amd as P
+from oracle import opt_shard as O
+from oracle.lru import LruResidency
+from oracle.swap import as_bytes
+from synth import ShardDesc, shard_bytes, token_ids, gamma_rates_trace
+from gpu_util import Rig
+
+pytestmark = pytest.mark.gpu
+
+DESC = ShardDesc(4, 1024, 4096, 8, vocab=8192, max_pos=64)      # ~118 MB: a load takes milliseconds
+SEQ, MAXB = 8, 4
+
+
+def make(n_models, resident, **kw):
+    size = shard_bytes(DESC)
+    rig = Rig([DESC] * n_models, budget=resident * size + 7, arena_bytes=(resident + 1) * P.arena_bytes(DESC),
+              max_tokens=MAXB * SEQ, mode=P.XFER_AUTO, two_lanes=True, **kw)
+    eng = P.Engine(rig.ctx, MAXB, SEQ, two_lanes=True)
+    ms = [rig.add(DESC, seed=160 + i) for i in range(n_models)]
+    bufs = [torch.empty(MAXB, SEQ, DESC.vocab, dtype=torch.float32, device="cuda") for _ in range(2)]
+    return rig, eng, ms, bufs
+
+
+def check_rows(rig, m, ids_list, got):
+    for row, ids in enumerate(ids_list):
+        want = O.forward(rig.tensors[m], ids, layers=DESC.layers, heads=DESC.heads)
+        assert np.abs(got[row] - want[0]).max() <= 2e-2
+        assert np.abs(got[row] - want[0]).mean() / np.abs(want).mean() <= 1e-3
+
+
+def test_hit_is_dispatched_while_a_miss_is_in_flight():
+    rig, eng, ms, bufs = make(3, 2)
+    try:
+        ids = [token_ids(500 + i, 1, SEQ, DESC.vocab) for i in range(6)]
+        # load model 0 through its first request
+        eng.submit(ms[0], ids[0], 0.0)
+        served, m, miss, lane = eng.dispatch(*bufs)
+        assert (served, m, miss, lane) == ([0], 0, True, 1)
+        assert eng.dispatch(*bufs) is None                     # nothing else queued
+        rig.ctx.sync()
+        assert eng.lanes_busy() == (False, False)
+        check_rows(rig, 0, [ids[0]], bufs[1].cpu().numpy())
+        # a miss on model 1, then a hit on model 0
+        eng.submit(ms[1], ids[1], 1.0)
+        eng.submit(ms[0], ids[2], 2.0)
+        a = eng.dispatch(*bufs)
+        b = eng.dispatch(*bufs)
+        assert a == ([1], 1, True, 1)                          # oldest head: model 1, not resident -> load lane
+        assert b == ([2], 0, False, 0)                         # the hit goes on the other lane at once
+        # a second request for model 1: not dispatched while model 1's miss is in flight
+        eng.submit(ms[1], ids[3], 3.0)
+        c = eng.dispatch(*bufs)
+        if c is None:
+            assert eng.pending() == 1
+            rig.ctx.sync()
+            check_rows(rig, 1, [ids[1]], bufs[1].cpu().numpy())
+            check_rows(rig, 0, [ids[2]], bufs[0].cpu().numpy())
+            c = eng.dispatch(*bufs)
+        assert c == ([3], 1, False, 0)                         # model 1 is loaded: its second request is a hit
+        rig.ctx.sync()
+        check_rows(rig, 1, [ids[3]], bufs[0].cpu().numpy())
+        assert eng.pending() == 0
+        with pytest.raises(P.CtnError):
+            eng.step(bufs[0])                                  # the serial entry point is not for this engine
+    finally:
+        eng.close()
+        rig.close()
+
+
+def test_trace_every_request_once_in_order_and_right():
+    from paper_2306_13835_amd.serving import serve_engine_async
+    rig, eng, ms, bufs = make(4, 2)
+    try:
+        orig = [[t.copy() for t in rig.tensors[m]] for m in ms]
+        arr, mod = gamma_rates_trace((60, 30, 30, 10), 4.0, 1.5, seed=77)
+        n = len(arr)
+        assert 60 < n < 600
+        ids = [token_ids(600 + i % 5, 1, SEQ, DESC.vocab) for i in range(n)]
+        order, checked = [], [0]
+
+        def on_batch(served, m, miss, lane, intact):
+            order.append((tuple(served), m, miss, lane))
+            if intact and checked[0] < 12:                             # spot-check some batches against the oracle
+                rig.ctx.sync()
+                check_rows(rig, m, [ids[r] for r in served], bufs[lane].cpu().numpy())
+                checked[0] += 1
+        lat, batches = serve_engine_async(rig.ctx, eng, ms, arr, mod, lambda i: ids[i], bufs[0], bufs[1], on_batch)
+        rig.ctx.sync()
+        served = [r for b in order for r in b[0]]
+        assert sorted(served) == list(range(n))
+        for m in range(4):
+            mine = [r for b in order for r in b[0] if b[1] == m]
+            assert mine == sorted(mine)
+        assert all(1 <= len(b[0]) <= MAXB and all(mod[r] == b[1] for r in b[0]) for b in order)
+        assert all(b[3] == (1 if b[2] else 0) for b in order)
+        assert (lat > 0).all()
+        # decisions = LRU on the order in which batches were dispatched (completion order may differ)
+        events = rig.ctx.events()
+        ref = LruResidency(2 * shard_bytes(DESC) + 7, [shard_bytes(DESC)] * 4)
+        for kind, m, victims in events:
+            assert ref.touch(m) == (kind, m, victims)
+        assert sum(e[0] == "miss" for e in events) == sum(b[2] for b in order)
+        for m in ms:
+            for t, o in zip(rig.tensors[m], orig[m]):
+                assert np.array_equal(as_bytes(t), as_bytes(o))
+    finally:
+        eng.close()
+        rig.close()
+
+
+def test_needs_library_streams_and_the_right_entry_points():
+    size = shard_bytes(DESC)
+    rig = Rig([DESC], budget=size, max_tokens=MAXB * SEQ, torch_streams=True, two_lanes=True)
+    try:
+        with pytest.raises(P.CtnError):
+            P.Engine(rig.ctx, MAXB, SEQ, two_lanes=True)       # caller-supplied streams have no second lane
+        eng = P.Engine(rig.ctx, MAXB, SEQ)
+        with pytest.raises(P.CtnError):
+            eng.dispatch(rig.arena, rig.arena)
+        eng.close()
+    finally:
+        rig.close()
