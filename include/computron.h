@@ -319,7 +319,9 @@ int ctn_engine_create_async(ctn_ctx* ctx, int32_t max_batch, int32_t seq, ctn_en
  * logits_out[lane] (device, fp32 [max_batch, seq, vocab/tp], one buffer per
  * lane) receives the batch's logits; the call returns with the work enqueued.
  * *n_served == 0 when nothing can be dispatched now (queues empty, lanes busy
- * or models loading).  *lane tells where the batch runs (0 hit lane, 1 load lane). */
+ * or models loading).  *lane tells where the batch runs (0 hit lane, 1 load lane;
+ * a model that ctn_engine_idle started loading and that is still arriving also
+ * takes the load lane, with *was_miss == 0). */
 int ctn_engine_dispatch(ctn_engine* eng, void* const logits_out[2], int64_t* served_ids, int32_t cap,
                         int32_t* n_served, ctn_model* model, int32_t* was_miss, int32_t* lane);
 /* busy[l] = 1 while the batch last dispatched on lane l has not completed

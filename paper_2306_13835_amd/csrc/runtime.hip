@@ -1211,10 +1211,20 @@ int ctn_engine_dispatch(ctn_engine* e, void* const logits_out[2], int64_t* serve
   refresh_lanes(e);
   const bool lane_free[2] = {e->lane_model[0] < 0, e->lane_model[1] < 0};
   int lane = 0;
+  // "Loaded" = every block resident and landed.  A model whose load was started ahead of its
+  // request (ctn_engine_idle) and is still arriving takes the load lane like a miss, so that its
+  // batch waits there and not in front of the loaded models' batches.
+  auto loaded = [&](int k) {
+    Model* mk = c->models[k].get();
+    if (!mk->full()) return false;
+    if (mk->pending_in && hipEventQuery(mk->ev_block.back()) == hipSuccess) mk->pending_in = false;
+    return !mk->pending_in;
+  };
   const int m = pick_two_lane(
-      e->queues, [&](int k) { return c->models[k]->full(); },
-      [&](int k) { return e->lane_model[kLoadLane] == k; }, lane_free, &lane);
+      e->queues, loaded, [&](int k) { return e->lane_model[kLoadLane] == k; }, lane_free, &lane);
+  (void)hipGetLastError();
   if (m < 0) return CTN_OK;
+  const bool miss = !c->models[m]->full();
   std::vector<QueuedRequest> batch = e->queues.pop(m, e->max_batch);
   e->packed.clear();
   for (const QueuedRequest& r : batch) e->packed.insert(e->packed.end(), r.ids.begin(), r.ids.end());
@@ -1236,7 +1246,7 @@ int ctn_engine_dispatch(ctn_engine* e, void* const logits_out[2], int64_t* serve
   for (size_t i = 0; i < batch.size(); ++i) served[i] = batch[i].id;
   *n_served = static_cast<int32_t>(batch.size());
   if (model) *model = m;
-  if (was_miss) *was_miss = lane == kLoadLane ? 1 : 0;
+  if (was_miss) *was_miss = miss ? 1 : 0;
   if (lane_out) *lane_out = lane;
   e->predictor.observe(m);
   return CTN_OK;

@@ -129,9 +129,9 @@ def serve_engine_async(ctx, engine, models: Sequence[int], arrival_s: np.ndarray
             nxt += 1
         if flying[0] is not None or flying[1] is not None:
             busy = engine.lanes_busy()
-            for lane in (0, 1):
-                if flying[lane] is not None and not busy[lane]:
-                    finished(lane)
+            ready = [lane for lane in (0, 1) if flying[lane] is not None and not busy[lane]]
+            for lane in sorted(ready, key=lambda l: flying[l][3]):     # noticed together: report in dispatch order
+                finished(lane)
         if done == n:
             break
         start = time.perf_counter() - t0

@@ -129,3 +129,48 @@ def test_needs_library_streams_and_the_right_entry_points():
         eng.close()
     finally:
         rig.close()
+
+
+def test_model_that_is_loading_ahead_takes_the_load_lane():
+    """A model whose load was started ahead of its request and is still arriving must not make the
+    batches of loaded models wait: its batch goes to the load lane, and is no miss."""
+    rig, eng, ms, bufs = make(3, 2)
+    try:
+        eng.set_prefetch(True, min_count=1, min_share_percent=50)
+        ids = [token_ids(700 + i, 1, SEQ, DESC.vocab) for i in range(8)]
+
+        def serve(model, k):
+            eng.submit(ms[model], ids[k], float(k))
+            r = eng.dispatch(*bufs)
+            assert r is not None and r[1] == model
+            rig.ctx.sync()
+            check_rows(rig, model, [ids[k]], bufs[r[3]].cpu().numpy())
+            return r
+        serve(0, 0); serve(1, 1); serve(0, 2)        # teaches 0 -> 1 and 1 -> 0; resident {0, 1}
+        serve(2, 3)                                  # evicts 1; resident {0, 2}
+        r = serve(0, 4)
+        assert r[2] is False and r[3] == 0           # a plain hit
+        ahead = eng.idle()                           # nothing queued: model 1 is predicted and starts loading
+        assert ahead == ms[1] and rig.ctx.is_resident(ms[1])
+        eng.submit(ms[1], ids[5], 5.0)
+        eng.submit(ms[0], ids[6], 6.0)
+        a = eng.dispatch(*bufs)
+        b = eng.dispatch(*bufs)
+        assert a[1] == 1 and a[2] is False           # not a miss: the load was already under way
+        if a[3] == 1:                                # still arriving: load lane, and model 0 goes ahead on the hit lane
+            assert b == ([6], 0, False, 0)
+            rig.ctx.sync()
+            check_rows(rig, 1, [ids[5]], bufs[1].cpu().numpy())
+            check_rows(rig, 0, [ids[6]], bufs[0].cpu().numpy())
+        else:                                        # it had landed already: both are hits, one after the other
+            rig.ctx.sync()
+            check_rows(rig, 1, [ids[5]], bufs[0].cpu().numpy())
+            b = b or eng.dispatch(*bufs)
+            assert b == ([6], 0, False, 0)
+            rig.ctx.sync()
+            check_rows(rig, 0, [ids[6]], bufs[0].cpu().numpy())
+        print("model loading ahead ran on lane", a[3], flush=True)
+        assert rig.ctx.stats()["n_prefetch"] == 1
+    finally:
+        eng.close()
+        rig.close()
