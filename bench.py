@@ -204,6 +204,21 @@ def run_swap(args):
     for _ in range(5):
         t = time.perf_counter(); request(0); ts.append((time.perf_counter() - t) * 1e3)
     side["forward_resident_ms"] = median(ts)
+    # the hit path at the request sizes of the paper's workloads (8 tokens; 1 x 64 in the serving trace):
+    # every weight byte is read once, so the bound is shard bytes / HBM bandwidth
+    if desc.has_embed:
+        for tokens in (8, 64):
+            if tokens > M or tokens > desc.max_pos:
+                continue
+            small_ids = token_ids(cfg["idseed"] + 7, 1, tokens, desc.vocab)
+            small_out = torch.empty(1, tokens, desc.out_features, dtype=torch.float32, device="cuda")
+            ts = []
+            for _ in range(8):
+                t = time.perf_counter()
+                ctx.infer(models[0], small_ids, out=small_out)
+                s_c.synchronize()
+                ts.append((time.perf_counter() - t) * 1e3)
+            side[f"forward_resident_1x{tokens}_ms"] = median(ts[3:])
     ctx.swap_out(models[0]); ctx.wait(models[0])
     ctx.sync()
 
@@ -284,6 +299,11 @@ def run_swap(args):
             "forward_resident_tokens_per_s": round(M / side["forward_resident_ms"] * 1e3, 1),
             "forward_resident_tflops": round(flop / side["forward_resident_ms"] / 1e9, 2),
             "forward_frac_of_mfma_f16_peak": round(flop / side["forward_resident_ms"] / 1e9 / MFMA_F16_PEAK_TFLOPS, 4),
+            "forward_small_requests": {
+                f"1x{t}": {"ms": round(side[f"forward_resident_1x{t}_ms"], 3),
+                           "weight_stream_bound_ms": round(nbytes / HBM_PEAK_GBPS / 1e6, 3),
+                           "frac_of_hbm_peak": round(nbytes / HBM_PEAK_GBPS / 1e6 / side[f"forward_resident_1x{t}_ms"], 4)}
+                for t in (8, 64) if f"forward_resident_1x{t}_ms" in side},
         },
         "roofline": {
             "kernel": "copy_table_kernel<0> (host -> HBM, one launch per transfer block)",

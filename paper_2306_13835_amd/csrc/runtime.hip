@@ -228,6 +228,40 @@ uint64_t block_footprint(const ctn_ctx* c, const ShardLayout& L, int b) {
   return c->res.block_mode() ? L.slot_bytes : L.block_span[b];
 }
 
+// Moves transfer block b of model m between its host tensors and `base` (where the block sits,
+// or will sit, in the arena) on stream s.  how: 0 = one hipMemcpyAsync per tensor (the paper's
+// per-tensor messages, Section 5.1), 1 = one copy-kernel launch over the block's runs, 2 = one
+// hipMemcpyAsync per run of adjacent tensors.
+enum { kPerTensorDma = 0, kCopyKernel = 1, kPerRunDma = 2 };
+int copy_block(ctn_ctx* c, Model* m, int b, char* base, bool to_device, int how, hipStream_t s) {
+  const ShardLayout& L = m->lay;
+  if (m->runs[b].empty()) return CTN_OK;        // a stage without tensors outside its layers
+  if (how == kCopyKernel) {
+    CopyTable t{};
+    for (const Model::Run& r : m->runs[b]) {
+      char* dev = base + L.offset_in_block(r.first);
+      t.seg[t.n].src = to_device ? m->host_dev[r.first] : dev;
+      t.seg[t.n].dst = to_device ? dev : m->host_dev[r.first];
+      t.seg[t.n].n16 = r.bytes / 16;
+      ++t.n;
+    }
+    if (!copy_table_finish(t)) return CTN_E_INVAL;
+    CTN_HIP(c, launch_copy_table(t, c->cfg.copy_blocks, s, to_device ? kCopyH2D : kCopyD2H));
+    return CTN_OK;
+  }
+  auto one = [&](int ti, uint64_t bytes) {
+    char* dev = base + L.offset_in_block(ti);
+    return to_device ? hipMemcpyAsync(dev, m->host[ti], bytes, hipMemcpyHostToDevice, s)
+                     : hipMemcpyAsync(m->host[ti], dev, bytes, hipMemcpyDeviceToHost, s);
+  };
+  if (how == kPerTensorDma) {
+    for (int ti : L.block_tensors[b]) CTN_HIP(c, one(ti, L.nbytes[ti]));
+  } else {
+    for (const Model::Run& r : m->runs[b]) CTN_HIP(c, one(r.first, r.bytes));
+  }
+  return CTN_OK;
+}
+
 // Eviction happens in two steps so that, on a miss, the load of the requested
 // model and its forward pass can be enqueued before the (latency-insensitive)
 // offload of the victims: evict_logical() updates the bookkeeping and frees
@@ -273,30 +307,14 @@ int enqueue_offload(ctn_ctx* c, const Eviction& ev) {
     if (m->used[lane]) CTN_HIP(c, hipStreamWaitEvent(c->s_d2h, m->ev_last_use[lane], 0));
   CTN_HIP(c, hipEventRecord(m->ev_out_start, c->s_d2h));
   const ShardLayout& L = m->lay;
+  // offloads: the copy kernel only when asked for; otherwise DMA, per tensor or per run of adjacent tensors
+  const int how = c->cfg.transfer_mode == CTN_XFER_KERNEL ? kCopyKernel
+                  : c->cfg.transfer_mode == CTN_XFER_DMA ? kPerTensorDma : kPerRunDma;
   uint64_t bytes = 0;
   for (int b = ev.b0; b < ev.b1; ++b) {
-    char* base = arena + ev.off[b - ev.b0];
     bytes += L.block_bytes[b];
-    if (m->runs[b].empty()) continue;
-    if (c->cfg.transfer_mode == CTN_XFER_KERNEL) {
-      CopyTable t{};
-      for (const Model::Run& r : m->runs[b]) {
-        t.seg[t.n].src = base + L.offset_in_block(r.first);
-        t.seg[t.n].dst = m->host_dev[r.first];
-        t.seg[t.n].n16 = r.bytes / 16;
-        ++t.n;
-      }
-      if (!copy_table_finish(t)) return CTN_E_INVAL;
-      CTN_HIP(c, launch_copy_table(t, c->cfg.copy_blocks, c->s_d2h, kCopyD2H));
-    } else if (c->cfg.transfer_mode == CTN_XFER_DMA) {   // one message per tensor (Section 5.1)
-      for (int ti : L.block_tensors[b])
-        CTN_HIP(c, hipMemcpyAsync(m->host[ti], base + L.offset_in_block(ti), L.nbytes[ti], hipMemcpyDeviceToHost,
-                                  c->s_d2h));
-    } else {                                             // one message per run of adjacent tensors
-      for (const Model::Run& r : m->runs[b])
-        CTN_HIP(c, hipMemcpyAsync(m->host[r.first], base + L.offset_in_block(r.first), r.bytes,
-                                  hipMemcpyDeviceToHost, c->s_d2h));
-    }
+    const int rc = copy_block(c, m, b, arena + ev.off[b - ev.b0], false, how, c->s_d2h);
+    if (rc) return rc;
   }
   CTN_HIP(c, hipEventRecord(m->ev_out_done, c->s_d2h));
   m->out_recorded = true;
@@ -444,29 +462,10 @@ int ensure_resident(ctn_ctx* c, int mi) {
   const bool load_by_kernel = c->cfg.transfer_mode == CTN_XFER_KERNEL ||
                               (c->cfg.transfer_mode == CTN_XFER_AUTO && m->fragmented && !earlier_offload_running);
   CTN_HIP(c, hipEventRecord(m->ev_in_start, c->s_h2d));
+  const int how = load_by_kernel ? kCopyKernel : c->cfg.transfer_mode == CTN_XFER_DMA ? kPerTensorDma : kPerRunDma;
   for (int b = first; b < L.n_blocks; ++b) {
-    char* base = arena + m->block_off[b];
-    if (m->runs[b].empty()) {
-      // nothing to move
-    } else if (load_by_kernel) {
-      CopyTable t{};
-      for (const Model::Run& r : m->runs[b]) {
-        t.seg[t.n].src = m->host_dev[r.first];
-        t.seg[t.n].dst = base + L.offset_in_block(r.first);
-        t.seg[t.n].n16 = r.bytes / 16;
-        ++t.n;
-      }
-      if (!copy_table_finish(t)) return CTN_E_INVAL;
-      CTN_HIP(c, launch_copy_table(t, c->cfg.copy_blocks, c->s_h2d, kCopyH2D));
-    } else if (c->cfg.transfer_mode == CTN_XFER_DMA) {   // one message per tensor (Section 5.1)
-      for (int ti : L.block_tensors[b])
-        CTN_HIP(c, hipMemcpyAsync(base + L.offset_in_block(ti), m->host[ti], L.nbytes[ti], hipMemcpyHostToDevice,
-                                  c->s_h2d));
-    } else {                                             // one message per run of adjacent tensors
-      for (const Model::Run& r : m->runs[b])
-        CTN_HIP(c, hipMemcpyAsync(base + L.offset_in_block(r.first), m->host[r.first], r.bytes,
-                                  hipMemcpyHostToDevice, c->s_h2d));
-    }
+    rc = copy_block(c, m, b, arena + m->block_off[b], true, how, c->s_h2d);
+    if (rc) return rc;
     CTN_HIP(c, hipEventRecord(m->ev_block[b], c->s_h2d));
   }
   m->k = L.n_blocks;
