@@ -20,9 +20,10 @@ DESC = ShardDesc(4, 1024, 4096, 8, vocab=8192, max_pos=64)      # ~118 MB: a loa
 SEQ, MAXB = 8, 4
 
 
-def make(n_models, resident, **kw):
+def make(n_models, resident, extra_bytes=7, **kw):
     size = shard_bytes(DESC)
-    rig = Rig([DESC] * n_models, budget=resident * size + 7, arena_bytes=(resident + 1) * P.arena_bytes(DESC),
+    arena = None if kw.get("block_residency") else (resident + 1) * P.arena_bytes(DESC)
+    rig = Rig([DESC] * n_models, budget=resident * size + extra_bytes, arena_bytes=arena,
               max_tokens=MAXB * SEQ, mode=P.XFER_AUTO, two_lanes=True, **kw)
     eng = P.Engine(rig.ctx, MAXB, SEQ, two_lanes=True)
     ms = [rig.add(DESC, seed=160 + i) for i in range(n_models)]
@@ -76,10 +77,15 @@ def test_hit_is_dispatched_while_a_miss_is_in_flight():
         rig.close()
 
 
-def test_trace_every_request_once_in_order_and_right():
+@pytest.mark.parametrize("block_residency,ahead", [(False, False), (True, False), (True, True)])
+def test_trace_every_request_once_in_order_and_right(block_residency, ahead):
     from paper_2306_13835_amd.serving import serve_engine_async
-    rig, eng, ms, bufs = make(4, 2)
+    from oracle.partial_lru import PartialLruResidency
+    from gpu_util import block_bytes
+    extra = shard_bytes(DESC) // 2 if block_residency else 7       # per-block residency gets slack to keep prefixes in
+    rig, eng, ms, bufs = make(4, 2, extra_bytes=extra, block_residency=block_residency)
     try:
+        eng.set_prefetch(ahead, min_count=2, min_share_percent=40)
         orig = [[t.copy() for t in rig.tensors[m]] for m in ms]
         arr, mod = gamma_rates_trace((60, 30, 30, 10), 4.0, 1.5, seed=77)
         n = len(arr)
@@ -101,14 +107,26 @@ def test_trace_every_request_once_in_order_and_right():
             mine = [r for b in order for r in b[0] if b[1] == m]
             assert mine == sorted(mine)
         assert all(1 <= len(b[0]) <= MAXB and all(mod[r] == b[1] for r in b[0]) for b in order)
-        assert all(b[3] == (1 if b[2] else 0) for b in order)
+        assert all(b[3] == 1 for b in order if b[2])            # misses run on the load lane
+        if not ahead:
+            assert all(b[3] == (1 if b[2] else 0) for b in order)
         assert (lat > 0).all()
         # decisions = LRU on the order in which batches were dispatched (completion order may differ)
         events = rig.ctx.events()
-        ref = LruResidency(2 * shard_bytes(DESC) + 7, [shard_bytes(DESC)] * 4)
-        for kind, m, victims in events:
-            assert ref.touch(m) == (kind, m, victims)
-        assert sum(e[0] == "miss" for e in events) == sum(b[2] for b in order)
+        budget = 2 * shard_bytes(DESC) + extra
+        if block_residency:
+            ref = PartialLruResidency(budget, [block_bytes(DESC)] * 4)
+            for kind, m, victims in events:
+                k, mm, _, ev = ref.touch(m)
+                assert (k, mm, tuple(v for v, _, _ in ev)) == (kind, m, victims)
+            assert rig.ctx.stats()["n_extra_evictions"] == 0
+        else:
+            ref = LruResidency(budget, [shard_bytes(DESC)] * 4)
+            for kind, m, victims in events:
+                assert ref.touch(m) == (kind, m, victims)
+        if not ahead:          # a load started ahead is a use (and a miss) without a batch
+            assert sum(e[0] == "miss" for e in events) == sum(b[2] for b in order)
+        assert rig.ctx.stats()["resident_bytes"] <= budget
         for m in ms:
             for t, o in zip(rig.tensors[m], orig[m]):
                 assert np.array_equal(as_bytes(t), as_bytes(o))
