@@ -268,3 +268,27 @@ def test_serving_shapes_full_size_decisions_logits_determinism(block_residency):
             assert_close(first[m], want, f"serving model {m}")
     finally:
         rig.close()
+
+
+def test_degenerate_shapes_no_layers_single_token():
+    """A model without decoder layers (embeddings, final LayerNorm and head only) and a one-token request:
+    the smallest things the path can be asked for; empty batches are refused."""
+    rows = []
+    for desc in (ShardDesc(0, 128, 512, 2, vocab=512, max_pos=8), ShardDesc(1, 128, 512, 2, vocab=512, max_pos=8, tp=2, rank=1)):
+        rig = Rig([desc], max_tokens=8)
+        try:
+            m = rig.add(desc, seed=170 + desc.layers)
+            assert len(rig.tensors[m]) == 16 * desc.layers + 4
+            for batch, seq in ((1, 1), (2, 3)):
+                ids = token_ids(175, batch, seq, desc.vocab)
+                got = rig.ctx.infer(m, ids)
+                want = O.forward(rig.tensors[m], ids, layers=desc.layers, heads=desc.heads, tp=desc.tp, rank=desc.rank,
+                                 dtype=np.float32)
+                assert_close(got, want, f"layers={desc.layers} {batch}x{seq}")
+                rows.append(got.shape)
+            assert P.lib().ctn_infer(rig.ctx.h, m, ids.ctypes.data, 0, 3, got.ctypes.data, 0) == -6   # empty batch
+            rig.ctx.swap_out(m); rig.ctx.wait(m)
+            assert rig.ctx.resident_blocks(m) == (0, desc.layers + 1)
+        finally:
+            rig.close()
+    assert rows == [(1, 1, 512), (2, 3, 512), (1, 1, 256), (2, 3, 256)]
