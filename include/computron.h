@@ -393,7 +393,7 @@ int ctn_op_gemm(const void* A_f16, const void* W_f16, const void* bias_f16, void
 int ctn_op_gemm_ws(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,
                    int32_t N, int32_t K, int32_t epilogue, void* workspace, uint64_t workspace_bytes,
                    void* stream);
-/* Test and tuning hook, process wide: forces tile configuration cfg (0..15; 9 and 10 = the streaming kernels for M <= 64, ignored for larger M; 14 and 15 = split-K
+/* Test and tuning hook, process wide: forces tile configuration cfg (0..16; 9 and 10 = the streaming kernels for M <= 64, ignored for larger M; 16 = the row-contiguous streaming kernel for M <= 16, ignored for larger M; 14 and 15 = split-K
  * over 64x64 / 32x128 tiles where a workspace is given) on every product of
  * ctn_op_gemm and ctn_infer; -1 restores the library's choice.  CTN_E_INVAL outside that range. */
 int ctn_debug_gemm_tile(int32_t cfg);

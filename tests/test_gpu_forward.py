@@ -37,6 +37,8 @@ TINY = [
     (ShardDesc(3, 256, 1024, 4, vocab=1000, max_pos=300, tp=2, rank=1), 3, 37),
     (ShardDesc(2, 512, 2048, 4, vocab=1024, max_pos=300, tp=4, rank=2), 2, 130),   # head size 128, ragged tiles
     (ShardDesc(2, 640, 2560, 10, vocab=1000, max_pos=300), 1, 264),
+    # hidden 4096: the small-request products with long rows (row-contiguous streaming kernel), q|k|v in one launch
+    (ShardDesc(1, 4096, 1024, 32, vocab=512, max_pos=40, tp=2, rank=1), 1, 8),
 ]
 
 

@@ -81,7 +81,7 @@ def test_layernorm(stream, rows, hidden):
     assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.maximum(np.abs(want), 2.0 ** -14) + 1e-6)
 
 
-GEMM_SHAPES = [(8, 2304, 768), (1, 128, 64), (33, 200, 72), (16, 50, 40), (17, 4096, 2048), (48, 33, 8192), (49, 640, 264), (64, 6144, 4096), (130, 257, 136),
+GEMM_SHAPES = [(8, 520, 4104), (16, 77, 5120), (3, 4096, 8192), (1, 33, 4096), (8, 2304, 768), (1, 128, 64), (33, 200, 72), (16, 50, 40), (17, 4096, 2048), (48, 33, 8192), (49, 640, 264), (64, 6144, 4096), (130, 257, 136),
                (1024, 4096, 2048), (300, 50272 // 4, 512), (2048, 1280, 5120)]
 
 
@@ -137,7 +137,7 @@ def test_attention(stream, batch, seq, heads, d):
     assert np.abs(got - want).mean() <= 4e-4 * np.abs(want).mean() + 1e-5
 
 
-@pytest.mark.parametrize("cfg", range(16))
+@pytest.mark.parametrize("cfg", range(17))
 @pytest.mark.parametrize("M,N,K,epi", [(300, 520, 328, P.EPI_BIAS_RESID_F32), (257, 129, 64, P.EPI_BIAS_RELU_F16),
                                        (61, 200, 1096, P.EPI_BIAS_F16), (9, 77, 40, P.EPI_F32)])
 def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
@@ -164,7 +164,7 @@ def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
     tol = 2.0 ** -10 * np.abs(want) + 1e-4 if out.dtype == torch.float16 else 1e-4
     assert np.all(np.abs(got - want) <= tol)
     with pytest.raises(P.CtnError):
-        B.debug_gemm_tile(16)
+        B.debug_gemm_tile(17)
 
 
 @pytest.mark.parametrize("M,N,K", [(64, 4096, 8192), (64, 520, 1096), (17, 6144, 4096), (33, 200, 264), (48, 8192, 512)])
