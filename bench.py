@@ -420,6 +420,8 @@ def main():
                     help="serve workload: residency per transfer block instead of per model")
     ap.add_argument("--two-lane", action="store_true",
                     help="serve / grid workloads: the asynchronous engine (batches of loaded models go on while another loads)")
+    ap.add_argument("--load-ahead", action="store_true",
+                    help="serve workload with --two-lane: let the idle engine load the predicted next model")
     ap.add_argument("--copy-blocks", type=int, default=0, help="workgroups per copy kernel (0: library default)")
     ap.add_argument("--copy-cus", type=int, default=0, help="compute units reserved per transfer direction")
     args = ap.parse_args()

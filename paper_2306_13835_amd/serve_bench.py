@@ -82,6 +82,8 @@ def run_serve(args):
         # the asynchronous engine of Section 3.2 (batch size 1 as in this workload): hits go on while a model loads
         from paper_2306_13835_amd.serving import serve_engine_async
         eng = P.Engine(ctx, batch, seq, two_lanes=True)
+        if getattr(args, "load_ahead", False):
+            eng.set_prefetch(True, min_count=3, min_share_percent=60)
         miss = np.zeros(n_req, dtype=bool)
         count = [0]
 
@@ -140,6 +142,7 @@ def run_serve(args):
                                + ", LRU",
                    "transfer": args.transfer, "host_layout": args.host_layout,
                    "residency": "per transfer block (prefix kept)" if blocks else "whole models (2 resident)",
+                   "load_ahead": bool(getattr(args, "load_ahead", False)),
                    "arena_bytes": int(arena.numel()), "arena_note": "budget + one transit range"},
         "latency_s": {"mean": round(float(lat.mean()), 4), "p50": round(float(np.percentile(lat, 50)), 4),
                       "p90": round(float(np.percentile(lat, 90)), 4), "p99": round(float(np.percentile(lat, 99)), 4),
@@ -152,6 +155,7 @@ def run_serve(args):
                        "partial_miss_blocks_p50": float(np.median(missing[part_miss])) if part_miss.any() else None},
         "misses": int(n_miss), "hit_ratio": round(1 - n_miss / n_req, 4),
         "partial_misses": st["n_partial_miss"] - st0["n_partial_miss"],
+        "loads_ahead": st["n_prefetch"] - st0["n_prefetch"],
         "extra_evictions": st["n_extra_evictions"] - st0["n_extra_evictions"],
         "bytes_swapped_in": st["bytes_h2d"] - st0["bytes_h2d"], "trace_seconds": round(float(arr[-1]), 2),
         "wall_seconds": round(wall, 2), "peak_resident_bytes": st["peak_resident_bytes"],
