@@ -21,6 +21,9 @@
  *     workspace and the streams belong to the caller and must outlive the
  *     context.  It owns only host-side descriptors and its events.
  *   - A context is not thread safe; use one host thread per context.
+ *   - An engine borrows its context: destroy engines before their context.
+ *     "streams ... belong to the caller" applies when the caller passes
+ *     streams; with none given the library creates and owns its streams.
  */
 #ifndef COMPUTRON_H
 #define COMPUTRON_H
