@@ -222,6 +222,14 @@ def run_swap(args):
     ctx.swap_out(models[0]); ctx.wait(models[0])
     ctx.sync()
 
+    # the same alternation if evictions only freed the device copy (parameters are read-only on the device);
+    # an option, off by default: the paper's swap-out is a real copy and so is the timed region's
+    ctx.set_mode(MODES[args.transfer], True, args.copy_blocks)
+    ctx.set_discard(True)
+    w_disc, _ = alternate(models, 4, 2)
+    ctx.set_discard(False)
+    side["discard_ms_per_step"] = w_disc / 4 * 1e3
+
     # the same alternation on the other host layout, for the report
     ctx.set_mode(MODES[args.transfer], True, args.copy_blocks)
     w_other, lat_other = alternate(models_other, 4, 2)
@@ -324,6 +332,9 @@ def run_swap(args):
             "frac": round(gemm_tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None,
             "avg_launch_ms": round(gms, 4), "launches_timed": reps,
         },
+        "without_copy_back": {"note": "option discard_on_evict (not the paper's swap-out, not the timed region): "
+                                      "evictions free the device copy only", "ms_per_step": round(side["discard_ms_per_step"], 3),
+                              "value_gbps": round(nbytes / side["discard_ms_per_step"] / 1e6, 3)},
         "other_host_layout": {
             "layout": "packed" if args.host_layout == "separate" else "separate",
             "ms_per_step": round(side["other_layout_ms_per_step"], 3),

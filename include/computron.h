@@ -112,7 +112,11 @@ typedef struct {
                                 recently used model, and a later use of that model reloads just the
                                 missing tail while its forward pass starts on the prefix.  Every
                                 block then occupies one slot of ctn_slot_bytes() in the arena. */
-  int32_t reserved;
+  int32_t discard_on_evict;  /* 0 (default, the paper's behaviour): an evicted model is copied back into
+                                its host tensors (Section 3.2: offload entries).  1: inference never
+                                writes parameters, so eviction only frees the device copy and the host
+                                tensors, which the caller must then leave unchanged while the model is
+                                registered, stay the single source; nothing crosses the link on swap-out. */
 } ctn_config;
 
 typedef struct {
@@ -255,6 +259,8 @@ int ctn_get_streams(ctn_ctx* ctx, void** compute, void** h2d, void** d2h);
  * models while the link is idle; 0 (the default: replay measured no faster than direct launches
  * on ROCm 7.2) launches every kernel directly. */
 int ctn_set_graphs(ctn_ctx* ctx, int32_t enable);
+/* Switches ctn_config.discard_on_evict between operations (evictions already decided keep their mode). */
+int ctn_set_discard(ctn_ctx* ctx, int32_t enable);
 /* Changes transfer mode / pipelining / copy-kernel width between operations. */
 int ctn_set_mode(ctn_ctx* ctx, int32_t transfer_mode, int32_t pipeline, int32_t copy_blocks);
 /* HIP status behind the last CTN_E_HIP of this context (ctx == NULL: of calls that take no context). */

@@ -35,6 +35,7 @@ struct PendingRelease {   // arena range given back by an eviction whose offload
 struct Eviction {         // blocks [b0, b1) of a model: decided, arena given back, not yet copied to the host
   int model, b0, b1;
   std::vector<uint64_t> off;   // arena offset of each of those blocks
+  bool discard = false;        // no copy back: only the ordering against the last readers is enqueued
 };
 
 struct Model {
@@ -280,6 +281,7 @@ void evict_logical(ctn_ctx* c, const Residency::Move& mv) {
     c->arena.release(run_off, run_len);
     c->pending.push_back({run_off, run_len, m->ev_out_done, mv.model});
   };
+  ev.discard = c->cfg.discard_on_evict != 0;
   for (int b = mv.b0; b < mv.b1; ++b) {
     const uint64_t off = m->block_off[b], len = block_footprint(c, m->lay, b);
     ev.off.push_back(off);
@@ -311,7 +313,9 @@ int enqueue_offload(ctn_ctx* c, const Eviction& ev) {
   const int how = c->cfg.transfer_mode == CTN_XFER_KERNEL ? kCopyKernel
                   : c->cfg.transfer_mode == CTN_XFER_DMA ? kPerTensorDma : kPerRunDma;
   uint64_t bytes = 0;
-  for (int b = ev.b0; b < ev.b1; ++b) {
+  // (a discarded device copy moves nothing; the stream waits above and the event below still
+  // order the reuse of its blocks after the load and the inferences that were using them)
+  for (int b = ev.b0; b < ev.b1 && !ev.discard; ++b) {
     bytes += L.block_bytes[b];
     const int rc = copy_block(c, m, b, arena + ev.off[b - ev.b0], false, how, c->s_d2h);
     if (rc) return rc;
@@ -649,6 +653,7 @@ int ctn_create(const ctn_config* cfg, ctn_ctx** out) {
   if (cfg->hbm_budget_bytes == 0 || cfg->arena_bytes == 0) return CTN_E_INVAL;
   if (cfg->transfer_mode < CTN_XFER_DMA || cfg->transfer_mode > CTN_XFER_AUTO) return CTN_E_INVAL;
   if (cfg->block_residency != 0 && cfg->block_residency != 1) return CTN_E_INVAL;
+  if (cfg->discard_on_evict != 0 && cfg->discard_on_evict != 1) return CTN_E_INVAL;
   if (!own_streams && (cfg->stream_h2d == cfg->stream_compute || cfg->stream_d2h == cfg->stream_compute ||
                        cfg->stream_h2d == cfg->stream_d2h))
     return CTN_E_INVAL;
@@ -1030,6 +1035,12 @@ int ctn_get_streams(ctn_ctx* c, void** compute, void** h2d, void** d2h) {
 int ctn_set_graphs(ctn_ctx* c, int32_t enable) {
   if (!c) return CTN_E_INVAL;
   c->use_graphs = enable && c->s_wide != nullptr;
+  return CTN_OK;
+}
+
+int ctn_set_discard(ctn_ctx* c, int32_t enable) {
+  if (!c || (enable != 0 && enable != 1)) return CTN_E_INVAL;
+  c->cfg.discard_on_evict = enable;
   return CTN_OK;
 }
 

@@ -295,3 +295,44 @@ def test_engine_loads_ahead_on_a_cyclic_stream():
     finally:
         eng.close()
         rig.close()
+
+
+def test_eviction_without_the_copy_back_is_opt_in_and_moves_nothing():
+    """discard_on_evict: eviction frees the device copy only.  The host tensors are neither written nor
+    needed to be; the default (off) is pinned by the overwrite tests above."""
+    from oracle import opt_shard as O
+    from synth import token_ids
+    desc = ShardDesc(2, 256, 1024, 4, vocab=1000, max_pos=64)
+    size = shard_bytes(desc)
+    rig = Rig([desc] * 3, budget=2 * size, arena_bytes=3 * P.arena_bytes(desc), max_tokens=16, mode=P.XFER_AUTO)
+    try:
+        ms = [rig.add(desc, seed=180 + i) for i in range(3)]
+        orig = [[t.copy() for t in rig.tensors[m]] for m in ms]
+        rig.ctx.set_discard(True)
+        rig.ctx.swap_in(ms[0]); rig.ctx.wait(ms[0])
+        marker = rig.tensors[ms[0]][4].copy()
+        rig.tensors[ms[0]][4][...] = 0                  # what the host holds now is what a reload must bring
+        rig.ctx.swap_out(ms[0]); rig.ctx.wait(ms[0])
+        assert not rig.tensors[ms[0]][4].any()          # nothing was copied back
+        assert rig.ctx.stats()["bytes_d2h"] == 0 and not rig.ctx.is_resident(ms[0])
+        rig.ctx.swap_in(ms[0]); rig.ctx.wait(ms[0])
+        assert not rig.ctx.debug_read_param(ms[0], 4).any()
+        rig.tensors[ms[0]][4][...] = marker
+        rig.ctx.swap_out(ms[0]); rig.ctx.sync()
+        ids = [token_ids(185 + i, 2, 8, desc.vocab) for i in range(3)]
+        want = [O.forward(rig.tensors[m], ids[m], layers=desc.layers, heads=desc.heads) for m in ms]
+        for m in (0, 1, 2, 0, 2, 1, 1, 0, 2):
+            got = rig.ctx.infer(ms[m], ids[m])
+            assert np.abs(got - want[m]).max() <= 2e-2
+        rig.ctx.sync()
+        st = rig.ctx.stats()
+        assert st["bytes_d2h"] == 0 and st["n_miss"] >= 7
+        rig.ctx.set_discard(False)                      # back to the paper's behaviour: a real copy
+        rig.tensors[ms[2]][5][...] = 0
+        rig.ctx.swap_out(ms[2]); rig.ctx.wait(ms[2])
+        assert rig.ctx.stats()["bytes_d2h"] == size
+        for m in ms:
+            for t, o in zip(rig.tensors[m], orig[m]):
+                assert np.array_equal(as_bytes(t), as_bytes(o))
+    finally:
+        rig.close()
