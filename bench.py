@@ -418,7 +418,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", choices=["swap", "serve", "grid", "cyclic", "scaling", "counters"], default="swap")
+    ap.add_argument("--workload", choices=["swap", "serve", "grid", "cyclic", "scaling", "mixed", "counters"], default="swap")
     ap.add_argument("--config", default="opt6.7b_tp2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--duration", type=float, default=30.0, help="grid workload: seconds of arrivals per trial")
@@ -456,6 +456,9 @@ def main():
     elif args.workload == "scaling":
         from paper_2306_13835_amd.serve_bench import run_scaling
         run_scaling(args)
+    elif args.workload == "mixed":
+        from paper_2306_13835_amd.serve_bench import run_mixed
+        run_mixed(args)
     else:
         run_swap(args)
 

@@ -403,9 +403,15 @@ int ensure_resident(ctn_ctx* c, int mi) {
   // Prefer holes no offload is reading, so load and offload overlap on the
   // two link directions (Section 3.2 / 5.1); otherwise the load waits.
   std::vector<RangeAllocator::Range> placed;    // arena ranges this load writes
-  auto undo = [&]() {
-    for (const RangeAllocator::Range& r : placed) c->arena.release(r.off, r.len);
-  };
+  struct GiveBack {                             // every early return below hands them back to the arena
+    RangeAllocator& arena;
+    const std::vector<RangeAllocator::Range>& ranges;
+    bool keep = false;
+    ~GiveBack() {
+      if (!keep)
+        for (const RangeAllocator::Range& r : ranges) arena.release(r.off, r.len);
+    }
+  } give_back{c->arena, placed};
   if (!by_block) {
     uint64_t off = c->arena.alloc_avoiding(L.arena_bytes, busy_ranges());
     while (off == UINT64_MAX) {
@@ -425,10 +431,7 @@ int ensure_resident(ctn_ctx* c, int mi) {
       for (int b = first; b < L.n_blocks; ++b) {
         uint64_t off = c->arena.alloc_avoiding(L.slot_bytes, busy_ranges());
         while (off == UINT64_MAX) {
-          if (!evict_for_room()) {
-            undo();
-            return CTN_E_BUSY;
-          }
+          if (!evict_for_room()) return CTN_E_BUSY;
           off = c->arena.alloc_avoiding(L.slot_bytes, busy_ranges());
         }
         placed.push_back({off, L.slot_bytes});
@@ -447,10 +450,7 @@ int ensure_resident(ctn_ctx* c, int mi) {
     if (overlaps_load(p) && !c->models[p.model]->offload_enqueued) reuses_victim_range = true;
   if (reuses_victim_range) {     // the completion events the load must wait on have to exist first
     rc = flush_deferred(c);
-    if (rc) {
-      undo();
-      return rc;
-    }
+    if (rc) return rc;
   }
   for (const PendingRelease& p : c->pending)
     if (overlaps_load(p)) CTN_HIP(c, hipStreamWaitEvent(c->s_h2d, p.done, 0));
@@ -472,6 +472,7 @@ int ensure_resident(ctn_ctx* c, int mi) {
     if (rc) return rc;
     CTN_HIP(c, hipEventRecord(m->ev_block[b], c->s_h2d));
   }
+  give_back.keep = true;
   m->k = L.n_blocks;
   m->last_load_first = first;
   m->load_recorded = true;

@@ -315,6 +315,96 @@ def run_cyclic(args):
     print(json.dumps(res), flush=True)
 
 
+def run_mixed(args):
+    """Shards of two sizes under one byte budget (the paper's closing section names heterogeneous model
+    sizes as open; its own runs use one size): three opt6.7b/TP2 shards and five opt1.3b shards, 20e9 B,
+    the serving trace's arrival process.  The residency decisions must be those of the byte-budget LRU
+    policy on the same trace; evictions forced by arena fragmentation (none of the policy's) are counted."""
+    import torch
+    import paper_2306_13835_amd as P
+    from paper_2306_13835_amd.serving import serve_trace
+    from synth import CONFIGS, fill_shard, token_ids, shard_bytes, param_list, gamma_zipf_trace
+
+    torch.cuda.set_device(0)
+    torch.zeros(1, device="cuda")
+    big, small = CONFIGS["opt6.7b_tp2"]["desc"], CONFIGS["opt1.3b_tp1"]["desc"]
+    c = CONFIGS["serve8x6.7b_tp2"]
+    kinds = [big, small, small, big, small, small, big, small]      # by popularity rank: sizes interleaved
+    n_models, batch, seq, budget = len(kinds), 1, 64, c["budget"]
+    n_req = args.requests or 1000
+    sizes = [shard_bytes(d) for d in kinds]
+    gap = 4096 if args.host_layout == "separate" else 0
+    pool = P.HostPool(sum(sz + len(param_list(d)) * (256 + gap) for sz, d in zip(sizes, kinds)) + 8192)
+    # room for the budget's worth of shards plus one large shard in transit
+    arena = torch.empty(4 * P.arena_bytes(big), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(P.workspace_bytes(d, batch * seq) for d in (big, small)) + 512, dtype=torch.uint8, device="cuda")
+    logits = torch.empty(batch * seq * max(d.vocab // d.tp for d in (big, small)), dtype=torch.float32, device="cuda")
+    ctx = P.Context(budget, arena, ws, transfer_mode={"dma": 0, "kernel": 1, "auto": 2}[args.transfer], pipeline=True)
+    t0 = time.time()
+    keep = [fill_shard(d, 70 + k, alloc=lambda sh: pool.take(sh, gap=gap), threads=16) for k, d in enumerate(kinds)]
+    models = [ctx.register_model(d, t) for d, t in zip(kinds, keep)]
+    log(f"[mixed] {n_models} shards ({sum(sizes) / 1e9:.1f} GB pinned) ready in {time.time() - t0:.1f}s")
+    arr, mod = gamma_zipf_trace(n_models, c["rate"], c["cv"], c["zipf"], n_req, 510)
+    ids = [token_ids(4000 + i, batch, seq, big.vocab) for i in range(n_req)]
+    for k in (0, 1, 0, 1):                     # unrecorded warm-up: a hit and a miss of each size
+        ctx.infer(models[k], ids[0], out=logits)
+    ctx.sync()
+    for m in models:
+        ctx.swap_out(m)
+    ctx.sync()
+    ev0, st0 = len(ctx.events()), ctx.stats()
+    last = [time.time()]
+
+    def progress(i):
+        if time.time() - last[0] > 20:
+            last[0] = time.time()
+            log(f"[mixed] request {i + 1}/{n_req}")
+
+    t0 = time.perf_counter()
+    lat, svc, miss = serve_trace(ctx, models, arr, mod, lambda i: ids[i], logits, progress=progress)
+    wall = time.perf_counter() - t0
+    ctx.sync()
+    st = ctx.stats()
+    events = [(e[0], e[1], e[2]) for e in ctx.events()[ev0:]]
+    replay = P.residency_replay(budget, sizes, [int(x) for x in mod])
+    extra = st["n_extra_evictions"] - st0["n_extra_evictions"]
+    is_big = np.array([kinds[int(m)] is big for m in mod])
+
+    def cls(sel, nbytes):
+        hit, ms = sel & ~miss, sel & miss
+        hit_ms = float(np.median(svc[hit]) * 1e3) if hit.any() else None
+        miss_ms = float(np.median(svc[ms]) * 1e3) if ms.any() else None
+        return {"requests": int(sel.sum()), "misses": int(ms.sum()),
+                "mean_latency_s": round(float(lat[sel].mean()), 4), "p99_latency_s": round(float(np.percentile(lat[sel], 99)), 4),
+                "hit_ms_p50": round(hit_ms, 3) if hit_ms is not None else None,
+                "miss_ms_p50": round(miss_ms, 3) if miss_ms is not None else None,
+                "miss_gbps_p50": round(nbytes / miss_ms / 1e6, 2) if miss_ms else None}
+
+    n_miss = st["n_miss"] - st0["n_miss"]
+    res = {"metric": "p99 request latency under swap, shards of two sizes under one byte budget",
+           "value": round(float(np.percentile(lat, 99)), 4), "unit": "s", "n_gpus": 1, "steps": n_req, "warmup": 4,
+           "ms_per_step": round(wall / n_req * 1e3, 3), "higher_is_better": False, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+           "config": {"workload": f"3 x opt6.7b_tp2 ({sizes[0]} B) + 5 x opt1.3b ({sizes[1]} B) shards, budget {budget} B, "
+                                  f"{n_req} requests batch {batch} x seq {seq}, Gamma CV=4 / Zipf 1.5 arrivals, "
+                                  "serial oldest-first engine, whole-model LRU by bytes",
+                      "sizes_by_popularity": ["6.7b/2" if d is big else "1.3b" for d in kinds],
+                      "transfer": args.transfer, "host_layout": args.host_layout, "arena_bytes": int(arena.numel())},
+           "latency_s": {"mean": round(float(lat.mean()), 4), "p50": round(float(np.percentile(lat, 50)), 4),
+                         "p99": round(float(np.percentile(lat, 99)), 4), "max": round(float(lat.max()), 4)},
+           "large": cls(is_big, sizes[0]), "small": cls(~is_big, sizes[1]),
+           "misses": int(n_miss), "hit_ratio": round(1 - n_miss / n_req, 4),
+           "bytes_swapped_in": st["bytes_h2d"] - st0["bytes_h2d"],
+           "peak_resident_bytes": st["peak_resident_bytes"], "extra_evictions_for_arena_room": int(extra),
+           "decisions_equal_policy_replay": bool(events == replay),
+           "hits_and_misses_equal_policy_replay": bool([e[:2] for e in events] == [e[:2] for e in replay]),
+           "trace_seconds": round(float(arr[-1]), 2), "wall_seconds": round(wall, 2)}
+    ctx.close()
+    del keep
+    pool.close()
+    print(json.dumps(res), flush=True)
+
+
 SPLITS = [(1, 1), (2, 1), (4, 1), (1, 2), (1, 4), (2, 2)]     # (TP, PP) of the paper's Section 5.1 sweeps
 
 
