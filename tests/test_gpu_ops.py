@@ -137,9 +137,10 @@ def test_attention(stream, batch, seq, heads, d):
     assert np.abs(got - want).mean() <= 4e-4 * np.abs(want).mean() + 1e-5
 
 
-@pytest.mark.parametrize("cfg", range(17))
+@pytest.mark.parametrize("cfg", range(18))
 @pytest.mark.parametrize("M,N,K,epi", [(300, 520, 328, P.EPI_BIAS_RESID_F32), (257, 129, 64, P.EPI_BIAS_RELU_F16),
-                                       (61, 200, 1096, P.EPI_BIAS_F16), (9, 77, 40, P.EPI_F32)])
+                                       (61, 200, 1096, P.EPI_BIAS_F16), (9, 77, 40, P.EPI_F32),
+                                       (300, 520, 320, P.EPI_BIAS_F16)])
 def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
     """Each tile shape the library can pick, forced through the tuning hook, on ragged sizes."""
     rng = np.random.default_rng(cfg * 1000 + M)
@@ -164,7 +165,50 @@ def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
     tol = 2.0 ** -10 * np.abs(want) + 1e-4 if out.dtype == torch.float16 else 1e-4
     assert np.all(np.abs(got - want) <= tol)
     with pytest.raises(P.CtnError):
-        B.debug_gemm_tile(17)
+        B.debug_gemm_tile(18)
+
+
+@pytest.mark.parametrize("M,N,K", [(1024, 2048, 512), (1000, 1100, 192), (129, 257, 64), (2048, 1280, 1280), (1024, 4096, 8192)])
+@pytest.mark.parametrize("epi", [P.EPI_BIAS_F16, P.EPI_BIAS_RELU_F16, P.EPI_BIAS_RESID_F32, P.EPI_F32])
+def test_gemm_direct_lds_fill_equals_register_staged(stream, M, N, K, epi):
+    """128x128x64 tiles filled straight from global memory into LDS (K a multiple of 64) against the same
+    tiles staged through registers: same K order, so the same bits; ragged edges, an odd number of K steps,
+    one-step products and (with the workspace, last shape) K slices included."""
+    rng = np.random.default_rng(M + 5 * N + K + epi)
+    A, W, bias = f16(rng, (M, K)), f16(rng, (N, K), 0.05), f16(rng, N, 0.5)
+    res = rng.standard_normal((M, N)).astype(np.float32)
+    dA, dW, db = dev(A), dev(W), dev(bias)
+    ws = torch.full((4 * M * N + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    outs = {}
+    try:
+        for cfg in (0, 17):
+            B.debug_gemm_tile(cfg)
+            out = dev(res) if epi in (P.EPI_BIAS_RESID_F32, P.EPI_F32) else torch.empty(M, N, dtype=torch.float16, device="cuda")
+            guard = torch.full((4096,), 7.0, dtype=torch.float32, device="cuda")
+            B.op_gemm(dA, dW, db, out, M, N, K, epi, stream)
+            stream.synchronize()
+            assert (guard == 7.0).all()
+            outs[cfg] = out.cpu().numpy()
+        B.debug_gemm_tile(-1)          # the library's own choice with a workspace (K slices at M = 1024, K = 8192)
+        for hook in (101, 100):
+            B.debug_gemm_tile(hook)
+            out = dev(res) if epi in (P.EPI_BIAS_RESID_F32, P.EPI_F32) else torch.empty(M, N, dtype=torch.float16, device="cuda")
+            B.op_gemm_ws(dA, dW, db, out, M, N, K, epi, ws, stream)
+            stream.synchronize()
+            outs[hook] = out.cpu().numpy()
+    finally:
+        B.debug_gemm_tile(101)
+        B.debug_gemm_tile(-1)
+    assert np.array_equal(outs[0], outs[17])
+    assert np.array_equal(outs[101], outs[100])
+    acc = A.astype(np.float64) @ W.astype(np.float64).T
+    want = {P.EPI_BIAS_F16: acc + bias.astype(np.float64), P.EPI_BIAS_RELU_F16: np.maximum(acc + bias.astype(np.float64), 0),
+            P.EPI_BIAS_RESID_F32: res + acc + bias.astype(np.float64), P.EPI_F32: acc}[epi]
+    got, scale = outs[0].astype(np.float64), np.sqrt(K) * 0.05
+    if outs[0].dtype == np.float16:
+        assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.abs(want) + 1e-4 * scale + 1e-7)
+    else:
+        assert np.abs(got - want).max() <= 2e-5 * scale * max(1.0, np.log2(K)) + 1e-6 * np.abs(want).max()
 
 
 @pytest.mark.parametrize("M,N,K", [(64, 4096, 8192), (64, 520, 1096), (17, 6144, 4096), (33, 200, 264), (48, 8192, 512)])
