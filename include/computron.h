@@ -405,8 +405,9 @@ int ctn_op_gemm_ws(const void* A_f16, const void* W_f16, const void* bias_f16, v
 /* Test and tuning hook, process wide: forces tile configuration cfg (0..17; 9 and 10 = the streaming kernels for M <= 64, ignored for larger M; 16 = the row-contiguous streaming kernel for M <= 16, ignored for larger M; 14 and 15 = split-K
  * over 64x64 / 32x128 tiles where a workspace is given; 0 = 128x128x64 tiles, filled straight from global memory into
  * LDS when K is a multiple of 64; 17 = the same tiles always staged through registers) on every product of
- * ctn_op_gemm and ctn_infer; -1 restores the library's choice.  100 / 101 switch the direct fills off / on
- * (default on) without forcing a tile.  CTN_E_INVAL for any other value. */
+ * ctn_op_gemm and ctn_infer; -1 restores the library's choice.  100 / 101 switch the direct fills off / on,
+ * 102 / 103 the register-staged tiles' second stage of loads in flight (both default on, where K is a multiple
+ * of the tile's K step; results do not change) without forcing a tile.  CTN_E_INVAL for any other value. */
 int ctn_debug_gemm_tile(int32_t cfg);
 /* Causal self-attention of every (batch, head): qkv fp16 [batch*seq, 3*heads*d]
  * holds q | k | v side by side; out fp16 [batch*seq, heads*d]

@@ -17,6 +17,8 @@
 //
 // Roofline: MFMA fp16 when M is a few hundred or more; HBM (W streamed once)
 // for M <= 64.  Algorithmic work 2*M*N*K flop, bytes 2*(M*K + N*K) + output.
+#include <type_traits>
+
 #include "computron.h"
 #include "kernels.h"
 
@@ -211,6 +213,146 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_nt_kernel_
   gemm_nt_body<BM, BN, BK, WM, WN, EPI>(g);
 }
 
+// ---- the same tiles with the global loads running two K steps ahead -----------------------------------------
+//
+// gemm_nt_body keeps one stage of global loads in flight and ends every step with a fenced barrier, which
+// (on this target) also waits for every outstanding vector memory operation.  Here the loads of step k + 2
+// are issued at the top of step k into a second register set and a raw s_barrier (after s_waitcnt lgkmcnt(0):
+// the stage stores are complete) ends the step, so two stages of operands are on their way while one is
+// multiplied.  Weights that come from HBM every time, as inside a forward pass, have about twice the latency of
+// the warm operands of a tuning loop; this is where the second stage pays (2048 x 5120 x 5376, weights rotating
+// through 8 copies: 156 against 183 us).  The step is branch free (loads past the end re-read the last step and
+// land in a stage nobody reads) so that the waits for the staged loads stay partial (vmcnt(n), n > 0), and
+// scheduling barriers keep the loads at the top of the step.  Same K order and epilogue: bit-equal results.
+// Needs K % BK == 0; rows past M or N re-read the last valid row and are not stored.
+__device__ __forceinline__ void stage_stores_done_barrier() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#endif
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int EPI>
+__device__ __forceinline__ void gemm_nt_deep_body(const GemmArgs& g) {
+  constexpr int THREADS = (BM / WM) * (BN / WN) * 64;
+  constexpr int LDS_ROW = BK + LDS_PAD;
+  constexpr int LPR = BK / 8, RPP = THREADS / LPR;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int PA = BM / RPP, PB = BN / RPP;
+  static_assert(BM % RPP == 0 && BN % RPP == 0, "cooperative load covers whole passes");
+
+  __shared__ __attribute__((aligned(16))) _Float16 As[2][BM][LDS_ROW];
+  __shared__ __attribute__((aligned(16))) _Float16 Bs[2][BN][LDS_ROW];
+
+  const int M = g.M, N = g.N, K = g.K;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n * g.parts * g.splits);
+  const int split = tile / (tiles_m * tiles_n * g.parts);
+  tile -= split * tiles_m * tiles_n * g.parts;
+  const int part = tile / (tiles_m * tiles_n);
+  tile -= part * tiles_m * tiles_n;
+  const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;
+  const _Float16* __restrict__ A = g.A;
+  const _Float16* __restrict__ W = part == 0 ? g.W[0] : (part == 1 ? g.W[1] : g.W[2]);
+  const _Float16* __restrict__ bias = part == 0 ? g.bias[0] : (part == 1 ? g.bias[1] : g.bias[2]);
+  const int ldc = g.ldc, col0 = part * N;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave % (BM / WM)) * WM, wn0 = (wave / (BM / WM)) * WN;
+  const int lrow = tid / LPR, lcol = (tid % LPR) * 8;
+
+  float16v acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const _Float16* pa[PA];
+  const _Float16* pb[PB];
+#pragma unroll
+  for (int p = 0; p < PA; ++p) {
+    const int r = m0 + p * RPP + lrow;
+    pa[p] = A + static_cast<int64_t>(r < M ? r : M - 1) * K + lcol;
+  }
+#pragma unroll
+  for (int p = 0; p < PB; ++p) {
+    const int r = n0 + p * RPP + lrow;
+    pb[p] = W + static_cast<int64_t>(r < N ? r : N - 1) * K + lcol;
+  }
+  u32x4 ra[2][PA], rb[2][PB];
+  auto load_global = [&](int set, int k0) {
+#pragma unroll
+    for (int p = 0; p < PA; ++p) ra[set][p] = *reinterpret_cast<const u32x4*>(pa[p] + k0);
+#pragma unroll
+    for (int p = 0; p < PB; ++p) rb[set][p] = *reinterpret_cast<const u32x4*>(pb[p] + k0);
+  };
+  auto store_lds = [&](int set, int buf) {
+#pragma unroll
+    for (int p = 0; p < PA; ++p) *reinterpret_cast<u32x4*>(&As[buf][p * RPP + lrow][lcol]) = ra[set][p];
+#pragma unroll
+    for (int p = 0; p < PB; ++p) *reinterpret_cast<u32x4*>(&Bs[buf][p * RPP + lrow][lcol]) = rb[set][p];
+  };
+
+  const int ksteps_all = K / BK;
+  const int kt_begin = static_cast<int>(static_cast<int64_t>(ksteps_all) * split / g.splits);
+  const int kt_end = static_cast<int>(static_cast<int64_t>(ksteps_all) * (split + 1) / g.splits);
+  const int ksteps = kt_end - kt_begin;
+  const int kbase = kt_begin * BK;
+  const int frow = lane & 31, fcol = (lane >> 5) * 8;
+
+  // One K step; `par` (its parity, compile time) names the stage multiplied and the register set refilled.
+  auto step = [&](int kt, auto par_c) {
+    constexpr int par = decltype(par_c)::value;
+    const int ahead = kt + 2 < ksteps ? kt + 2 : ksteps - 1;
+    load_global(par, kbase + ahead * BK);             // this set's previous content went to LDS one step ago
+    __builtin_amdgcn_sched_barrier(0);                // keep the loads up here, two steps ahead of their use
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      half8 af[TM], bf[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        af[i] = *reinterpret_cast<const half8*>(&As[par][wm0 + i * 32 + frow][ks * 16 + fcol]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        bf[j] = *reinterpret_cast<const half8*>(&Bs[par][wn0 + j * 32 + frow][ks * 16 + fcol]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    store_lds(par ^ 1, par ^ 1);                      // step kt + 1, loaded one step ago (past the end: unused)
+    stage_stores_done_barrier();
+  };
+
+  if (ksteps > 0) {
+    load_global(0, kbase);
+    store_lds(0, 0);
+    load_global(1, kbase + (ksteps > 1 ? BK : 0));
+    stage_stores_done_barrier();
+    int kt = 0;
+    for (; kt + 2 <= ksteps; kt += 2) {
+      step(kt, std::integral_constant<int, 0>{});
+      step(kt + 1, std::integral_constant<int, 1>{});
+    }
+    if (kt < ksteps) step(kt, std::integral_constant<int, 0>{});
+  }
+  store_tile<TM, TN, EPI>(g, acc, bias, g.out, m0 + wm0, n0 + wn0, col0, ldc, split, lane);
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int EPI>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_nt_deep_kernel(const GemmArgs g) {
+  gemm_nt_deep_body<BM, BN, BK, WM, WN, EPI>(g);
+}
+template <int BM, int BN, int BK, int WM, int WN, int EPI>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_nt_deep_kernel_occ2(const GemmArgs g) {
+  gemm_nt_deep_body<BM, BN, BK, WM, WN, EPI>(g);
+}
+
+bool g_deep_loads = true;   // tuning hook: loads two steps ahead where K is a multiple of the tile's K step
+
 template <int BM, int BN, int BK, int WM, int WN>
 hipError_t launch_tiles(const GemmArgs& g, int epi, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * g.parts * g.splits;
@@ -220,10 +362,18 @@ hipError_t launch_tiles(const GemmArgs& g, int epi, hipStream_t s) {
   constexpr int kWaves = (BM / WM) * (BN / WN);
   constexpr bool kOcc2 = WM * WN >= 64 * 64 && WM * WN <= 128 * 64 &&
                          ((kWaves == 4 && 4 * (BM + BN) * (BK + 8) <= 80 * 1024) || kWaves == 8);
+  // (128x128 per wavefront already fills the register file with accumulators: no room for a second set;
+  // the 8-wave tiles sit at their 128-register limit and measured 7 % slower with it)
+  const bool deep = g_deep_loads && g.K % BK == 0 && WM * WN < 128 * 128 && kWaves <= 4;
 #define CTN_GEMM(E)                                                                                  \
   do {                                                                                               \
-    if constexpr (kOcc2) hipLaunchKernelGGL((gemm_nt_kernel_occ2<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g); \
-    else hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g);          \
+    if constexpr (kOcc2) {                                                                           \
+      if (deep) hipLaunchKernelGGL((gemm_nt_deep_kernel_occ2<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g); \
+      else hipLaunchKernelGGL((gemm_nt_kernel_occ2<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g);   \
+    } else {                                                                                         \
+      if (deep) hipLaunchKernelGGL((gemm_nt_deep_kernel<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g); \
+      else hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WM, WN, E>), grid, block, 0, s, g);        \
+    }                                                                                                \
   } while (0)
   switch (epi) {
     case EPI_PARTIAL: CTN_GEMM(EPI_PARTIAL); break;
@@ -751,7 +901,10 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
   // (measured inside the forward pass, weights coming from HBM: this rule still holds with direct-to-LDS
   // fills in the 128x128x64 tile, whose advantage over the wide tile is confined to operands that are already
   // in the last-level cache)
-  if (173 * rounds_wide < 100 * rounds_narrow) return launch_config(13, g, epi, s);
+  // Where that comparison favoured the wide tile, the 128x128x64 tile with its loads two steps ahead now does
+  // a little better still inside the forward pass (13B shards: 22.5 -> 22.2 and 19.6 -> 19.4 ms).
+  if (173 * rounds_wide < 100 * rounds_narrow)
+    return launch_config(g_deep_loads && g.K % 64 == 0 ? 17 : 13, g, epi, s);
   return launch_config(0, g, epi, s);
 }
 
@@ -760,6 +913,10 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
 int gemm_force_tile(int cfg) {
   if (cfg == 100 || cfg == 101) {      // tuning hook: direct-to-LDS stage fills off / on
     g_direct_fill = cfg == 101;
+    return 0;
+  }
+  if (cfg == 102 || cfg == 103) {      // tuning hook: global loads two steps ahead off / on
+    g_deep_loads = cfg == 103;
     return 0;
   }
   if (cfg < -1 || cfg > 17) return -1;

@@ -168,6 +168,45 @@ def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
         B.debug_gemm_tile(18)
 
 
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5, 6, 7, 11, 12, 13, 14, 15, 17])
+@pytest.mark.parametrize("M,N,K,epi", [(300, 520, 320, P.EPI_BIAS_RESID_F32), (257, 129, 64, P.EPI_BIAS_RELU_F16),
+                                       (640, 1100, 1088, P.EPI_BIAS_F16), (64, 264, 2048, P.EPI_F32)])
+def test_gemm_loads_two_steps_ahead_change_nothing(stream, cfg, M, N, K, epi):
+    """The register-staged tiles with a second stage of global loads in flight (K a multiple of the tile's
+    K step: one, two, five, seventeen steps; ragged edges; K slices with the workspace) against the plain loop:
+    same K order, so the same bits."""
+    rng = np.random.default_rng(cfg * 77 + M + K)
+    A, W, bias = f16(rng, (M, K)), f16(rng, (N, K), 0.05), f16(rng, N, 0.5)
+    res = rng.standard_normal((M, N)).astype(np.float32)
+    dA, dW, db = dev(A), dev(W), dev(bias)
+    ws = torch.full((16 * M * N + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    outs = {}
+    try:
+        B.debug_gemm_tile(100)                       # (direct fills off, so that configuration 0 is register staged too)
+        B.debug_gemm_tile(cfg)
+        for hook in (103, 102):
+            B.debug_gemm_tile(hook)
+            out = dev(res) if epi in (P.EPI_BIAS_RESID_F32, P.EPI_F32) else torch.empty(M, N, dtype=torch.float16, device="cuda")
+            guard = torch.full((4096,), 7.0, dtype=torch.float32, device="cuda")
+            B.op_gemm_ws(dA, dW, db, out, M, N, K, epi, ws, stream)
+            stream.synchronize()
+            assert (guard == 7.0).all()
+            outs[hook] = out.cpu().numpy()
+    finally:
+        B.debug_gemm_tile(103)
+        B.debug_gemm_tile(101)
+        B.debug_gemm_tile(-1)
+    assert np.array_equal(outs[103], outs[102])
+    acc = A.astype(np.float64) @ W.astype(np.float64).T
+    want = {P.EPI_BIAS_F16: acc + bias.astype(np.float64), P.EPI_BIAS_RELU_F16: np.maximum(acc + bias.astype(np.float64), 0),
+            P.EPI_BIAS_RESID_F32: res + acc + bias.astype(np.float64), P.EPI_F32: acc}[epi]
+    got, scale = outs[103].astype(np.float64), np.sqrt(K) * 0.05
+    if outs[103].dtype == np.float16:
+        assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.abs(want) + 1e-4 * scale + 1e-7)
+    else:
+        assert np.abs(got - want).max() <= 2e-5 * scale * max(1.0, np.log2(K)) + 1e-6 * np.abs(want).max()
+
+
 @pytest.mark.parametrize("M,N,K", [(1024, 2048, 512), (1000, 1100, 192), (129, 257, 64), (2048, 1280, 1280), (1024, 4096, 8192)])
 @pytest.mark.parametrize("epi", [P.EPI_BIAS_F16, P.EPI_BIAS_RELU_F16, P.EPI_BIAS_RESID_F32, P.EPI_F32])
 def test_gemm_direct_lds_fill_equals_register_staged(stream, M, N, K, epi):
