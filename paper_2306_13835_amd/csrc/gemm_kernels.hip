@@ -651,6 +651,7 @@ __global__ __launch_bounds__(SK_WAVES * 64) void gemm_skinny_kernel(const GemmAr
 // multiplies the window's K chunk w.  Measured with cold weights at M = 8: 15.1 us against 18.9 us
 // for a 67 MB matrix.  The 16 partial tiles are summed through LDS in wavefront order.
 constexpr int RS_WIN = 512, RS_ROW = RS_WIN + 8, RS_AHEAD = 2;
+static_assert(RS_AHEAD % 2 == 0, "the LDS stage alternates with the position inside a trip");
 template <int EPI>
 __global__ __launch_bounds__(SK_WAVES * 64) void gemm_rowstream_kernel(const GemmArgs g) {
   __shared__ __attribute__((aligned(16))) _Float16 wt[2][16][RS_ROW];
@@ -665,33 +666,53 @@ __global__ __launch_bounds__(SK_WAVES * 64) void gemm_rowstream_kernel(const Gem
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
   const bool row_ok = n0 + wave < N;
-  const _Float16* wrow = W + static_cast<int64_t>(row_ok ? n0 + wave : 0) * K + lane * 8;   // this lane's piece of each window
+  const _Float16* wrow = W + static_cast<int64_t>(row_ok ? n0 + wave : 0) * K;
+  const _Float16* arow = A + static_cast<int64_t>(r16 < M ? r16 : 0) * K;
   const int steps = (K + RS_WIN - 1) / RS_WIN;
-  auto load_w = [&](int p) {
-    half8 v = half8{0, 0, 0, 0, 0, 0, 0, 0};
-    if (row_ok && p < steps && p * RS_WIN + lane * 8 < K) v = *reinterpret_cast<const half8*>(wrow + static_cast<int64_t>(p) * RS_WIN);
-    return v;
+  // Loads are branch free (an address that is always valid, zeros selected afterwards where the window or the
+  // row does not exist) and the barrier is a raw one: a fenced barrier, or a branch around a load, makes the
+  // compiler wait for every outstanding load, and the windows that are meant to be in flight would not be.
+  // (the zeros are selected where a value is consumed, not where it is loaded: a select right behind the load
+  // would wait for it)
+  const half8 zero8 = half8{0, 0, 0, 0, 0, 0, 0, 0};
+  auto w_ok = [&](int p) { return row_ok && p * RS_WIN + lane * 8 < K; };   // (p >= steps implies false)
+  auto load_w = [&](int p) {                            // this lane's 16 bytes of window p of its wave's row
+    return *reinterpret_cast<const half8*>(wrow + (w_ok(p) ? p * RS_WIN + lane * 8 : 0));
   };
+  auto a_ok = [&](int p) { return r16 < M && p * RS_WIN + wave * 32 + kg * 8 < K; };
+  auto load_a = [&](int p) {                            // this lane's 8 activations of chunk `wave` of window p
+    return *reinterpret_cast<const half8*>(arow + (a_ok(p) ? p * RS_WIN + wave * 32 + kg * 8 : 0));
+  };
+  // Issue order matters: vector memory returns in order, so a load waited for takes everything older with it.
+  // Per window p the order is  A(p + 1), W(p + RS_AHEAD):  waiting for W(p) and then A(p) leaves the newer
+  // windows in flight.
+  // (the prologue issues in the order the loop leaves behind, W(0) .. W(RS_AHEAD - 2), A(0), W(RS_AHEAD - 1), so
+  // that the wait counts the compiler derives for the loop's entry and for its back edge agree)
   half8 wr[RS_AHEAD];
 #pragma unroll
-  for (int u = 0; u < RS_AHEAD; ++u) wr[u] = load_w(u);
+  for (int u = 0; u + 1 < RS_AHEAD; ++u) wr[u] = load_w(u);
+  __builtin_amdgcn_sched_barrier(0);
+  half8 a_cur = load_a(0);
+  __builtin_amdgcn_sched_barrier(0);
+  wr[RS_AHEAD - 1] = load_w(RS_AHEAD - 1);
+  __builtin_amdgcn_sched_barrier(0);
   float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
   for (int p0 = 0; p0 < steps; p0 += RS_AHEAD) {
 #pragma unroll
     for (int u = 0; u < RS_AHEAD; ++u) {
-      const int p = p0 + u;
-      if (p < steps) {                                  // uniform over the workgroup
-        const int buf = p & 1;
-        *reinterpret_cast<half8*>(&wt[buf][wave][lane * 8]) = wr[u];
-        wr[u] = load_w(p + RS_AHEAD);
-        const int k = p * RS_WIN + wave * 32 + kg * 8;  // this lane's 8 values of the window's chunk `wave`
-        half8 af = half8{0, 0, 0, 0, 0, 0, 0, 0};
-        if (r16 < M && k < K) af = *reinterpret_cast<const half8*>(A + static_cast<int64_t>(r16) * K + k);
-        // one barrier per window: the other buffer was last read before the previous barrier
-        __syncthreads();
-        const half8 bf = *reinterpret_cast<const half8*>(&wt[buf][r16][wave * 32 + kg * 8]);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc, 0, 0, 0);
-      }
+      const int p = p0 + u, buf = u & 1;               // (RS_AHEAD is even: the stage alternates with u)
+      // past the last window the same code runs on zeros: no branch, and zeros add nothing
+      *reinterpret_cast<half8*>(&wt[buf][wave][lane * 8]) = w_ok(p) ? wr[u] : zero8;
+      __builtin_amdgcn_sched_barrier(0);
+      const half8 a_next = load_a(p + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      wr[u] = load_w(p + RS_AHEAD);
+      __builtin_amdgcn_sched_barrier(0);
+      stage_stores_done_barrier();                      // one per window: the other stage was last read before the previous one
+      const half8 bf = *reinterpret_cast<const half8*>(&wt[buf][r16][wave * 32 + kg * 8]);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_ok(p) ? a_cur : zero8, bf, acc, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      a_cur = a_next;
     }
   }
   // accumulator layout of a 16x16 tile: lane holds column (lane % 16), rows 4*(lane/16) + e
