@@ -166,6 +166,9 @@ def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
     assert np.all(np.abs(got - want) <= tol)
     with pytest.raises(P.CtnError):
         B.debug_gemm_tile(18)
+    for bad in (-2, 99, 104):          # 100..103 are the fill / load-depth switches, nothing else is accepted
+        with pytest.raises(P.CtnError):
+            B.debug_gemm_tile(bad)
 
 
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5, 6, 7, 11, 12, 13, 14, 15, 17])
