@@ -924,8 +924,12 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
   // in the last-level cache)
   // Where that comparison favoured the wide tile, the 128x128x64 tile with its loads two steps ahead now does
   // a little better still inside the forward pass (13B shards: 22.5 -> 22.2 and 19.6 -> 19.4 ms).
-  if (173 * rounds_wide < 100 * rounds_narrow)
+  if (173 * rounds_wide < 100 * rounds_narrow) {
+    // a short K (the out-projection of a finely split shard: K = hidden / TP) has few steps per tile to hide
+    // a stage's latency behind; half-size steps do better (13B / TP4 forward 22.4 -> 21.9 ms)
+    if (g.K <= 2560) return launch_config(5, g, epi, s);
     return launch_config(g_deep_loads && g.K % 64 == 0 ? 17 : 13, g, epi, s);
+  }
   return launch_config(0, g, epi, s);
 }
 
