@@ -899,6 +899,12 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
     }
     return launch_skinny_any(g, epi, s, n_total >= 6144 ? 1 : 0);
   }
+  if (g.M <= 256 && g.partial && static_cast<int64_t>(g.N) * g.parts <= 16384) {
+    // A few requests batched (the paper's workloads: up to 32 requests of 8 tokens): still bound by streaming
+    // the weights once, so the same K-sliced 64x64 tiles as for 64 tokens, as long as slicing adds workgroups.
+    const int splits = choose_splits(g, 64, 64, partial_floats);
+    if (splits > 1) return launch_splitk(g, 6, splits, epi, s, defer);
+  }
   // Tile choice by how the tile count fills 256 CUs (two workgroups per CU for the big tiles):
   const int t0 = ((g.M + 127) / 128) * ((g.N + 127) / 128) * g.parts;
   if (g.partial && t0 <= 256 && g.K >= 4096) {

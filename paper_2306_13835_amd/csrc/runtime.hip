@@ -169,8 +169,10 @@ uint64_t activation_bytes(const ctn_model_desc& d, int64_t M, bool with_logits, 
                  o_log = with_logits ? take(4ull * M * vl) : 0;
   // up to 16 K-slices of the widest product that is ever split (not the vocabulary head)
   const uint64_t widest = std::max<uint64_t>(std::max<uint64_t>(3 * hl, fl), h);
-  // (larger batches split only the row-parallel products, N = hidden, in at most 4 slices)
-  const uint64_t partial_floats = M <= 64 ? 16ull * M * widest : 4ull * M * h;
+  // (larger batches split only the row-parallel products, N = hidden, in at most 4 slices).  Never less than a
+  // smaller batch needs: a workspace sized for max_tokens must serve every batch up to it.
+  const uint64_t small_m = M < 64 ? M : 64;
+  const uint64_t partial_floats = std::max<uint64_t>(16ull * small_m * widest, 4ull * M * h);
   const uint64_t o_part = partial_floats ? take(4ull * partial_floats) : 0;
   if (out && base) {
     out->ids = reinterpret_cast<int32_t*>(base + o_ids);

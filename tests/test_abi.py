@@ -52,6 +52,11 @@ def test_size_queries_match_the_shapes():
     assert w2 >= M * (4 + 4 * h + 2 * h + 6 * hl + 2 * hl + 2 * fl + 4 * vl)
     bad = ShardDesc(2, 96, 384, 2)           # head size 48 is not supported
     assert P.arena_bytes(bad) == 0 and P.workspace_bytes(bad, 8) == 0
+    # a workspace sized for max_tokens serves every smaller batch: the size never shrinks as tokens grow
+    for name in ("opt125m_tp1", "opt6.7b_tp2", "opt13b_tp4", "opt13b_tp2_pp2"):
+        d = CONFIGS[name]["desc"]
+        sizes = [P.workspace_bytes(d, m) for m in (1, 2, 8, 16, 17, 32, 63, 64, 65, 100, 128, 255, 256, 257, 512, 1024, 2048)]
+        assert all(a <= b for a, b in zip(sizes, sizes[1:])), (name, sizes)
 
 
 @given(st.lists(st.integers(0, 5), min_size=0, max_size=80),

@@ -272,6 +272,25 @@ def test_serving_shapes_full_size_decisions_logits_determinism(block_residency):
         rig.close()
 
 
+@pytest.mark.parametrize("tokens", [(1, 8), (4, 8), (8, 8), (9, 8), (16, 8), (24, 8), (32, 8), (3, 67)])
+def test_batches_of_short_requests_in_a_workspace_sized_for_the_largest(tokens):
+    """The paper's workloads batch up to 32 requests of 8 tokens (Section 5.2).  One context whose workspace is
+    sized for 256 tokens runs every smaller batch too, through whichever product kernels the batch size selects
+    (row streaming, K-sliced 64x64 tiles up to 256 tokens, full tiles), each within the bar."""
+    desc = ShardDesc(2, 512, 2048, 4, vocab=1024, max_pos=80, tp=2, rank=1)
+    rig = Rig([desc], max_tokens=256)
+    try:
+        m = rig.add(desc, seed=230)
+        b, s_ = tokens
+        ids = token_ids(231 + b, b, s_, desc.vocab)
+        got = rig.ctx.infer(m, ids)
+        assert_close(got, oracle_logits(rig, m, desc, ids), f"{b} x {s_}")
+        again = rig.ctx.infer(m, ids)
+        assert np.array_equal(got, again)          # K slices are added in a fixed order
+    finally:
+        rig.close()
+
+
 def test_degenerate_shapes_no_layers_single_token():
     """A model without decoder layers (embeddings, final LayerNorm and head only) and a one-token request:
     the smallest things the path can be asked for; empty batches are refused."""
