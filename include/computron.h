@@ -1,7 +1,7 @@
 /*
  * computron.h — C ABI of the MI355X model-swapping library.
  *
- * One GPU's share of "model parallel swapping" (Computron, arXiv 2306.13835):
+ * One GPU's share of model-parallel swapping (Computron, arXiv 2306.13835):
  * the fp16 parameters of one tensor-parallel rank of an OPT decoder live in
  * page-locked host memory (Section 3.2, last paragraph), are swapped into a
  * device arena when the model is requested and swapped out again when a
@@ -223,7 +223,8 @@ int ctn_infer_stage(ctn_ctx* ctx, ctn_model m, const int32_t* token_ids_host, co
                     int32_t in_is_device, int32_t batch, int32_t seq, void* out, int32_t out_is_device);
 
 /* Workspace bytes a context needs for models of this description at up to
- * max_tokens = batch*seq tokens per inference and n_models registrations. */
+ * max_tokens = batch*seq tokens per inference and n_models registrations.  Never decreases as
+ * max_tokens grows: a workspace of this size serves every smaller batch as well. */
 uint64_t ctn_workspace_bytes(const ctn_model_desc* desc, int64_t max_tokens, int32_t n_models);
 /* Arena bytes one shard of this description occupies (tensors padded to 256 B). */
 uint64_t ctn_arena_bytes(const ctn_model_desc* desc);
@@ -314,9 +315,8 @@ int ctn_engine_step(ctn_engine* eng, void* logits_out, int64_t* served_ids, int3
                     ctn_model* model, int32_t* was_miss);
 int ctn_engine_pending(ctn_engine* eng, int64_t* n);
 
-/* The two-lane engine (Section 3.2: load entries are asynchronous, "a later
- * batch entry [can] proceed without waiting for a previous load entry
- * involving another model").  Lane 0 runs batches of completely loaded
+/* The two-lane engine (Section 3.2: load entries are asynchronous, so a batch
+ * of one model need not wait for the load of another).  Lane 0 runs batches of completely loaded
  * models, one at a time; lane 1 takes one miss at a time, the model's swap-in
  * followed, block by block, by its batch; a model whose miss is in flight is
  * not dispatched again until that batch has completed.  Needs a context with
@@ -396,7 +396,7 @@ int ctn_op_layernorm(const float* x, const void* gain_f16, const void* bias_f16,
 int ctn_op_gemm(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,
                 int32_t N, int32_t K, int32_t epilogue, void* stream);
 /* The same product with a device scratch buffer (16-byte aligned; may be NULL): products with
- * M <= 64 may then cut K into slices computed by separate workgroups, whose fp32 partial tiles
+ * M <= 256 (and larger ones with few tiles and a long K) may then cut K into slices computed by separate workgroups, whose fp32 partial tiles
  * are added in a fixed order, so the result does not depend on timing.  ctn_infer does the same
  * with a slice of its workspace. */
 int ctn_op_gemm_ws(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,

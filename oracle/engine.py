@@ -22,8 +22,8 @@ duration of one batch.  Everything else is deterministic bookkeeping, which is
 what the library's scheduler is compared with.
 
 `simulate_async` is the engine of Section 3.2 proper: load entries are
-asynchronous, so "a later batch entry [can] proceed without waiting for a
-previous load entry involving another model".  On one GPU this becomes two
+asynchronous, so a batch of one model need not wait for the load of another.
+On one GPU this becomes two
 lanes that run side by side:
   * the hit lane executes batches of models that are completely loaded, one
     batch at a time;
