@@ -360,6 +360,8 @@ def run_counters(args):
     torch.zeros(1, device="cuda")
     cfg = CONFIGS[args.config]
     desc, batch, seq = cfg["desc"], cfg["batch"], cfg["seq"]
+    if args.shape:                                             # e.g. 1x64: the forward pass of a small request instead
+        batch, seq = (int(x) for x in args.shape.lower().split("x"))
     nbytes, M = shard_bytes(desc), batch * seq
     arena = torch.empty(P.arena_bytes(desc), dtype=torch.uint8, device="cuda")
     ws = torch.empty(P.workspace_bytes(desc, M), dtype=torch.uint8, device="cuda")
@@ -375,14 +377,15 @@ def run_counters(args):
     B.op_copy(b, a, cal, 1024, ctx.stream_compute)           # copy_table_kernel<2>: reads and writes 2^30 B
     ctx.stream_compute.synchronize()
     ctx.swap_in(m); ctx.wait(m)                              # copy_table_kernel<0> x (layers + 1)
-    ctx.infer(m, token_ids(cfg["idseed"], batch, seq, desc.vocab), out=logits)
+    for _ in range(max(1, args.repeat)):
+        ctx.infer(m, token_ids(cfg["idseed"], batch, seq, desc.vocab), out=logits)
     ctx.sync()
     ctx.swap_out(m); ctx.wait(m)                             # copy_table_kernel<1> x (layers + 1)
     ctx.close()
     del tensors
     pool.close()
     print(json.dumps({"workload": "counters", "config": args.config, "calibration_copy_bytes": cal,
-                      "shard_bytes": nbytes}), flush=True)
+                      "shard_bytes": nbytes, "batch": batch, "seq": seq, "forwards": max(1, args.repeat)}), flush=True)
 
 
 def cpu_baseline(tensors, ids, desc, nbytes):
@@ -433,6 +436,8 @@ def main():
                     help="serve / grid workloads: the asynchronous engine (batches of loaded models go on while another loads)")
     ap.add_argument("--load-ahead", action="store_true",
                     help="serve workload with --two-lane: let the idle engine load the predicted next model")
+    ap.add_argument("--shape", default="", help="counters workload: BATCHxSEQ of the forward pass (default: the config's)")
+    ap.add_argument("--repeat", type=int, default=1, help="counters workload: number of resident forward passes")
     ap.add_argument("--copy-blocks", type=int, default=0, help="workgroups per copy kernel (0: library default)")
     ap.add_argument("--copy-cus", type=int, default=0, help="compute units reserved per transfer direction")
     args = ap.parse_args()
