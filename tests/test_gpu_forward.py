@@ -155,7 +155,9 @@ def test_full_size_shards_sampled_batch_rows(name, rows):
     the oracle evaluates a sample of the batch rows (rows do not interact)."""
     c = CONFIGS[name]
     desc, batch, seq = c["desc"], c["batch"], c["seq"]
-    rig = Rig([desc], max_tokens=batch * seq)
+    # bench.py's own configuration: library-owned CU-partitioned streams, transfer mode AUTO, every host
+    # tensor a pinned region of its own (4 KiB apart), per-layer pipelining
+    rig = Rig([desc], max_tokens=batch * seq, mode=P.XFER_AUTO, gap=4096)
     try:
         t0 = time.time()
         m = rig.add(desc, seed=c["wseed"])
