@@ -38,6 +38,10 @@ PCIE5_X16_NOMINAL_GBPS = 64.0
 # passes summarised in profiles/counters_opt6.7b_tp2_pmc.md: FETCH_SIZE 98,373 KiB x 2.0 (calibration
 # factor of that counter) of loads from the host mapping + WRITE_SIZE 196,684 KiB x 1.0 of HBM stores.
 COPY_KERNEL_TRAFFIC = {"opt6.7b_tp2": {"fetch_bytes": 98373 * 2 * 1024, "write_bytes": 196684 * 1024}}
+# Same two passes, the fc1 product of that shard inside its 4 x 256 forward (M=1024, N=8192, K=4096,
+# 128x128x64 tiles): FETCH_SIZE 65,614 KiB x 2.0 = W once (67.1 MB) + A once per XCD (8 x 8.4 MB);
+# WRITE_SIZE 16,488 KiB = the fp16 output once.
+GEMM_FC1_TRAFFIC = {"opt6.7b_tp2": {"fetch_bytes": 65614 * 2 * 1024, "write_bytes": 16488 * 1024}}
 
 
 def log(*a):
@@ -327,9 +331,11 @@ def run_swap(args):
             "launches_timed": len(launch_ms), "measured_over": roof_where,
         },
         "roofline_gemm": {
-            "kernel": f"gemm_nt_kernel<128,128,64,64> fc1 shape M={gM} N={gN} K={gK}, bias+ReLU epilogue",
+            "kernel": f"gemm_dma_kernel<1> (128x128x64 tiles) fc1 shape M={gM} N={gN} K={gK}, bias+ReLU epilogue",
             "bound": "mfma", "achieved": round(gemm_tflops, 2), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(gemm_tflops / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None,
+            "frac": round(gemm_tflops / MFMA_F16_PEAK_TFLOPS, 4),
+            "traffic": sum(GEMM_FC1_TRAFFIC[args.config].values()) if args.config in GEMM_FC1_TRAFFIC else None,
+            "algorithmic_bytes": 2 * (gM * gK + gN * gK + gM * gN),
             "avg_launch_ms": round(gms, 4), "launches_timed": reps,
         },
         "without_copy_back": {"note": "option discard_on_evict (not the paper's swap-out, not the timed region): "

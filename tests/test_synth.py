@@ -83,7 +83,7 @@ def test_token_ids_cover_full_vocab():
     assert np.array_equal(ids, token_ids(103, 4, 256, 50272))
 
 
-def test_forward_flop_matches_survey_figures():
+def test_forward_flop_matches_closed_form_figures():
     assert abs(forward_flop(CONFIGS["opt6.7b_tp2"]["desc"], 4, 256) / 6.88e12 - 1) < 0.02
     assert abs(forward_flop(CONFIGS["opt13b_tp4"]["desc"], 16, 128) / 13.2e12 - 1) < 0.02
     assert abs(forward_flop(CONFIGS["opt1.3b_tp1"]["desc"], 8, 128) / 2.71e12 - 1) < 0.02
