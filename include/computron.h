@@ -407,7 +407,10 @@ int ctn_op_gemm_ws(const void* A_f16, const void* W_f16, const void* bias_f16, v
  * LDS when K is a multiple of 64; 17 = the same tiles always staged through registers) on every product of
  * ctn_op_gemm and ctn_infer; -1 restores the library's choice.  100 / 101 switch the direct fills off / on,
  * 102 / 103 the register-staged tiles' second stage of loads in flight (both default on, where K is a multiple
- * of the tile's K step; results do not change) without forcing a tile.  CTN_E_INVAL for any other value. */
+ * of the tile's K step; results do not change) without forcing a tile; 104 / 105 switch off / on (default) that a
+ * K-sliced row-parallel product inside ctn_infer leaves the sum of its slices to the LayerNorm that follows
+ * (results do not change); 106 / 107 switch off / on (default) the second pass of a K-sliced product reading four
+ * columns per thread with every slice in flight (results do not change).  CTN_E_INVAL for any other value. */
 int ctn_debug_gemm_tile(int32_t cfg);
 /* Causal self-attention of every (batch, head): qkv fp16 [batch*seq, 3*heads*d]
  * holds q | k | v side by side; out fp16 [batch*seq, heads*d]

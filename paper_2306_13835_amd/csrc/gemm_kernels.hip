@@ -803,7 +803,77 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs g) {
   }
 }
 
+// The same pass four columns per thread with every slice's load issued before the first is used
+// (MAXS loads in flight; slices past the last re-read slice 0 and are dropped by a select): one
+// memory round trip per element instead of one per slice.  Same order of additions, same bits.
+// Needs N and ldc to be multiples of 4.
+typedef _Float16 half4r __attribute__((ext_vector_type(4)));
+template <int EPI, int MAXS>
+__global__ __launch_bounds__(256) void splitk_reduce4_kernel(const GemmArgs g) {
+  const int64_t ncols4 = static_cast<int64_t>(g.N) * g.parts / 4;
+  const int64_t total4 = static_cast<int64_t>(g.M) * ncols4;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= total4) return;
+  const int64_t m = idx / ncols4, c = (idx % ncols4) * 4;
+  const int part = static_cast<int>(c / g.N), n = static_cast<int>(c % g.N);
+  const float4v* src = reinterpret_cast<const float4v*>(g.partial) + idx;
+  float4v p[MAXS];
+#pragma unroll
+  for (int sl = 0; sl < MAXS; ++sl) p[sl] = src[(sl < g.splits ? sl : 0) * total4];
+  const int64_t o = m * g.ldc + c;
+  float4v r = {0.f, 0.f, 0.f, 0.f};
+  if (EPI == CTN_EPI_BIAS_RESID_F32) r = *reinterpret_cast<const float4v*>(static_cast<float*>(g.out) + o);
+  half4r bias = {0, 0, 0, 0};
+  if (EPI != CTN_EPI_F32) {
+    const _Float16* bp = part == 0 ? g.bias[0] : (part == 1 ? g.bias[1] : g.bias[2]);
+    bias = *reinterpret_cast<const half4r*>(bp + n);
+  }
+  float4v v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int sl = 0; sl < MAXS; ++sl) v += sl < g.splits ? p[sl] : float4v{0.f, 0.f, 0.f, 0.f};
+  if (EPI != CTN_EPI_F32) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += static_cast<float>(bias[e]);
+  }
+  if (EPI == CTN_EPI_BIAS_F16 || EPI == CTN_EPI_BIAS_RELU_F16) {
+    half4r h;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      h[e] = static_cast<_Float16>(EPI == CTN_EPI_BIAS_RELU_F16 ? (v[e] > 0.f ? v[e] : 0.f) : v[e]);
+    *reinterpret_cast<half4r*>(static_cast<_Float16*>(g.out) + o) = h;
+  } else if (EPI == CTN_EPI_BIAS_RESID_F32) {
+    *reinterpret_cast<float4v*>(static_cast<float*>(g.out) + o) = r + v;
+  } else {
+    *reinterpret_cast<float4v*>(static_cast<float*>(g.out) + o) = v;
+  }
+}
+
+template <int EPI>
+void launch_reduce4(const GemmArgs& g, hipStream_t s) {
+  const int64_t total4 = static_cast<int64_t>(g.M) * g.N * g.parts / 4;
+  const dim3 grid(static_cast<unsigned>((total4 + 255) / 256)), block(256);
+  if (g.splits <= 4) hipLaunchKernelGGL((splitk_reduce4_kernel<EPI, 4>), grid, block, 0, s, g);
+  else if (g.splits <= 8) hipLaunchKernelGGL((splitk_reduce4_kernel<EPI, 8>), grid, block, 0, s, g);
+  else hipLaunchKernelGGL((splitk_reduce4_kernel<EPI, 16>), grid, block, 0, s, g);
+}
+
+bool g_reduce4 = true;   // test hook: the four-column reduction where the shape allows it
+
 hipError_t launch_splitk_reduce(const GemmArgs& g, int epi, hipStream_t s) {
+  if (g_reduce4 && g.N % 4 == 0 && g.ldc % 4 == 0 && g.splits <= 16 &&
+      reinterpret_cast<uintptr_t>(g.out) % 16 == 0 && reinterpret_cast<uintptr_t>(g.partial) % 16 == 0 &&
+      (epi == CTN_EPI_F32 || (reinterpret_cast<uintptr_t>(g.bias[0]) % 8 == 0 &&
+                              (g.parts < 2 || reinterpret_cast<uintptr_t>(g.bias[1]) % 8 == 0) &&
+                              (g.parts < 3 || reinterpret_cast<uintptr_t>(g.bias[2]) % 8 == 0)))) {
+    switch (epi) {
+      case CTN_EPI_BIAS_F16: launch_reduce4<CTN_EPI_BIAS_F16>(g, s); break;
+      case CTN_EPI_BIAS_RELU_F16: launch_reduce4<CTN_EPI_BIAS_RELU_F16>(g, s); break;
+      case CTN_EPI_BIAS_RESID_F32: launch_reduce4<CTN_EPI_BIAS_RESID_F32>(g, s); break;
+      case CTN_EPI_F32: launch_reduce4<CTN_EPI_F32>(g, s); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   const int64_t total = static_cast<int64_t>(g.M) * g.N * g.parts;
   const dim3 grid(static_cast<unsigned>((total + 255) / 256)), block(256);
 #define CTN_RED(E) hipLaunchKernelGGL((splitk_reduce_kernel<E>), grid, block, 0, s, g)
@@ -819,6 +889,7 @@ hipError_t launch_splitk_reduce(const GemmArgs& g, int epi, hipStream_t s) {
 }
 
 int g_force_tile = -1;   // test / tuning hook: tile configuration forced for every product
+bool g_defer_sums = true; // test hook: a split residual product may leave its summation to the caller's LayerNorm
 
 hipError_t launch_config(int cfg, const GemmArgs& g, int epi, hipStream_t s) {
   switch (cfg) {
@@ -861,10 +932,10 @@ hipError_t launch_splitk(GemmArgs g, int cfg, int splits, int epi, hipStream_t s
   g.splits = splits;
   hipError_t e = launch_config(cfg, g, EPI_PARTIAL, s);
   if (e != hipSuccess) return e;
-  if (defer && epi == CTN_EPI_BIAS_RESID_F32 && g.parts == 1 && g.ldc == g.N && g.M >= 256) {
-    // the caller's next kernel reads x anyway and finishes the update there (one wavefront per
-    // row: only worth it when there are many rows; with few rows and many slices the stand-alone
-    // reduction, which spreads over the whole chip, is faster: 4.3 against 6.1 ms per 1 x 64 forward)
+  if (g_defer_sums && defer && epi == CTN_EPI_BIAS_RESID_F32 && g.parts == 1 && g.ldc == g.N) {
+    // the caller's next kernel, a LayerNorm, reads x anyway and finishes the update there (with
+    // few rows its variant that keeps every slice's load in flight at once: one kernel and one
+    // memory round trip in place of two kernels)
     defer->partial = g.partial;
     defer->splits = splits;
     defer->bias = g.bias[0];
@@ -948,6 +1019,14 @@ int gemm_force_tile(int cfg) {
   }
   if (cfg == 102 || cfg == 103) {      // tuning hook: global loads two steps ahead off / on
     g_deep_loads = cfg == 103;
+    return 0;
+  }
+  if (cfg == 106 || cfg == 107) {      // test hook: four-column split-K reduction off / on
+    g_reduce4 = cfg == 107;
+    return 0;
+  }
+  if (cfg == 104 || cfg == 105) {      // test hook: summation of split residual products left to LayerNorm off / on
+    g_defer_sums = cfg == 105;
     return 0;
   }
   if (cfg < -1 || cfg > 17) return -1;

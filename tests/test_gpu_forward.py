@@ -293,6 +293,32 @@ def test_batches_of_short_requests_in_a_workspace_sized_for_the_largest(tokens):
         rig.close()
 
 
+@pytest.mark.parametrize("hidden,heads", [(512, 4), (2048, 16), (4096, 32), (5120, 40), (8192, 64)])
+def test_layernorm_finishing_split_products_changes_no_bit(hidden, heads):
+    """Between 17 and 256 tokens the row-parallel products are cut along K and leave the sum of their slices to
+    the LayerNorm that follows (one workgroup per row, every slice's load in flight at once).  That kernel adds in
+    the stand-alone reduction's order, so switching the hand-over off must change no bit, at every row width the
+    kernel has a variant for; one case per width is also held against the oracle."""
+    from paper_2306_13835_amd import binding as B
+    desc = ShardDesc(2, hidden, 2 * hidden, heads, vocab=512, max_pos=80, tp=2, rank=1)
+    rig = Rig([desc], max_tokens=256)
+    try:
+        m = rig.add(desc, seed=240)
+        for b, s_ in ((1, 64), (3, 8), (4, 64), (1, 17)):
+            ids = token_ids(241 + b, b, s_, desc.vocab)
+            try:
+                B.debug_gemm_tile(104)
+                apart = rig.ctx.infer(m, ids)
+            finally:
+                B.debug_gemm_tile(105)
+            fused = rig.ctx.infer(m, ids)
+            assert np.array_equal(fused, apart), (hidden, b, s_)
+            if (b, s_) == (1, 64) and hidden <= 5120:      # (the bar is stated for the configs' widths, up to 5120)
+                assert_close(fused, oracle_logits(rig, m, desc, ids), f"hidden {hidden}, {b} x {s_}")
+    finally:
+        rig.close()
+
+
 def test_degenerate_shapes_no_layers_single_token():
     """A model without decoder layers (embeddings, final LayerNorm and head only) and a one-token request:
     the smallest things the path can be asked for; empty batches are refused."""

@@ -166,7 +166,7 @@ def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
     assert np.all(np.abs(got - want) <= tol)
     with pytest.raises(P.CtnError):
         B.debug_gemm_tile(18)
-    for bad in (-2, 99, 104):          # 100..103 are the fill / load-depth switches, nothing else is accepted
+    for bad in (-2, 99, 108):          # 100..107 are the fill / load-depth / hand-over / reduction switches, nothing else is accepted
         with pytest.raises(P.CtnError):
             B.debug_gemm_tile(bad)
 
@@ -275,14 +275,17 @@ def test_gemm_split_k_with_workspace(stream, M, N, K, epi, force):
     outs = []
     B.debug_gemm_tile(force)
     try:
-        for _ in range(2):
+        for hook in (107, 107, 106):       # the reduction four columns at a time, again, then one column at a time
+            B.debug_gemm_tile(hook)
             out = mk()
             B.op_gemm_ws(dev(A), dev(W), dev(bias), out, M, N, K, epi, ws, stream)
             stream.synchronize()
             outs.append(out.cpu().numpy())
     finally:
+        B.debug_gemm_tile(107)
         B.debug_gemm_tile(-1)
     assert np.array_equal(outs[0], outs[1])
+    assert np.array_equal(outs[0], outs[2])       # both reductions add the slices in the same order
     got = outs[0].astype(np.float64)
     scale = np.sqrt(K) * 0.05
     if outs[0].dtype == np.float16:
