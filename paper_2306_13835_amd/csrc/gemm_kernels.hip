@@ -915,12 +915,16 @@ hipError_t launch_config(int cfg, const GemmArgs& g, int epi, hipStream_t s) {
   }
 }
 
-// Split-K for small M: enough (tile, slice) workgroups to fill the chip twice, each slice at
+// Split-K for small M: enough (tile, slice) workgroups to fill the chip once (32-row tiles) or twice, each slice at
 // least two K steps long, the partial buffer permitting.  Returns 1 when splitting does not pay.
 int choose_splits(const GemmArgs& g, int bm, int bn, size_t partial_floats) {
   const int tiles = ((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) * g.parts;
   const int ksteps = (g.K + 63) / 64;
-  int splits = 512 / (tiles > 0 ? tiles : 1);
+  // (measured on whole forward passes, workgroup targets from 128 to 2048: the 32x128 tiles of up to 32 rows do
+  // best with one workgroup per CU, 3 x 8 tokens 2.77 -> 2.54 ms on the 6.7B/TP2 shard, 3.27 -> 2.91 ms on the
+  // 13B/TP4 shard; the 64x64 tiles with two, every other target 5-25 % slower)
+  const int target = bm <= 32 ? 256 : 512;
+  int splits = target / (tiles > 0 ? tiles : 1);
   if (splits > ksteps / 2) splits = ksteps / 2;
   if (splits > 16) splits = 16;
   const size_t per_slice = static_cast<size_t>(g.M) * g.N * g.parts;
