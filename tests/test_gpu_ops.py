@@ -120,7 +120,8 @@ def test_gemm_rejects_bad_k(stream):
 
 @pytest.mark.parametrize("batch,seq,heads,d", [(1, 8, 12, 64), (2, 33, 3, 64), (4, 256, 16, 128), (1, 64, 16, 128),
                                                (2, 129, 2, 128), (16, 128, 10, 128), (1, 300, 2, 64),
-                                               (1, 2048, 1, 64), (1, 1, 1, 128), (3, 127, 5, 64)])
+                                               (1, 2048, 1, 64), (1, 1, 1, 128), (3, 127, 5, 64),
+                                               (8, 256, 16, 128), (4, 200, 40, 64)])   # (256 and more wide workgroups)
 def test_attention(stream, batch, seq, heads, d):
     rng = np.random.default_rng(batch * seq + heads + d)
     hl = heads * d
