@@ -396,21 +396,30 @@ int ctn_op_layernorm(const float* x, const void* gain_f16, const void* bias_f16,
 int ctn_op_gemm(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,
                 int32_t N, int32_t K, int32_t epilogue, void* stream);
 /* The same product with a device scratch buffer (16-byte aligned; may be NULL): products with
- * M <= 256 (and larger ones with few tiles and a long K) may then cut K into slices computed by separate workgroups, whose fp32 partial tiles
- * are added in a fixed order, so the result does not depend on timing.  ctn_infer does the same
+ * M <= 256 (and larger ones with few tiles and a long K) may then cut K into slices computed by
+ * separate workgroups, whose fp32 partial tiles are added in a fixed order, so the result does
+ * not depend on timing.  ctn_infer does the same
  * with a slice of its workspace. */
 int ctn_op_gemm_ws(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,
                    int32_t N, int32_t K, int32_t epilogue, void* workspace, uint64_t workspace_bytes,
                    void* stream);
-/* Test and tuning hook, process wide: forces tile configuration cfg (0..17; 9 and 10 = the streaming kernels for M <= 64, ignored for larger M; 16 = the row-contiguous streaming kernel for M <= 16, ignored for larger M; 14 and 15 = split-K
- * over 64x64 / 32x128 tiles where a workspace is given; 0 = 128x128x64 tiles, filled straight from global memory into
- * LDS when K is a multiple of 64; 17 = the same tiles always staged through registers) on every product of
- * ctn_op_gemm and ctn_infer; -1 restores the library's choice.  100 / 101 switch the direct fills off / on,
- * 102 / 103 the register-staged tiles' second stage of loads in flight (both default on, where K is a multiple
- * of the tile's K step; results do not change) without forcing a tile; 104 / 105 switch off / on (default) that a
- * K-sliced row-parallel product inside ctn_infer leaves the sum of its slices to the LayerNorm that follows
- * (results do not change); 106 / 107 switch off / on (default) the second pass of a K-sliced product reading four
- * columns per thread with every slice in flight (results do not change).  CTN_E_INVAL for any other value. */
+/* Test and tuning hook, process wide: forces tile configuration cfg on every product of ctn_op_gemm and
+ * ctn_infer; -1 restores the library's choice.
+ *   0        128x128x64 tiles, filled straight from global memory into LDS when K is a multiple of 64
+ *   1..8, 11..13  the other register-staged tile shapes
+ *   9, 10    the streaming kernels for M <= 64 (ignored for larger M)
+ *   14, 15   split-K over 64x64 / 32x128 tiles where a workspace is given
+ *   16       the row-contiguous streaming kernel for M <= 16 (ignored for larger M)
+ *   17       128x128x64 tiles always staged through registers
+ * Switches that force no tile and change no result (all default on):
+ *   100 / 101  direct global -> LDS fills off / on
+ *   102 / 103  the register-staged tiles' second stage of loads in flight off / on (where K is a multiple
+ *              of the tile's K step)
+ *   104 / 105  off / on: a K-sliced row-parallel product inside ctn_infer leaves the sum of its slices to the
+ *              LayerNorm that follows
+ *   106 / 107  off / on: the second pass of a K-sliced product reads four columns per thread with every
+ *              slice in flight
+ * CTN_E_INVAL for any other value. */
 int ctn_debug_gemm_tile(int32_t cfg);
 /* Causal self-attention of every (batch, head): qkv fp16 [batch*seq, 3*heads*d]
  * holds q | k | v side by side; out fp16 [batch*seq, heads*d]
