@@ -226,6 +226,14 @@ def run_swap(args):
     ctx.swap_out(models[0]); ctx.wait(models[0])
     ctx.sync()
 
+    # the same alternation with every load and offload through the copy kernel (--transfer kernel); AUTO, the
+    # default, offloads by DMA and moves loads to the DMA engines too while earlier offloads are still running:
+    # kernel-issued host reads lose rate against concurrent writes to the host
+    if args.transfer != "kernel":
+        ctx.set_mode(MODES["kernel"], True, args.copy_blocks)
+        w_kern, _ = alternate(models, 4, 2)
+        side["kernel_loads_ms_per_step"] = w_kern / 4 * 1e3
+
     # the same alternation if evictions only freed the device copy (parameters are read-only on the device);
     # an option, off by default: the paper's swap-out is a real copy and so is the timed region's
     ctx.set_mode(MODES[args.transfer], True, args.copy_blocks)
@@ -341,6 +349,11 @@ def run_swap(args):
         "without_copy_back": {"note": "option discard_on_evict (not the paper's swap-out, not the timed region): "
                                       "evictions free the device copy only", "ms_per_step": round(side["discard_ms_per_step"], 3),
                               "value_gbps": round(nbytes / side["discard_ms_per_step"] / 1e6, 3)},
+        "kernel_transfers_throughout": ({"note": "the timed workload with --transfer kernel: every load and offload "
+                                                 "through the copy kernel, none through the DMA engines",
+                                         "ms_per_step": round(side["kernel_loads_ms_per_step"], 3),
+                                         "value_gbps": round(nbytes / side["kernel_loads_ms_per_step"] / 1e6, 3)}
+                                        if "kernel_loads_ms_per_step" in side else None),
         "other_host_layout": {
             "layout": "packed" if args.host_layout == "separate" else "separate",
             "ms_per_step": round(side["other_layout_ms_per_step"], 3),
