@@ -41,6 +41,9 @@ COPY_KERNEL_TRAFFIC = {"opt6.7b_tp2": {"fetch_bytes": 98373 * 2 * 1024, "write_b
 # Same two passes, the fc1 product of that shard inside its 4 x 256 forward (M=1024, N=8192, K=4096,
 # 128x128x64 tiles): FETCH_SIZE 65,614 KiB x 2.0 = W once (67.1 MB) + A once per XCD (8 x 8.4 MB);
 # WRITE_SIZE 16,488 KiB = the fp16 output once.
+# Same passes, LayerNorm of 1024 x 4096: FETCH_SIZE 8,281 KiB x 2.0 (16.96 MB for 16.78 MB of fp32 rows),
+# WRITE_SIZE 8,192 KiB (the fp16 rows).
+LAYERNORM_TRAFFIC = {"opt6.7b_tp2": (8281 * 2 + 8192) * 1024}
 GEMM_FC1_TRAFFIC = {"opt6.7b_tp2": {"fetch_bytes": 65614 * 2 * 1024, "write_bytes": 16488 * 1024}}
 
 
@@ -287,6 +290,18 @@ def run_swap(args):
                                       for _ in range(reps)]) / reps
     gemm_tflops = 2.0 * gM * gN * gK / gms / 1e9
 
+    # LayerNorm of the forward pass's activations [M, h] alone, for the HBM roofline of the elementwise kernels:
+    # 16 input buffers in rotation (more than the last-level cache holds), fp32 in, fp16 out
+    lM, lh, lrot = M, desc.hidden, 16
+    lx = [torch.randn(lM, lh, device="cuda") for _ in range(lrot)]
+    lg, lb = torch.ones(lh, device="cuda").half(), torch.zeros(lh, device="cuda").half()
+    lo = torch.empty(lM, lh, device="cuda").half()
+    B.op_layernorm(lx[0], lg, lb, lo, lM, lh, sg)
+    lreps = 4 * lrot
+    lms = ev_time(torch, sg, lambda: [B.op_layernorm(lx[i % lrot], lg, lb, lo, lM, lh, sg) for i in range(lreps)]) / lreps
+    ln_bytes = 6 * lM * lh
+    del lx
+
     value = args.steps * nbytes / wall / 1e9
     flop = forward_flop(desc, batch, seq)
     result = {
@@ -349,6 +364,13 @@ def run_swap(args):
         "without_copy_back": {"note": "option discard_on_evict (not the paper's swap-out, not the timed region): "
                                       "evictions free the device copy only", "ms_per_step": round(side["discard_ms_per_step"], 3),
                               "value_gbps": round(nbytes / side["discard_ms_per_step"] / 1e6, 3)},
+        "roofline_layernorm": {
+            "kernel": f"layernorm_kernel, {lM} rows x {lh} (fp32 in, fp16 out), inputs rotating through {lrot} buffers",
+            "bound": "hbm", "achieved": round(ln_bytes / lms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(ln_bytes / lms / 1e6 / HBM_PEAK_GBPS, 4),
+            "traffic": LAYERNORM_TRAFFIC.get(args.config), "algorithmic_bytes": ln_bytes,
+            "avg_launch_ms": round(lms, 5), "launches_timed": lreps,
+        },
         "kernel_transfers_throughout": ({"note": "the timed workload with --transfer kernel: every load and offload "
                                                  "through the copy kernel, none through the DMA engines",
                                          "ms_per_step": round(side["kernel_loads_ms_per_step"], 3),
