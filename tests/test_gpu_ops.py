@@ -67,7 +67,8 @@ def test_embed(stream, hidden, rank, tp):
     assert np.array_equal(x.cpu().numpy(), want)                    # one fp32 add: exact
 
 
-@pytest.mark.parametrize("rows,hidden", [(1, 768), (8, 768), (5, 2048), (133, 4096), (64, 5120), (3, 128), (9, 8192)])
+@pytest.mark.parametrize("rows,hidden", [(1, 768), (8, 768), (5, 2048), (133, 4096), (64, 5120), (3, 128), (9, 8192),
+                                         (300, 4096), (257, 5120), (256, 2048), (700, 768)])   # (more than 256 rows: the four-wavefront kernel)
 def test_layernorm(stream, rows, hidden):
     rng = np.random.default_rng(rows * hidden)
     x = (rng.standard_normal((rows, hidden)) * 3 + 0.5).astype(np.float32)
