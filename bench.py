@@ -44,6 +44,9 @@ COPY_KERNEL_TRAFFIC = {"opt6.7b_tp2": {"fetch_bytes": 98373 * 2 * 1024, "write_b
 # Same passes, LayerNorm of 1024 x 4096: FETCH_SIZE 8,281 KiB x 2.0 (16.96 MB for 16.78 MB of fp32 rows),
 # WRITE_SIZE 8,192 KiB (the fp16 rows).
 LAYERNORM_TRAFFIC = {"opt6.7b_tp2": (8281 * 2 + 8192) * 1024}
+# FETCH_SIZE over one resident forward pass of a small request (profiles/forward_small_requests_...md):
+# bytes that left HBM per pass, against 6,667,665,408 B of weights.
+SMALL_REQUEST_FETCH = {"opt6.7b_tp2": {8: 6849e6, 64: 7963e6}}
 GEMM_FC1_TRAFFIC = {"opt6.7b_tp2": {"fetch_bytes": 65614 * 2 * 1024, "write_bytes": 16488 * 1024}}
 
 
@@ -337,7 +340,8 @@ def run_swap(args):
             "forward_small_requests": {
                 f"1x{t}": {"ms": round(side[f"forward_resident_1x{t}_ms"], 3),
                            "weight_stream_bound_ms": round(nbytes / HBM_PEAK_GBPS / 1e6, 3),
-                           "frac_of_hbm_peak": round(nbytes / HBM_PEAK_GBPS / 1e6 / side[f"forward_resident_1x{t}_ms"], 4)}
+                           "frac_of_hbm_peak": round(nbytes / HBM_PEAK_GBPS / 1e6 / side[f"forward_resident_1x{t}_ms"], 4),
+                           "traffic": SMALL_REQUEST_FETCH.get(args.config, {}).get(t)}
                 for t in (8, 64) if f"forward_resident_1x{t}_ms" in side},
         },
         "roofline": {
