@@ -96,7 +96,8 @@ typedef struct {
   int32_t transfer_mode;     /* CTN_XFER_DMA: one hipMemcpyAsync per tensor (the paper's per-tensor
                                 messages, Section 5.1); CTN_XFER_KERNEL: one copy kernel per layer
                                 block; CTN_XFER_AUTO: loads of a host list in many separate pieces
-                                use the copy kernel unless an earlier offload is still running
+                                use the copy kernel unless an earlier offload is still running or
+                                was enqueued less than two load times ago
                                 (then, and for lists whose tensors lie back to back on the host,
                                 one DMA copy per run of adjacent tensors: the DMA engines share a
                                 link that is busy in both directions more evenly); offloads use DMA */
