@@ -47,7 +47,8 @@ hipError_t launch_layernorm(float* x, const _Float16* g, const _Float16* b, _Flo
 hipError_t launch_gemm(const _Float16* A, const _Float16* W, const _Float16* bias, void* out, int M, int N,
                        int K, int epilogue, hipStream_t s, float* partial = nullptr, size_t partial_floats = 0,
                        PendingSum* defer = nullptr);
-// Test / tuning hook: force one tile configuration (0..16) for every product; -1 restores the heuristic.
+// Test / tuning hook: force one tile configuration (0..17) for every product, -1 restores the heuristic;
+// 100..107 switch single mechanisms off / on (the values are listed at ctn_debug_gemm_tile in the C header).
 int gemm_force_tile(int cfg);
 // Three products sharing A in one launch: out[M, 3N] = [A W0^T + b0 | A W1^T + b1 | A W2^T + b2].
 hipError_t launch_gemm3(const _Float16* A, const _Float16* const W[3], const _Float16* const bias[3], void* out,
