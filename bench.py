@@ -320,6 +320,7 @@ def run_swap(args):
         "shard_load_latency_s": round(median(in_ms) / 1e3, 5),
         "first_token_latency_ms_p50": round(median(lat), 3),
         "first_token_latency_ms_max": round(max(lat), 3),
+        "step_latencies_ms": [round(x, 1) for x in lat],
         "link_peak_measured_gbps": {k: round(v, 3) for k, v in link.items()},
         "link_peak_both_directions_gbps": {k: round(v, 3) for k, v in bidir.items()},
         "swap_out_gbps_device_timeline": round(nbytes / median(out_ms) / 1e6, 3),

@@ -412,7 +412,7 @@ int ctn_op_gemm_ws(const void* A_f16, const void* W_f16, const void* bias_f16, v
  *   14, 15   split-K over 64x64 / 32x128 tiles where a workspace is given
  *   16       the row-contiguous streaming kernel for M <= 16 (ignored for larger M)
  *   17       128x128x64 tiles always staged through registers
- * Switches that force no tile and change no result (all default on):
+ * Switches that force no tile (all default on; 100..107 change no result):
  *   100 / 101  direct global -> LDS fills off / on
  *   102 / 103  the register-staged tiles' second stage of loads in flight off / on (where K is a multiple
  *              of the tile's K step)
@@ -420,6 +420,9 @@ int ctn_op_gemm_ws(const void* A_f16, const void* W_f16, const void* bias_f16, v
  *              LayerNorm that follows
  *   106 / 107  off / on: the second pass of a K-sliced product reads four columns per thread with every
  *              slice in flight
+ *   108 / 109  off / on: where the last round of 128x128 tiles would fill at most half of the chip, its columns
+ *              are computed in K slices by a second launch (a workspace is needed; the order of the fp32
+ *              additions in those columns differs from the one-launch product, nothing else)
  * CTN_E_INVAL for any other value. */
 int ctn_debug_gemm_tile(int32_t cfg);
 /* Causal self-attention of every (batch, head): qkv fp16 [batch*seq, 3*heads*d]

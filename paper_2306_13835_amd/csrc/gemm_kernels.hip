@@ -948,7 +948,10 @@ hipError_t launch_splitk(GemmArgs g, int cfg, int splits, int epi, hipStream_t s
   return launch_splitk_reduce(g, epi, s);
 }
 
-hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_floats, PendingSum* defer = nullptr) {
+bool g_tail_split = true;   // test hook: columns of a thinly filled last round computed in K slices
+
+hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_floats, PendingSum* defer = nullptr,
+                    bool allow_tail = true) {
   if (defer) *defer = PendingSum{};
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   if (g.K <= 0 || g.K % 8 || g.parts < 1 || g.parts > 3) return hipErrorInvalidValue;
@@ -993,6 +996,35 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
   }
   if (t0 <= 128) return launch_config(6, g, epi, s);               // few tiles: 64x64
   if (t0 <= 320) return launch_config(1, g, epi, s);               // under one round: 128x64 doubles the count
+  // A last round that fills at most half of the 512 slots (640 tiles of a 13B/TP4 layer, 1576 of the
+  // vocabulary head) costs nearly a whole round.  The columns of the full rounds go out as one product and
+  // the remaining columns as a second one whose tiles are cut along K, so that its workgroups fill the
+  // chip too and each takes a fraction of a tile's time; a third, small kernel adds the slices in order.
+  if (g_tail_split && allow_tail && g.partial && g.parts == 1 && t0 > 512 && t0 % 512 && t0 % 512 <= 256 &&
+      g.K >= 2048 && g.K % 64 == 0) {
+    const int tiles_m = (g.M + 127) / 128, tiles_n = (g.N + 127) / 128;
+    const int n_main = (t0 / 512) * 512 / tiles_m;                  // column tiles of the full rounds
+    const int tail_tiles = (tiles_n - n_main) * tiles_m;
+    GemmArgs tail = g;
+    tail.N = g.N - n_main * 128;
+    int splits = 512 / tail_tiles;
+    if (splits > 4) splits = 4;
+    if (splits > g.K / 64 / 4) splits = g.K / 64 / 4;               // a slice keeps at least four K steps
+    const size_t per_slice = static_cast<size_t>(g.M) * tail.N;
+    if (splits > static_cast<int>(partial_floats / per_slice)) splits = static_cast<int>(partial_floats / per_slice);
+    if (n_main > 0 && tail.N > 0 && splits >= 2) {
+      GemmArgs main_part = g;
+      main_part.N = n_main * 128;
+      hipError_t e = dispatch(main_part, epi, s, partial_floats, nullptr, false);
+      if (e != hipSuccess) return e;
+      const size_t skip = static_cast<size_t>(n_main) * 128;
+      tail.W[0] = g.W[0] + skip * g.K;
+      if (tail.bias[0]) tail.bias[0] = g.bias[0] + skip;
+      const size_t elem = (epi == CTN_EPI_BIAS_F16 || epi == CTN_EPI_BIAS_RELU_F16) ? 2 : 4;
+      tail.out = static_cast<char*>(g.out) + skip * elem;
+      return launch_splitk(tail, 0, splits, epi, s, nullptr);
+    }
+  }
   // Plenty of tiles: 128x128x64 (4 wavefronts) or 256x128x32 (8 wavefronts of 64x64), both two
   // workgroups per CU, i.e. 512 per round.  The wide tile moves 1.15 times the flops per unit time
   // when its rounds are full (measured at 1500-3000 tiles); what decides is the last, partly
@@ -1023,6 +1055,10 @@ int gemm_force_tile(int cfg) {
   }
   if (cfg == 102 || cfg == 103) {      // tuning hook: global loads two steps ahead off / on
     g_deep_loads = cfg == 103;
+    return 0;
+  }
+  if (cfg == 108 || cfg == 109) {      // test hook: K-sliced tail columns off / on
+    g_tail_split = cfg == 109;
     return 0;
   }
   if (cfg == 106 || cfg == 107) {      // test hook: four-column split-K reduction off / on

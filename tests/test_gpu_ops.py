@@ -168,7 +168,7 @@ def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
     assert np.all(np.abs(got - want) <= tol)
     with pytest.raises(P.CtnError):
         B.debug_gemm_tile(18)
-    for bad in (-2, 99, 108):          # 100..107 are the fill / load-depth / hand-over / reduction switches, nothing else is accepted
+    for bad in (-2, 99, 110):          # 100..109 are the fill / load-depth / hand-over / reduction / tail switches, nothing else is accepted
         with pytest.raises(P.CtnError):
             B.debug_gemm_tile(bad)
 
@@ -253,6 +253,44 @@ def test_gemm_direct_lds_fill_equals_register_staged(stream, M, N, K, epi):
         assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.abs(want) + 1e-4 * scale + 1e-7)
     else:
         assert np.abs(got - want).max() <= 2e-5 * scale * max(1.0, np.log2(K)) + 1e-6 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("M,N,K", [(1024, 8832, 2048), (2048, 5120, 2048), (1000, 8744, 2112)])
+@pytest.mark.parametrize("epi", [P.EPI_BIAS_F16, P.EPI_BIAS_RELU_F16, P.EPI_BIAS_RESID_F32, P.EPI_F32])
+def test_gemm_tail_columns_in_k_slices(stream, M, N, K, epi):
+    """A product whose 128x128 tiles end in a thinly filled round (552, 640 and 552 tiles against 512 slots): the
+    columns of that round are computed in K slices by a second launch and added in a fixed order.  Same bar as
+    any other product, the same bits when repeated, nothing written past the output, and close to the
+    one-launch result (only the order of the fp32 additions differs in the tail columns)."""
+    rng = np.random.default_rng(M + 3 * N + K + epi)
+    A, W, bias = f16(rng, (M, K)), f16(rng, (N, K), 0.05), f16(rng, N, 0.5)
+    res = rng.standard_normal((M, N)).astype(np.float32)
+    dA, dW, db = dev(A), dev(W), dev(bias)
+    ws = torch.full((4 * M * 4096 + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    outs = []
+    try:
+        for hook in (109, 109, 108):
+            B.debug_gemm_tile(hook)
+            out = dev(res) if epi in (P.EPI_BIAS_RESID_F32, P.EPI_F32) else torch.empty(M, N, dtype=torch.float16, device="cuda")
+            guard = torch.full((4096,), 7.0, dtype=torch.float32, device="cuda")
+            B.op_gemm_ws(dA, dW, db, out, M, N, K, epi, ws, stream)
+            stream.synchronize()
+            assert (guard == 7.0).all()
+            outs.append(out.cpu().numpy())
+    finally:
+        B.debug_gemm_tile(109)
+    assert np.array_equal(outs[0], outs[1])
+    acc = A.astype(np.float64) @ W.astype(np.float64).T
+    want = {P.EPI_BIAS_F16: acc + bias.astype(np.float64), P.EPI_BIAS_RELU_F16: np.maximum(acc + bias.astype(np.float64), 0),
+            P.EPI_BIAS_RESID_F32: res + acc + bias.astype(np.float64), P.EPI_F32: acc}[epi]
+    scale = np.sqrt(K) * 0.05
+    for got in (outs[0].astype(np.float64), outs[2].astype(np.float64)):
+        if outs[0].dtype == np.float16:
+            assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.abs(want) + 1e-4 * scale + 1e-7)
+        else:
+            assert np.abs(got - want).max() <= 2e-5 * scale * max(1.0, np.log2(K)) + 1e-6 * np.abs(want).max()
+    n_main = (((M + 127) // 128) * ((N + 127) // 128)) // 512 * 512 // ((M + 127) // 128) * 128
+    assert np.array_equal(outs[0][:, :n_main], outs[2][:, :n_main])      # the full rounds' columns: one launch either way
 
 
 @pytest.mark.parametrize("M,N,K", [(64, 4096, 8192), (64, 520, 1096), (17, 6144, 4096), (33, 200, 264), (48, 8192, 512)])
