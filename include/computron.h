@@ -397,7 +397,8 @@ int ctn_op_layernorm(const float* x, const void* gain_f16, const void* bias_f16,
 int ctn_op_gemm(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,
                 int32_t N, int32_t K, int32_t epilogue, void* stream);
 /* The same product with a device scratch buffer (16-byte aligned; may be NULL): products with
- * M <= 256 (and larger ones with few tiles and a long K) may then cut K into slices computed by
+ * M <= 256 (and larger ones with few tiles and K >= 2048, or, in the columns of a thinly filled
+ * last round of tiles, any product with K >= 2048) may then cut K into slices computed by
  * separate workgroups, whose fp32 partial tiles are added in a fixed order, so the result does
  * not depend on timing.  ctn_infer does the same
  * with a slice of its workspace. */
