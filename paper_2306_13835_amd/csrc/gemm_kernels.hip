@@ -968,9 +968,15 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
     // measured on MI355X: very wide outputs (the vocabulary head) re-read A too often in the
     // streaming kernel; mid-size outputs take 32 features per workgroup to halve A's L2 traffic
     const int64_t n_total = static_cast<int64_t>(g.N) * g.parts;
-    if (g.M <= 16 && g.K >= 4096) return launch_rowstream(g, epi, s);   // long rows: row-contiguous reads pay
+    // The row-stream kernel launches one workgroup per 16 features.  A count a little over one per CU (320 for
+    // the 5120 features of a 13B/TP4 layer) leaves most CUs waiting for the few that got two, and its cost
+    // grows with the tokens (every workgroup reads all of A); from 9 tokens on the K-sliced tiles do better
+    // there: 13B/TP4 forward of 12 tokens 2.88 -> 2.72 ms, of 16 tokens 3.16 -> 2.78 ms (8 tokens: 2.69 either way).
+    const int rs_wgs = ((g.N + 15) / 16) * g.parts;
+    const bool rs_poor = g.M > 8 && g.partial && rs_wgs > 256 && rs_wgs * 10 < 512 * 7;
+    if (g.M <= 16 && g.K >= 4096 && !rs_poor) return launch_rowstream(g, epi, s);   // long rows: row-contiguous reads pay
     if (n_total > 16384) return launch_config(g.M <= 32 ? 7 : 6, g, epi, s);
-    if (g.M > 16 && g.partial) {                        // LDS-staged tiles, K split across workgroups
+    if ((g.M > 16 || rs_poor) && g.partial) {                        // LDS-staged tiles, K split across workgroups
       const int cfg = g.M <= 32 ? 7 : 6;
       const int splits = choose_splits(g, cfg == 6 ? 64 : 32, cfg == 6 ? 64 : 128, partial_floats);
       if (splits > 1) return launch_splitk(g, cfg, splits, epi, s, defer);

@@ -319,6 +319,24 @@ def test_layernorm_finishing_split_products_changes_no_bit(hidden, heads):
         rig.close()
 
 
+@pytest.mark.parametrize("tokens", [(1, 8), (1, 9), (1, 12), (2, 8)])
+def test_a_few_tokens_on_a_layer_of_5120_features(tokens):
+    """One layer of the 13B/TP4 shape: 5120 output features are 320 row-stream workgroups for 256 CUs, where
+    from 9 tokens on fc1 and fc2 go to K-sliced tiles while q|k|v (240 workgroups) stays with the row-stream
+    kernel; 8 tokens use it throughout.  Every mix within the bar and the same bits when repeated."""
+    desc = ShardDesc(1, 5120, 20480, 40, vocab=512, max_pos=40, tp=4, rank=2)
+    rig = Rig([desc], max_tokens=64)
+    try:
+        m = rig.add(desc, seed=250)
+        b, s_ = tokens
+        ids = token_ids(251 + b * s_, b, s_, desc.vocab)
+        got = rig.ctx.infer(m, ids)
+        assert_close(got, oracle_logits(rig, m, desc, ids), f"{b} x {s_}")
+        assert np.array_equal(got, rig.ctx.infer(m, ids))
+    finally:
+        rig.close()
+
+
 def test_degenerate_shapes_no_layers_single_token():
     """A model without decoder layers (embeddings, final LayerNorm and head only) and a one-token request:
     the smallest things the path can be asked for; empty batches are refused."""
