@@ -52,18 +52,3 @@ class DeviceImage:
         for src, dst in zip(self.tensors, host):
             as_bytes(dst)[:] = src
         self.resident = False
-
-
-def checksum64(t: np.ndarray) -> int:
-    """Order-sensitive 64-bit checksum (FNV-1a over 8-byte words) for logs."""
-    b = as_bytes(t)
-    pad = (-b.size) % 8
-    if pad:
-        b = np.concatenate([b, np.zeros(pad, dtype=np.uint8)])
-    words = b.view(np.uint64)
-    h = np.uint64(0xCBF29CE484222325)
-    prime = np.uint64(0x100000001B3)
-    with np.errstate(over="ignore"):
-        for w in words[: 1 << 16]:  # logs only: bounded prefix
-            h = (h ^ w) * prime
-    return int(h)

@@ -10,7 +10,7 @@ import pytest
 torch = pytest.importorskip("torch")
 import paper_2306_13835_amd as P
 from oracle import opt_shard as O
-from oracle.swap import as_bytes
+from oracle.swap import DeviceImage, as_bytes
 from synth import CONFIGS, ShardDesc, token_ids, shard_bytes
 from gpu_util import Rig, errors
 
@@ -130,29 +130,97 @@ def test_infer_under_eviction_pressure_matches_oracle():
         rig.close()
 
 
+def device_copy_equals_image(rig, m, img):
+    """Every tensor read back from the arena equals the oracle's device image, byte for byte."""
+    for i in range(len(rig.tensors[m])):
+        got = rig.ctx.debug_read_param(m, i)
+        assert np.array_equal(as_bytes(got), img.tensors[i]), f"device copy of tensor {i} differs"
+
+
+def scribble(tensors, value=0xA5):
+    for t in tensors:
+        as_bytes(t)[:] = value
+
+
+def host_equals_image(tensors, img):
+    for i, t in enumerate(tensors):
+        assert np.array_equal(as_bytes(t), img.tensors[i]), f"host tensor {i} differs after swap-out"
+
+
 def test_opt125m_swap_in_forward_swap_out_verify():
+    """The first benchmark configuration as stated: swap in all 196 tensors, forward 1 x 8, swap out, then
+    compare every tensor byte for byte (the host copies are overwritten first, so the bytes must have crossed
+    the link twice)."""
     c = CONFIGS["opt125m_tp1"]
     desc = c["desc"]
-    rig = Rig([desc], max_tokens=c["batch"] * c["seq"])
+    rig = Rig([desc], max_tokens=c["batch"] * c["seq"], gap=4096)
     try:
         m = rig.add(desc, seed=c["wseed"])
-        orig_sum = [int(as_bytes(t).astype(np.uint64).sum()) for t in rig.tensors[m]]
+        assert len(rig.tensors[m]) == 196
+        img = DeviceImage([t.nbytes for t in rig.tensors[m]])
+        img.swap_in(rig.tensors[m])
         ids = token_ids(c["idseed"], c["batch"], c["seq"], desc.vocab)
+        want = oracle_logits(rig, m, desc, ids)
+        rig.arena.fill_(0x7E)
+        torch.cuda.synchronize()
         rig.ctx.swap_in(m); rig.ctx.wait(m)
+        device_copy_equals_image(rig, m, img)
         got = rig.ctx.infer(m, ids)
-        assert_close(got, oracle_logits(rig, m, desc, ids), "opt125m")
-        for t in rig.tensors[m][:6]:
-            as_bytes(t)[:] = 0
+        assert_close(got, want, "opt125m")
+        scribble(rig.tensors[m])
         rig.ctx.swap_out(m); rig.ctx.wait(m)
-        assert [int(as_bytes(t).astype(np.uint64).sum()) for t in rig.tensors[m]] == orig_sum
+        host_equals_image(rig.tensors[m], img)
     finally:
         rig.close()
 
 
-@pytest.mark.parametrize("name,rows", [("opt1.3b_tp1", [0, 5]), ("opt6.7b_tp2", [3]), ("opt13b_tp4", [7])])
-def test_full_size_shards_sampled_batch_rows(name, rows):
-    """Full benchmark shapes, pipelined demand-paged inference exactly as bench.py runs it;
-    the oracle evaluates a sample of the batch rows (rows do not interact)."""
+def test_opt1_3b_twenty_swap_cycles_every_mode_then_all_tensors():
+    """The second benchmark configuration as stated: 20 swap-in / swap-out cycles of the 1.3B shard (the three
+    transfer modes in turn), a forward pass of 8 x 128 tokens on the way, then all 388 tensors byte for byte.
+    Every cycle overwrites a twentieth of the host tensors while the shard is on the device (all of them in the
+    last cycle), so stale host bytes cannot pass for a swap-out; the device copy is read back in three cycles."""
+    c = CONFIGS["opt1.3b_tp1"]
+    desc, batch, seq = c["desc"], c["batch"], c["seq"]
+    rig = Rig([desc], max_tokens=batch * seq, mode=P.XFER_AUTO, gap=4096)
+    try:
+        m = rig.add(desc, seed=c["wseed"])
+        host = rig.tensors[m]
+        assert len(host) == 388
+        img = DeviceImage([t.nbytes for t in host])
+        img.swap_in(host)
+        ids = token_ids(c["idseed"], batch, seq, desc.vocab)
+        rows = [1, 6]
+        want = oracle_logits(rig, m, desc, ids[rows])
+        rig.arena.fill_(0x7E)
+        torch.cuda.synchronize()
+        modes = (P.XFER_KERNEL, P.XFER_DMA, P.XFER_AUTO)
+        for cycle in range(20):
+            rig.ctx.set_mode(modes[cycle % 3], True)
+            rig.ctx.swap_in(m); rig.ctx.wait(m)
+            assert rig.ctx.is_resident(m)
+            if cycle in (0, 7, 19):
+                device_copy_equals_image(rig, m, img)
+            if cycle == 10:
+                got = rig.ctx.infer(m, ids)
+                assert_close(got[rows], want, "opt1.3b inside the swap cycles")
+            scribble(host if cycle == 19 else host[cycle::20], 0xA5 if cycle % 2 else 0x00)
+            rig.ctx.swap_out(m); rig.ctx.wait(m)
+            assert not rig.ctx.is_resident(m)
+            print(f"cycle {cycle} mode {modes[cycle % 3]} done", flush=True)
+        host_equals_image(host, img)
+        st = rig.ctx.stats()
+        assert st["bytes_h2d"] == st["bytes_d2h"] == 20 * shard_bytes(desc)
+        assert st["n_swap_in"] == st["n_swap_out"] == 20
+    finally:
+        rig.close()
+
+
+@pytest.mark.parametrize("name", ["opt1.3b_tp1", "opt6.7b_tp2", "opt13b_tp4"])
+def test_full_size_shards_every_tensor_every_batch_row(name):
+    """Full benchmark shapes, pipelined demand-paged inference exactly as bench.py runs it.  The oracle
+    evaluates every batch row (so every M tile of every product is compared); the device copy of every tensor
+    is compared with the oracle's image after the pipelined load, and every host tensor after a swap-out that
+    follows an overwrite of all of them."""
     c = CONFIGS[name]
     desc, batch, seq = c["desc"], c["batch"], c["seq"]
     # bench.py's own configuration: library-owned CU-partitioned streams, transfer mode AUTO, every host
@@ -161,7 +229,10 @@ def test_full_size_shards_sampled_batch_rows(name, rows):
     try:
         t0 = time.time()
         m = rig.add(desc, seed=c["wseed"])
-        print(f"{name}: weights in {time.time() - t0:.1f}s", flush=True)
+        host = rig.tensors[m]
+        img = DeviceImage([t.nbytes for t in host])
+        img.swap_in(host)
+        print(f"{name}: weights and oracle image in {time.time() - t0:.1f}s", flush=True)
         ids = token_ids(c["idseed"], batch, seq, desc.vocab)
         rig.arena.fill_(0x7E)
         torch.cuda.synchronize()
@@ -169,18 +240,19 @@ def test_full_size_shards_sampled_batch_rows(name, rows):
         rig.ctx.infer(m, ids, out=out)               # not resident: layer-pipelined swap-in + forward
         rig.ctx.sync()
         got = out.cpu().numpy()
-        t0 = time.time()
-        want = oracle_logits(rig, m, desc, ids[rows])
-        print(f"{name}: oracle rows {rows} in {time.time() - t0:.1f}s", flush=True)
-        assert_close(got[rows], want, name)
         assert np.isfinite(got).all()
-        # spot-check the device copy of a few tensors, then a real swap-out
-        for i in (0, 1, 4, len(rig.tensors[m]) - 3):
-            assert np.array_equal(rig.ctx.debug_read_param(m, i), rig.tensors[m][i])
-        keep = rig.tensors[m][4].copy()
-        rig.tensors[m][4][:] = 0
+        for r0 in range(0, batch, 4):                # the oracle in slices of four rows, so progress shows
+            rows = list(range(r0, min(batch, r0 + 4)))
+            t0 = time.time()
+            want = oracle_logits(rig, m, desc, ids[rows])
+            print(f"{name}: oracle rows {rows} in {time.time() - t0:.1f}s", flush=True)
+            assert_close(got[rows], want, f"{name} rows {rows}")
+        device_copy_equals_image(rig, m, img)
+        print(f"{name}: device copy of all {len(host)} tensors equals the image", flush=True)
+        scribble(host)
         rig.ctx.swap_out(m); rig.ctx.wait(m)
-        assert np.array_equal(rig.tensors[m][4], keep)
+        host_equals_image(host, img)
+        print(f"{name}: all {len(host)} host tensors restored by the swap-out", flush=True)
     finally:
         rig.close()
 
