@@ -405,6 +405,18 @@ int ctn_op_gemm(const void* A_f16, const void* W_f16, const void* bias_f16, void
 int ctn_op_gemm_ws(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,
                    int32_t N, int32_t K, int32_t epilogue, void* workspace, uint64_t workspace_bytes,
                    void* stream);
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): ctn_op_gemm_ws with the scratch buffer taken from a static device
+ * array of ctn_static_scratch_bytes() (64 MiB) that every GPU the library runs on holds until the process
+ * ends.  Calls no hipMalloc / hipFree and no allocating routine.  The product may be cut into up to 16
+ * K slices (M <= 256) or 4 (larger M); shapes whose slices would not fit, 4*M*N*16 (M <= 256) or 4*M*N*4
+ * bytes beyond the array's size, return CTN_E_TOO_BIG.  Results equal ctn_op_gemm_ws with a workspace of
+ * the same size, bit for bit.  All calls on one GPU share the array (every slice is written before it is
+ * read, so stale contents do no harm): two calls that overlap in time on one GPU, on different streams
+ * or from different threads, race; calls on one stream are ordered. */
+int ctn_op_gemm_static(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,
+                       int32_t N, int32_t K, int32_t epilogue, void* stream);
+uint64_t ctn_static_scratch_bytes(void);
 /* Test and tuning hook, process wide: forces tile configuration cfg on every product of ctn_op_gemm and
  * ctn_infer; -1 restores the library's choice.
  *   0        128x128x64 tiles, filled straight from global memory into LDS when K is a multiple of 64

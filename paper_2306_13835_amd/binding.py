@@ -23,7 +23,7 @@ DECLARED_SYMBOLS = [
     "ctn_slot_bytes", "ctn_resident_blocks", "ctn_get_block_events", "ctn_block_residency_replay",
     "ctn_engine_set_prefetch", "ctn_engine_idle", "ctn_predictor_replay", "ctn_infer_stage",
     "ctn_engine_create_async", "ctn_engine_dispatch", "ctn_engine_lanes", "ctn_engine_replay_async",
-    "ctn_set_discard",
+    "ctn_set_discard", "ctn_op_gemm_static", "ctn_static_scratch_bytes",
 ]
 
 
@@ -128,6 +128,8 @@ def lib() -> C.CDLL:
         "ctn_op_gemm": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, vp]),
         "ctn_op_gemm_ws": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, vp, u64, vp]),
         "ctn_op_attention": (C.c_int, [vp, vp, i32, i32, i32, i32, vp]),
+        "ctn_op_gemm_static": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, vp]),
+        "ctn_static_scratch_bytes": (u64, []),
         "ctn_debug_gemm_tile": (C.c_int, [i32]),
         "ctn_engine_create": (C.c_int, [vp, i32, i32, P(vp)]),
         "ctn_engine_destroy": (C.c_int, [vp]),
@@ -555,6 +557,16 @@ def op_gemm_ws(A, W, bias, out, M, N, K, epilogue, workspace, stream):
     nbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _op(lib().ctn_op_gemm_ws(_addr(A), _addr(W), _addr(bias), _addr(out), M, N, K, epilogue, _addr(workspace), nbytes,
                              stream.cuda_stream), "ctn_op_gemm_ws")
+
+
+def op_gemm_static(A, W, bias, out, M, N, K, epilogue, stream):
+    """ctn_op_gemm_ws with the library's static scratch array: allocates nothing."""
+    _op(lib().ctn_op_gemm_static(_addr(A), _addr(W), _addr(bias), _addr(out), M, N, K, epilogue, stream.cuda_stream),
+        "ctn_op_gemm_static")
+
+
+def static_scratch_bytes() -> int:
+    return int(lib().ctn_static_scratch_bytes())
 
 
 def op_attention(qkv, out, batch, seq, heads, head_dim, stream):

@@ -14,6 +14,7 @@
 #include <cstdio>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -25,7 +26,37 @@
 
 using namespace ctn;
 
+// Scratch for ctn_op_gemm_static: callers that must not allocate (HIP graph capture, tight serving
+// loops) get the split-K partial tiles from this array instead of a workspace of their own.  Every
+// device the library runs on holds its own copy until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress: kernels receive the looked-up device address.
+constexpr uint64_t kStaticScratchBytes = 64ull << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, once looked up
+
+// Device address of the static scratch array on the current device (looked up once per device,
+// with that device current).  hipSuccess and *out set, or the failing HIP status.
+hipError_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 struct PendingRelease {   // arena range given back by an eviction whose offload may still be copying
   uint64_t off, len;
@@ -675,6 +706,15 @@ int ctn_create(const ctn_config* cfg, ctn_ctx** out) {
     return CTN_E_INVAL;
   int n_dev = 0;
   if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev < 1) return CTN_E_HIP;   // no silent fallback
+  {   // the static scratch array's address on this device, for ctn_op_gemm_static
+    void* sp = nullptr;
+    const hipError_t e = static_scratch(&sp);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      g_last_hip = (int)e;
+      return CTN_E_HIP;
+    }
+  }
   ctn_ctx* c = new (std::nothrow) ctn_ctx();
   if (!c) return CTN_E_NOMEM;
   c->cfg = *cfg;
@@ -1527,6 +1567,26 @@ int ctn_op_gemm_ws(const void* A, const void* W, const void* bias, void* out, in
                            static_cast<const _Float16*>(bias), out, M, N, K, epilogue,
                            static_cast<hipStream_t>(stream), static_cast<float*>(workspace), workspace_bytes / 4));
 }
+
+int ctn_op_gemm_static(const void* A, const void* W, const void* bias, void* out, int32_t M, int32_t N, int32_t K,
+                       int32_t epilogue, void* stream) {
+  if (!A || !W || !out || M < 0 || N < 0) return CTN_E_INVAL;
+  // room for the largest number of K slices a product of this shape may be cut into
+  const uint64_t need = 4ull * static_cast<uint64_t>(M) * static_cast<uint64_t>(N) * (M <= 256 ? 16u : 4u);
+  if (need > kStaticScratchBytes) return CTN_E_TOO_BIG;
+  void* sp = nullptr;
+  const hipError_t e = static_scratch(&sp);      // cached after the first call on a device; allocates nothing
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    g_last_hip = (int)e;
+    return CTN_E_HIP;
+  }
+  return op_rc(launch_gemm(static_cast<const _Float16*>(A), static_cast<const _Float16*>(W),
+                           static_cast<const _Float16*>(bias), out, M, N, K, epilogue,
+                           static_cast<hipStream_t>(stream), static_cast<float*>(sp), kStaticScratchBytes / 4));
+}
+
+uint64_t ctn_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int ctn_debug_gemm_tile(int32_t cfg) { return gemm_force_tile(cfg) == 0 ? CTN_OK : CTN_E_INVAL; }
 
