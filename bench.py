@@ -84,7 +84,7 @@ def measure_link_peak(torch, P, B, pool_bytes=1 << 30, reps=10):
     return out
 
 
-MODES = {"dma": 0, "kernel": 1, "auto": 2}
+MODES = {"dma": 0, "kernel": 1, "auto": 2, "dma_in_kernel_out": 3, "kernel_in_dma_out": 4, "dma_runs": 5}
 GAP = 4096   # bytes between host tensors in the "separate" layout
 
 
@@ -107,6 +107,37 @@ def measure_bidir_peak(torch, P, B, ctx, nbytes=1 << 29, reps=5):
     del d1, d2
     pool.close()
     return {"h2d": median([r[0] for r in res]), "d2h": median([r[1] for r in res])}
+
+
+def fit_alpha_beta(torch, P, B, stream, sizes=(4 << 10, 64 << 10, 1 << 20, 8 << 20, 32 << 20, 64 << 20)):
+    """Section 5.1's message cost T(n) = alpha + beta * n, fitted for single host -> device messages of n bytes:
+    one hipMemcpyAsync per message (what a per-tensor swap pays for each tensor) and one copy-kernel launch
+    per message (what the per-block launch pays once for up to 16 tensors).  Every size is timed with HIP
+    events over a run of back-to-back messages on one stream; least squares on relative error."""
+    pool = P.HostPool(2 * max(sizes) + 8192)
+    h = pool.take((2 * max(sizes),), np.uint8)
+    h[:] = 5
+    d = torch.empty(2 * max(sizes), dtype=torch.uint8, device="cuda")
+    out = {}
+    for name, send in (("dma_message", lambda n, off: B.op_dma(d.data_ptr() + off, h.ctypes.data + off, n, stream)),
+                       ("kernel_launch", lambda n, off: B.op_copy(d.data_ptr() + off, h.ctypes.data + off, n, 32, stream))):
+        ts = []
+        for n in sizes:
+            k = 40 if n <= (1 << 20) else 6
+            offs = [(i % 2) * max(sizes) for i in range(k)]
+            send(n, 0)
+            stream.synchronize()
+            best = min(ev_time(torch, stream, lambda: [send(n, o) for o in offs]) for _ in range(3)) / k   # ms
+            ts.append(best * 1e-3)
+        n_arr, t_arr = np.array(sizes, dtype=np.float64), np.array(ts)
+        A = np.stack([np.ones_like(n_arr), n_arr], axis=1) / t_arr[:, None]      # relative-error weighting
+        (alpha, beta), *_ = np.linalg.lstsq(A, np.ones_like(t_arr), rcond=None)
+        out[name] = {"alpha_us": round(float(alpha) * 1e6, 2), "beta_ns_per_KiB": round(float(beta) * 1024e9, 3),
+                     "asymptotic_gbps": round(1e-9 / float(beta), 2),
+                     "per_message_us": {str(n): round(t * 1e6, 2) for n, t in zip(sizes, ts)}}
+    del d
+    pool.close()
+    return out
 
 
 def run_swap(args):
@@ -133,7 +164,7 @@ def run_swap(args):
     torch.cuda.synchronize()
     # library-owned streams: one hardware queue and a private set of compute units per direction
     ctx = P.Context(nbytes, arena, ws, transfer_mode=P.XFER_KERNEL, pipeline=True,
-                    copy_blocks=args.copy_blocks, copy_cus=args.copy_cus)
+                    copy_blocks=args.copy_blocks, copy_cus=args.copy_cus, copy_waves_out=args.copy_waves_out)
     s_c = ctx.stream_compute
     # Host parameter store.  "separate": every tensor is its own pinned region with a gap before
     # the next one, as individually allocated parameter tensors are (the paper's per-tensor
@@ -232,13 +263,18 @@ def run_swap(args):
     ctx.swap_out(models[0]); ctx.wait(models[0])
     ctx.sync()
 
-    # the same alternation with every load and offload through the copy kernel (--transfer kernel); AUTO, the
-    # default, offloads by DMA and moves loads to the DMA engines too while earlier offloads are still running:
-    # kernel-issued host reads lose rate against concurrent writes to the host
-    if args.transfer != "kernel":
-        ctx.set_mode(MODES["kernel"], True, args.copy_blocks)
-        w_kern, _ = alternate(models, 4, 2)
-        side["kernel_loads_ms_per_step"] = w_kern / 4 * 1e3
+    # the same alternation on the other transfer paths, for the comparison of the copy kernel with the DMA engines:
+    # one hipMemcpyAsync per run of adjacent tensors, one per tensor (the paper's per-tensor messages), and the
+    # copy kernel at full width in both directions (AUTO narrows the offload's kernel)
+    side["paths"] = {}
+    for alt, mode, waves_out in (("dma_runs", "dma_runs", 0), ("dma_per_tensor", "dma", 0),
+                                 ("kernel_both_ways_full_width", "kernel", 0), ("kernel_both_ways_offload_8_waves", "kernel", 8)):
+        ctx.set_mode(MODES[mode], True, args.copy_blocks)
+        ctx.set_copy_width(args.copy_blocks, waves_out)
+        w_alt, lat_alt = alternate(models, 4, 2)
+        side["paths"][alt] = {"ms_per_step": round(w_alt / 4 * 1e3, 3), "value_gbps": round(4 * nbytes / w_alt / 1e9, 3),
+                              "step_latencies_ms": [round(x, 1) for x in lat_alt]}
+    ctx.set_copy_width(args.copy_blocks, args.copy_waves_out)
 
     # the same alternation if evictions only freed the device copy (parameters are read-only on the device);
     # an option, off by default: the paper's swap-out is a real copy and so is the timed region's
@@ -269,12 +305,13 @@ def run_swap(args):
         in_ms.append(i_ms)
         out_ms.append(o_ms)
         timed_blocks.append(list(blocks))
-    loads_by_kernel = args.transfer == "kernel"   # "auto" switches to DMA while earlier offloads are running
-    if loads_by_kernel:
-        roof_blocks, roof_where = timed_blocks, "timed region (last load of each model)"
-    else:
-        roof_blocks, roof_where = side["blocks_kernel"], "kernel-mode loads of this run outside the timed region " \
-                                                          "(the timed region's loads went through the DMA engines)"
+    # AUTO on a host list in separate pieces: a miss that evicts loads through the DMA engines (one copy per run)
+    # while its victim's offload goes through the copy kernel; a packed list takes DMA copies both ways
+    loads_by_kernel = args.transfer in ("kernel", "kernel_in_dma_out")
+    offloads_by_kernel = args.transfer in ("kernel", "dma_in_kernel_out") or \
+        (args.transfer == "auto" and args.host_layout == "separate")
+    roof_blocks = timed_blocks
+    roof_where = "timed region: the last load of each of the two models (2 x %d launches)" % len(block_bytes)
     launch_ms = [d for blocks in roof_blocks for d in np.diff([0.0] + blocks)]
     avg_launch_ms = float(np.mean(launch_ms))
     avg_launch_bytes = float(np.mean(block_bytes))
@@ -307,15 +344,76 @@ def run_swap(args):
 
     value = args.steps * nbytes / wall / 1e9
     flop = forward_flop(desc, batch, seq)
+    ms_step = wall / args.steps * 1e3
+    n_launch = len(block_bytes)
+    link_note = ("measured: median 1 GiB hipMemcpyAsync pinned<->HBM in this run, one direction at a time "
+                 f"(PCIe Gen5 x16 nominal {PCIE5_X16_NOMINAL_GBPS} GB/s; HBM peak {HBM_PEAK_GBPS} GB/s is not the bound)")
+    if loads_by_kernel:
+        roofline = {
+            "kernel": "copy_table_kernel<0, 256> (host -> HBM, one launch per transfer block)",
+            "bound": "host_link", "achieved": round(achieved, 3), "peak": round(link["h2d"], 3), "unit": "GB/s",
+            "frac": round(achieved / link["h2d"], 4),
+            "traffic": sum(COPY_KERNEL_TRAFFIC[args.config].values()) if args.config in COPY_KERNEL_TRAFFIC else None,
+            "traffic_detail": dict(COPY_KERNEL_TRAFFIC.get(args.config, {}),
+                                   note="per layer-block launch: bytes loaded over the host link + bytes stored to HBM; "
+                                        "algorithmic = 201,404,416 each"),
+            "peak_source": link_note,
+            "bytes_per_launch": avg_launch_bytes, "avg_launch_ms": round(avg_launch_ms, 4),
+            "launches_timed": len(launch_ms), "measured_over": roof_where,
+            "note": "every launch of the timed region runs beside an offload on the link's other direction; alone the "
+                    "same kernel reaches isolated.swap_in_gbps_kernel",
+        }
+    else:
+        roofline = {
+            "kernel": "hipMemcpyAsync host -> HBM (DMA engines / the runtime's copy shader), not a kernel of this library",
+            "bound": "host_link", "achieved": round(achieved, 3), "peak": round(link["h2d"], 3), "unit": "GB/s",
+            "frac": round(achieved / link["h2d"], 4), "traffic": None, "peak_source": link_note,
+            "bytes_per_launch": avg_launch_bytes, "avg_launch_ms": round(avg_launch_ms, 4),
+            "launches_timed": len(launch_ms), "measured_over": roof_where + " (per transfer block: its copies together)",
+        }
+    out_launch_ms = float(np.mean(out_ms)) / n_launch
+    roofline_out = {
+        "kernel": ("copy_table_kernel<1, 256> (HBM -> host, one launch per transfer block)" if offloads_by_kernel
+                   else "hipMemcpyAsync HBM -> host, not a kernel of this library"),
+        "bound": "host_link", "achieved": round(avg_launch_bytes / out_launch_ms / 1e6, 3), "peak": round(link["d2h"], 3),
+        "unit": "GB/s", "frac": round(avg_launch_bytes / out_launch_ms / 1e6 / link["d2h"], 4), "traffic": None,
+        "bytes_per_launch": avg_launch_bytes, "avg_launch_ms": round(out_launch_ms, 4), "launches_timed": 2 * n_launch,
+        "measured_over": "timed region: the last offload of each of the two models, start event to end event over its "
+                         f"{n_launch} back-to-back launches",
+        "peak_source": link_note,
+        "note": "every launch of the timed region runs beside a load on the link's other direction (both at once the link "
+                "carries link_peak_both_directions_gbps); alone the same kernel reaches isolated.swap_out_gbps_kernel",
+    }
+    # Every step moves the shard once in each direction.  With both directions busy the link carries less
+    # per direction than alone (link_peak_both_directions_gbps, large DMA copies): the step cannot be shorter
+    # than the slower direction's share of it.
+    slow = min(bidir["h2d"], bidir["d2h"])
+    two_way = {"bytes_each_way_per_step": nbytes, "slower_direction_gbps_under_two_way_dma": round(slow, 3),
+               "bound_ms_per_step": round(nbytes / slow / 1e6, 3), "ms_per_step": round(ms_step, 3),
+               "frac": round(nbytes / slow / 1e6 / ms_step, 4)}
+    kt = side["paths"]["kernel_both_ways_offload_8_waves"]
+    kernel_throughout = {"note": "the timed workload with every load and offload through the copy kernel (loads 128 "
+                                 "wavefronts wide, offloads 8), none through the DMA engines",
+                         "ms_per_step": kt["ms_per_step"], "value_gbps": kt["value_gbps"],
+                         "over_headline_ms": round(kt["ms_per_step"] / ms_step, 4)}
+    alpha_beta = fit_alpha_beta(torch, P, B, sg)
+    # what the fitted model predicts for this shard's swap-in, against what was measured alone on the link
+    ab_d, ab_k = alpha_beta["dma_message"], alpha_beta["kernel_launch"]
+    alpha_beta["shard_swap_in_ms"] = {
+        "per_tensor_dma_model": round(n_t * ab_d["alpha_us"] * 1e-3 + nbytes / ab_d["asymptotic_gbps"] / 1e6, 2),
+        "per_tensor_dma_measured": round(side["swap_in_ms_dma"], 2),
+        "per_block_kernel_model": round(n_launch * ab_k["alpha_us"] * 1e-3 + nbytes / ab_k["asymptotic_gbps"] / 1e6, 2),
+        "per_block_kernel_measured": round(side["swap_in_ms_kernel"], 2),
+        "messages": {"per_tensor_dma": n_t, "per_block_kernel": n_launch}}
     result = {
         "metric": "host->HBM swap-in GB/s (demand-paged requests, swap-out overlapped, forward pipelined)",
         "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(wall / args.steps * 1e3, 3), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{args.config} shard x2 models, budget 1 resident, alternating blocking requests, "
                                f"batch {batch} x seq {seq}", "shard_bytes": nbytes, "tensors": n_t,
                    "transfer": args.transfer, "host_layout": args.host_layout, "pipeline": "per-layer events",
-                   "copy_blocks": args.copy_blocks, "copy_cus": args.copy_cus},
+                   "copy_blocks": args.copy_blocks, "copy_cus": args.copy_cus, "copy_waves_out": args.copy_waves_out},
         "swap_in_gbps_device_timeline": round(nbytes / median(in_ms) / 1e6, 3),
         "shard_load_latency_s": round(median(in_ms) / 1e3, 5),
         "first_token_latency_ms_p50": round(median(lat), 3),
@@ -345,19 +443,10 @@ def run_swap(args):
                            "traffic": SMALL_REQUEST_FETCH.get(args.config, {}).get(t)}
                 for t in (8, 64) if f"forward_resident_1x{t}_ms" in side},
         },
-        "roofline": {
-            "kernel": "copy_table_kernel<0> (host -> HBM, one launch per transfer block)",
-            "bound": "host_link", "achieved": round(achieved, 3), "peak": round(link["h2d"], 3), "unit": "GB/s",
-            "frac": round(achieved / link["h2d"], 4),
-            "traffic": sum(COPY_KERNEL_TRAFFIC[args.config].values()) if args.config in COPY_KERNEL_TRAFFIC else None,
-            "traffic_detail": dict(COPY_KERNEL_TRAFFIC.get(args.config, {}),
-                                   note="per layer-block launch: bytes loaded over the host link + bytes stored to HBM; "
-                                        "algorithmic = 201,404,416 each"),
-            "peak_source": "measured: median 1 GiB hipMemcpyAsync pinned->HBM in this run "
-                           f"(PCIe Gen5 x16 nominal {PCIE5_X16_NOMINAL_GBPS} GB/s; HBM peak {HBM_PEAK_GBPS} GB/s is not the bound)",
-            "bytes_per_launch": avg_launch_bytes, "avg_launch_ms": round(avg_launch_ms, 4),
-            "launches_timed": len(launch_ms), "measured_over": roof_where,
-        },
+        "roofline": roofline_out if (offloads_by_kernel and not loads_by_kernel) else roofline,
+        "roofline_load": roofline,
+        "roofline_offload": roofline_out,
+        "link_bound_two_way": two_way,
         "roofline_gemm": {
             "kernel": f"gemm_dma_kernel<1> (128x128x64 tiles) fc1 shape M={gM} N={gN} K={gK}, bias+ReLU epilogue",
             "bound": "mfma", "achieved": round(gemm_tflops, 2), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -376,11 +465,12 @@ def run_swap(args):
             "traffic": LAYERNORM_TRAFFIC.get(args.config), "algorithmic_bytes": ln_bytes,
             "avg_launch_ms": round(lms, 5), "launches_timed": lreps,
         },
-        "kernel_transfers_throughout": ({"note": "the timed workload with --transfer kernel: every load and offload "
-                                                 "through the copy kernel, none through the DMA engines",
-                                         "ms_per_step": round(side["kernel_loads_ms_per_step"], 3),
-                                         "value_gbps": round(nbytes / side["kernel_loads_ms_per_step"] / 1e6, 3)}
-                                        if "kernel_loads_ms_per_step" in side else None),
+        "transfer_paths_compared": dict(side["paths"], note="the timed workload, 4 steps each, on the other transfer paths "
+                                        "(dma_runs: one hipMemcpyAsync per run of adjacent tensors in both directions; dma_per_tensor: "
+                                        "the paper's per-tensor messages; kernel_both_ways: the copy kernel for loads and offloads); "
+                                        f"the timed region ran '{args.transfer}'"),
+        "kernel_transfers_throughout": kernel_throughout,
+        "alpha_beta_fit": alpha_beta,
         "other_host_layout": {
             "layout": "packed" if args.host_layout == "separate" else "separate",
             "ms_per_step": round(side["other_layout_ms_per_step"], 3),
@@ -390,9 +480,35 @@ def run_swap(args):
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(tensors[0], ids[0], desc, nbytes)
     ctx.close()
-    del tensors
+    del tensors, sep, packed, primary, other, arena, ws, logits
     pool.close()
+    torch.cuda.empty_cache()
+    if args.serve_requests > 0:
+        result["serving"] = serving_leg(args)
     print(json.dumps(result), flush=True)
+
+
+def serving_leg(args):
+    """The second half of the metric, p99 request latency under swap, on a bounded prefix of the serving
+    workload (8 shards of the opt6.7b TP=2 shape, budget 20e9 B, Gamma CV 4 / Zipf 1.5 arrivals at 20
+    requests/s, 1 x 64 tokens): the paper's engine as it stands (serial, oldest first, whole-model LRU) and
+    this library's asynchronous two-lane engine with residency per transfer block."""
+    from paper_2306_13835_amd.serve_bench import serve_setup, serve_once
+    c, pool, keep = serve_setup(args.host_layout)
+    n_req = min(args.serve_requests, c["n_requests"])
+    out = {"workload": f"serve8x6.7b_tp2 reduced to the first {n_req} of {c['n_requests']} requests of the seeded trace "
+                       f"(8 shards, budget {c['budget']} B, real-time open-loop replay)", "requests": n_req}
+    keys = ("latency_s", "misses", "hit_ratio", "partial_misses", "decisions_equal_policy_replay", "service_ms",
+            "bytes_swapped_in", "wall_seconds", "trace_seconds")
+    for name, kw in (("serial_engine_whole_models", {}), ("two_lane_engine_block_residency", {"blocks": True, "two_lanes": True})):
+        log(f"[bench] serving leg: {name}, {n_req} requests")
+        r = serve_once(c, keep, n_req, args.transfer, args.host_layout, **kw)
+        out[name] = {k: r[k] for k in keys}
+        out[name]["p99_latency_s"] = r["latency_s"]["p99"]
+        out[name]["p50_latency_s"] = r["latency_s"]["p50"]
+    del keep
+    pool.close()
+    return out
 
 
 def run_counters(args):
@@ -439,27 +555,30 @@ def cpu_baseline(tensors, ids, desc, nbytes):
     from oracle.swap import DeviceImage           # oracle use is confined to this baseline leg
     from oracle import opt_shard as O
     cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
-    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+    blas_threads = None
+    try:                                          # the threads numpy's BLAS really uses for the oracle's matmuls
+        from threadpoolctl import threadpool_info
+        blas_threads = max([int(p.get("num_threads", 0)) for p in threadpool_info() if p.get("user_api") == "blas"] or [0]) or None
+    except Exception:
+        pass
     img = DeviceImage([t.nbytes for t in tensors])
     t = time.perf_counter(); img.swap_in(tensors); t_in = time.perf_counter() - t
-    first = 2 if desc.has_embed else 0                      # the first decoder layer's 16 tensors
-    scratch = [np.empty_like(x) for x in tensors[first:first + 16]]
-    t = time.perf_counter()
-    img2 = DeviceImage([x.nbytes for x in scratch]); img2.swap_in(tensors[first:first + 16]); img2.swap_out(scratch)
-    t_layer = (time.perf_counter() - t) / 2
-    t_out = t_layer * nbytes / sum(x.nbytes for x in scratch)      # swap-out extrapolated from one layer block
-    del img, img2, scratch
+    back = [np.empty_like(x) for x in tensors]    # the whole shard back into host tensors of the same sizes
+    t = time.perf_counter(); img.swap_out(back); t_out = time.perf_counter() - t
+    del img, back
     rows = [0]
     t = time.perf_counter()
     O.forward_stage(tensors, ids[rows], layers=desc.layers, heads=desc.heads, tp=desc.tp, rank=desc.rank,
                     pp=desc.pp, stage=desc.stage)
     t_fwd = (time.perf_counter() - t) * ids.shape[0] / len(rows)
     step = t_in + t_fwd + t_out
-    return {"value": round(nbytes / step / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": f"full-shard per-tensor memcpy swap-in ({t_in:.2f}s), swap-out extrapolated from one layer "
-                      f"block ({t_out:.2f}s), fp32 forward of 1 of {ids.shape[0]} batch rows x{ids.shape[0]} "
-                      f"({t_fwd:.1f}s); serial, no overlap",
-            "oracle_swap_in_gbps": round(nbytes / t_in / 1e9, 3), "oracle_forward_s": round(t_fwd, 2)}
+    return {"value": round(nbytes / step / 1e9, 4), "unit": "GB/s", "cores": blas_threads or cores, "kind": "oracle",
+            "sample": f"full-shard per-tensor memcpy swap-in ({t_in:.2f}s) and swap-out ({t_out:.2f}s), one thread; fp32 "
+                      f"forward of 1 of {ids.shape[0]} batch rows, extrapolated x{ids.shape[0]} ({t_fwd:.1f}s), "
+                      f"{blas_threads or '?'} BLAS threads; serial, no overlap",
+            "cores_note": f"threads the oracle's matrix products ran on (numpy BLAS pool); the box offers {cores} to this process",
+            "oracle_swap_in_gbps": round(nbytes / t_in / 1e9, 3), "oracle_swap_out_gbps": round(nbytes / t_out / 1e9, 3),
+            "oracle_forward_s": round(t_fwd, 2)}
 
 
 def main():
@@ -472,7 +591,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--duration", type=float, default=30.0, help="grid workload: seconds of arrivals per trial")
     ap.add_argument("--requests", type=int, default=0, help="serve workload: number of requests (0: all 2000)")
-    ap.add_argument("--transfer", choices=["auto", "kernel", "dma"], default="auto",
+    ap.add_argument("--transfer", choices=sorted(MODES), default="auto",
                     help="transfer mode of the timed region")
     ap.add_argument("--host-layout", choices=["separate", "packed"], default="separate",
                     help="how the parameter tensors lie in pinned host memory")
@@ -486,6 +605,10 @@ def main():
     ap.add_argument("--repeat", type=int, default=1, help="counters workload: number of resident forward passes")
     ap.add_argument("--copy-blocks", type=int, default=0, help="workgroups per copy kernel (0: library default)")
     ap.add_argument("--copy-cus", type=int, default=0, help="compute units reserved per transfer direction")
+    ap.add_argument("--copy-waves-out", type=int, default=0, help="wavefronts of an offload's copy kernel (0: library's choice)")
+    ap.add_argument("--serve-requests", type=int, default=400,
+                    help="swap workload: requests of the serving trace replayed after the timed region for the latency "
+                         "percentiles (0: skip that leg)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (one rank's shard of the model); "

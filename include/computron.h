@@ -50,7 +50,8 @@ enum {
   CTN_E_NOMEM = -7    /* host allocation failed / workspace too small for the library's tables */
 };
 
-enum { CTN_XFER_DMA = 0, CTN_XFER_KERNEL = 1, CTN_XFER_AUTO = 2 };
+enum { CTN_XFER_DMA = 0, CTN_XFER_KERNEL = 1, CTN_XFER_AUTO = 2,
+       CTN_XFER_DMA_IN_KERNEL_OUT = 3, CTN_XFER_KERNEL_IN_DMA_OUT = 4, CTN_XFER_DMA_RUNS = 5 };
 
 /* One rank's share of an OPT decoder.  layers, heads, ffn and vocab are those
  * of the whole model; the rank owns heads/tp heads, ffn/tp hidden units,
@@ -95,15 +96,21 @@ typedef struct {
                                 the forward pass.  Otherwise all three must be given, distinct. */
   int32_t transfer_mode;     /* CTN_XFER_DMA: one hipMemcpyAsync per tensor (the paper's per-tensor
                                 messages, Section 5.1); CTN_XFER_KERNEL: one copy kernel per layer
-                                block; CTN_XFER_AUTO: loads of a host list in many separate pieces
-                                use the copy kernel unless an earlier offload is still running or
-                                was enqueued less than two load times ago
-                                (then, and for lists whose tensors lie back to back on the host,
-                                one DMA copy per run of adjacent tensors: the DMA engines share a
-                                link that is busy in both directions more evenly); offloads use DMA */
+                                block, both directions; CTN_XFER_DMA_RUNS: one hipMemcpyAsync per run of
+                                tensors that lie back to back on the host, both directions;
+                                CTN_XFER_DMA_IN_KERNEL_OUT / CTN_XFER_KERNEL_IN_DMA_OUT: the copy kernel
+                                in one direction, one DMA copy per run in the other.
+                                CTN_XFER_AUTO, decided per miss from the context's own record and its
+                                events (never the clock): a host list in many separate pieces is loaded
+                                by the copy kernel when the link's other direction is idle (the miss
+                                evicts nothing and no earlier offload is still running), else by one DMA
+                                copy per run, with the victims' offloads going through the copy kernel
+                                at a width that keeps the two directions at the same pace; an explicit
+                                ctn_swap_out uses the copy kernel at full width; a list whose tensors
+                                lie back to back on the host takes one DMA copy per run both ways */
   int32_t pipeline;          /* 0: inference waits for the whole shard (the paper's rule, Section 3.2);
                                 1: inference waits layer by layer */
-  int32_t copy_blocks;       /* workgroups of a copy kernel; 0 = library default */
+  int32_t copy_blocks;       /* workgroups (256 threads) of a copy kernel; 0 = library default */
   int32_t copy_cus;          /* library-owned streams only: compute units reserved per transfer
                                 direction, at least 8 (one per XCD); 0 = library default */
   int32_t block_residency;   /* 0: a model is resident or not as a whole (the paper's demand paging,
@@ -118,6 +125,9 @@ typedef struct {
                                 writes parameters, so eviction only frees the device copy and the host
                                 tensors, which the caller must then leave unchanged while the model is
                                 registered, stay the single source; nothing crosses the link on swap-out. */
+  int32_t copy_waves_out;    /* wavefronts of an offload's copy kernel (a multiple of 4 runs as workgroups of
+                                256 threads, another even count as workgroups of 128, an odd count as
+                                single wavefronts); 0 = 4 * copy_blocks, as for loads */
 } ctn_config;
 
 typedef struct {
@@ -265,6 +275,9 @@ int ctn_set_graphs(ctn_ctx* ctx, int32_t enable);
 int ctn_set_discard(ctn_ctx* ctx, int32_t enable);
 /* Changes transfer mode / pipelining / copy-kernel width between operations. */
 int ctn_set_mode(ctn_ctx* ctx, int32_t transfer_mode, int32_t pipeline, int32_t copy_blocks);
+/* Width of the copy kernel between operations: workgroups (of 256 threads) for loads, wavefronts for
+ * offloads; 0 = library default / the same width as loads. */
+int ctn_set_copy_width(ctn_ctx* ctx, int32_t blocks_in, int32_t waves_out);
 /* HIP status behind the last CTN_E_HIP of this context (ctx == NULL: of calls that take no context). */
 int ctn_last_hip_error(ctn_ctx* ctx);
 const char* ctn_strerror(int code);

@@ -9,7 +9,7 @@ import numpy as np
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcomputron_mi355.so")
 
-XFER_DMA, XFER_KERNEL, XFER_AUTO = 0, 1, 2
+XFER_DMA, XFER_KERNEL, XFER_AUTO, XFER_DMA_IN_KERNEL_OUT, XFER_KERNEL_IN_DMA_OUT, XFER_DMA_RUNS = 0, 1, 2, 3, 4, 5
 EPI_BIAS_F16, EPI_BIAS_RELU_F16, EPI_BIAS_RESID_F32, EPI_F32 = 0, 1, 2, 3
 
 DECLARED_SYMBOLS = [
@@ -23,7 +23,7 @@ DECLARED_SYMBOLS = [
     "ctn_slot_bytes", "ctn_resident_blocks", "ctn_get_block_events", "ctn_block_residency_replay",
     "ctn_engine_set_prefetch", "ctn_engine_idle", "ctn_predictor_replay", "ctn_infer_stage",
     "ctn_engine_create_async", "ctn_engine_dispatch", "ctn_engine_lanes", "ctn_engine_replay_async",
-    "ctn_set_discard", "ctn_op_gemm_static", "ctn_static_scratch_bytes",
+    "ctn_set_discard", "ctn_op_gemm_static", "ctn_static_scratch_bytes", "ctn_set_copy_width",
 ]
 
 
@@ -42,7 +42,8 @@ class Config(C.Structure):
                 ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_uint64),
                 ("stream_compute", C.c_void_p), ("stream_h2d", C.c_void_p), ("stream_d2h", C.c_void_p),
                 ("transfer_mode", C.c_int32), ("pipeline", C.c_int32), ("copy_blocks", C.c_int32),
-                ("copy_cus", C.c_int32), ("block_residency", C.c_int32), ("discard_on_evict", C.c_int32)]
+                ("copy_cus", C.c_int32), ("block_residency", C.c_int32), ("discard_on_evict", C.c_int32),
+                ("copy_waves_out", C.c_int32)]
 
 
 class Stats(C.Structure):
@@ -118,6 +119,7 @@ def lib() -> C.CDLL:
         "ctn_set_graphs": (C.c_int, [vp, i32]),
         "ctn_set_mode": (C.c_int, [vp, i32, i32, i32]),
         "ctn_set_discard": (C.c_int, [vp, i32]),
+        "ctn_set_copy_width": (C.c_int, [vp, i32, i32]),
         "ctn_last_hip_error": (C.c_int, [vp]),
         "ctn_strerror": (C.c_char_p, [C.c_int]),
         "ctn_residency_replay": (C.c_int, [u64, P(u64), i32, P(i32), u64, P(Event)]),
@@ -373,7 +375,8 @@ class Context:
 
     def __init__(self, budget: int, arena, workspace, stream_compute=None, stream_h2d=None, stream_d2h=None,
                  transfer_mode: int = XFER_KERNEL, pipeline: bool = True, copy_blocks: int = 0,
-                 copy_cus: int = 0, block_residency: bool = False, discard_on_evict: bool = False):
+                 copy_cus: int = 0, block_residency: bool = False, discard_on_evict: bool = False,
+                 copy_waves_out: int = 0):
         """With no streams given the library creates its own three (CU-partitioned); they are
         exposed as `stream_compute`, `stream_h2d`, `stream_d2h` (torch ExternalStream)."""
         import torch
@@ -382,7 +385,7 @@ class Context:
         cfg = Config(int(budget), arena.data_ptr(), arena.numel() * arena.element_size(),
                      workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                      sp[0], sp[1], sp[2], transfer_mode, int(bool(pipeline)), copy_blocks, copy_cus,
-                     int(bool(block_residency)), int(bool(discard_on_evict)))
+                     int(bool(block_residency)), int(bool(discard_on_evict)), copy_waves_out)
         h = C.c_void_p()
         rc = lib().ctn_create(C.byref(cfg), C.byref(h))
         if rc:
@@ -518,6 +521,10 @@ class Context:
     def set_discard(self, enable: bool):
         """Eviction without the copy back (the host tensors stay the single source)."""
         self._check(lib().ctn_set_discard(self.h, int(bool(enable))), "ctn_set_discard")
+
+    def set_copy_width(self, blocks_in: int, waves_out: int = 0):
+        """Copy-kernel width: workgroups of 256 threads for loads, wavefronts for offloads."""
+        self._check(lib().ctn_set_copy_width(self.h, blocks_in, waves_out), "ctn_set_copy_width")
 
     def set_mode(self, transfer_mode: int, pipeline: bool, copy_blocks: int = 0):
         self._check(lib().ctn_set_mode(self.h, transfer_mode, int(bool(pipeline)), copy_blocks), "ctn_set_mode")

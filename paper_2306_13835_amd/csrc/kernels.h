@@ -15,14 +15,19 @@ struct CopySeg {
 };
 struct CopyTable {
   int32_t n;
+  int32_t threads;                          // workgroup size the chunk counts were made for
   uint32_t chunk_prefix[kCopyMaxSegs + 1];  // chunks before segment i
   CopySeg seg[kCopyMaxSegs];
 };
-// Fills chunk_prefix from seg[].n16; returns false if the table is too large.
-bool copy_table_finish(CopyTable& t);
+// Width of a copy launch is given in wavefronts: a multiple of 4 runs as workgroups of 256 threads, another
+// even count as workgroups of 128, an odd count as single-wavefront workgroups.
+int copy_workgroup_threads(int waves);
+// Fills chunk_prefix from seg[].n16 for workgroups of `threads`; returns false if the table is too large.
+bool copy_table_finish(CopyTable& t, int threads);
 enum { kCopyH2D = 0, kCopyD2H = 1, kCopyOther = 2 };
-hipError_t launch_copy_table(const CopyTable& t, int blocks, hipStream_t s, int dir);
-int default_copy_blocks();
+// waves <= 0: the library default.  The table must have been finished for copy_workgroup_threads(waves).
+hipError_t launch_copy_table(const CopyTable& t, int waves, hipStream_t s, int dir);
+int default_copy_waves();
 
 // A residual update that a split-K product has left undone: x[row][col] += sum over slices (in
 // slice order) of partial[slice][row][col] + bias[col].  splits == 0: nothing pending.

@@ -10,7 +10,6 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <chrono>
 #include <cstdio>
 #include <cstring>
 #include <memory>
@@ -68,6 +67,7 @@ struct Eviction {         // blocks [b0, b1) of a model: decided, arena given ba
   int model, b0, b1;
   std::vector<uint64_t> off;   // arena offset of each of those blocks
   bool discard = false;        // no copy back: only the ordering against the last readers is enqueued
+  int waves = 0;               // CTN_XFER_AUTO: width of the copy kernel for this offload (0: as wide as a load's)
 };
 
 struct Model {
@@ -154,8 +154,7 @@ struct ctn_ctx {
   uint64_t placements = 0;
   std::vector<ctn_block_event> block_events;
   std::vector<RetiredGraphs> retired;
-  int contended_misses = 0;          // > 0: recent misses found earlier offloads still running
-  double last_offload_s = -1.0;      // host clock when the last offload that moved bytes was enqueued
+  int evict_waves = 0;               // CTN_XFER_AUTO: copy-kernel width of the offloads decided next (0: full)
   std::vector<ctn_event> events;
   ctn_stats stats{};
   int last_hip = 0;
@@ -164,10 +163,6 @@ struct ctn_ctx {
 namespace {
 
 int g_last_hip = 0;   // HIP status of the last failing call made without a context
-
-double host_seconds() {
-  return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
-}
 
 #define CTN_HIP(ctx, expr)                        \
   do {                                            \
@@ -273,20 +268,46 @@ uint64_t block_footprint(const ctn_ctx* c, const ShardLayout& L, int b) {
 // per-tensor messages, Section 5.1), 1 = one copy-kernel launch over the block's runs, 2 = one
 // hipMemcpyAsync per run of adjacent tensors.
 enum { kPerTensorDma = 0, kCopyKernel = 1, kPerRunDma = 2 };
-int copy_block(ctn_ctx* c, Model* m, int b, char* base, bool to_device, int how, hipStream_t s) {
+// Offloads by the copy kernel beside loads by the DMA engines (CTN_XFER_DMA_IN_KERNEL_OUT, and CTN_XFER_AUTO
+// in a run of back-to-back swaps): writes to the host that a kernel issues take link capacity from the loads
+// running beside them, the more the wider the kernel is.  Measured on the alternating two-model workload
+// (6.7B/TP2 shard, one DMA copy per run for the loads), offload 4 / 8 / 12 / 128 wavefronts wide: load 54.5 /
+// 50.2 / 44.0 / 37.5 GB/s against offload 24.2 / 44.9 / 50.0 / 50.7 GB/s.  The two directions trade places
+// between 8 and 12 wavefronts, and sharply (an intermediate number of bytes in flight lands on one side or the
+// other), so a balanced offload alternates its blocks between the two.
+constexpr int kBalancedWavesLow = 8, kBalancedWavesHigh = 12;
+constexpr int kBalancedOffload = -1;          // Eviction::waves: alternate as above
+
+// How an offload of model m travels under the context's transfer mode.
+int offload_path(const ctn_ctx* c, const Model* m) {
+  switch (c->cfg.transfer_mode) {
+    case CTN_XFER_DMA: return kPerTensorDma;
+    case CTN_XFER_KERNEL: case CTN_XFER_DMA_IN_KERNEL_OUT: return kCopyKernel;
+    case CTN_XFER_KERNEL_IN_DMA_OUT: case CTN_XFER_DMA_RUNS: return kPerRunDma;
+    default: return m->fragmented ? kCopyKernel : kPerRunDma;   // CTN_XFER_AUTO
+  }
+}
+
+int copy_block(ctn_ctx* c, Model* m, int b, char* base, bool to_device, int how, hipStream_t s, int waves) {
   const ShardLayout& L = m->lay;
   if (m->runs[b].empty()) return CTN_OK;        // a stage without tensors outside its layers
   if (how == kCopyKernel) {
     CopyTable t{};
+    static_assert(kLayerTensors <= kCopyMaxSegs, "a layer block's tensors must fit one copy table");
     for (const Model::Run& r : m->runs[b]) {
+      if (t.n >= kCopyMaxSegs) {                 // a block 0 with more runs than one table holds: flush and go on
+        if (!copy_table_finish(t, copy_workgroup_threads(waves))) return CTN_E_INVAL;
+        CTN_HIP(c, launch_copy_table(t, waves, s, to_device ? kCopyH2D : kCopyD2H));
+        t = CopyTable{};
+      }
       char* dev = base + L.offset_in_block(r.first);
       t.seg[t.n].src = to_device ? m->host_dev[r.first] : dev;
       t.seg[t.n].dst = to_device ? dev : m->host_dev[r.first];
       t.seg[t.n].n16 = r.bytes / 16;
       ++t.n;
     }
-    if (!copy_table_finish(t)) return CTN_E_INVAL;
-    CTN_HIP(c, launch_copy_table(t, c->cfg.copy_blocks, s, to_device ? kCopyH2D : kCopyD2H));
+    if (!copy_table_finish(t, copy_workgroup_threads(waves))) return CTN_E_INVAL;
+    CTN_HIP(c, launch_copy_table(t, waves, s, to_device ? kCopyH2D : kCopyD2H));
     return CTN_OK;
   }
   auto one = [&](int ti, uint64_t bytes) {
@@ -321,6 +342,7 @@ void evict_logical(ctn_ctx* c, const Residency::Move& mv) {
     c->pending.push_back({run_off, run_len, m->ev_out_done, mv.model});
   };
   ev.discard = c->cfg.discard_on_evict != 0;
+  ev.waves = c->evict_waves;
   for (int b = mv.b0; b < mv.b1; ++b) {
     const uint64_t off = m->block_off[b], len = block_footprint(c, m->lay, b);
     ev.off.push_back(off);
@@ -348,22 +370,27 @@ int enqueue_offload(ctn_ctx* c, const Eviction& ev) {
     if (m->used[lane]) CTN_HIP(c, hipStreamWaitEvent(c->s_d2h, m->ev_last_use[lane], 0));
   CTN_HIP(c, hipEventRecord(m->ev_out_start, c->s_d2h));
   const ShardLayout& L = m->lay;
-  // offloads: the copy kernel only when asked for; otherwise DMA, per tensor or per run of adjacent tensors
-  const int how = c->cfg.transfer_mode == CTN_XFER_KERNEL ? kCopyKernel
-                  : c->cfg.transfer_mode == CTN_XFER_DMA ? kPerTensorDma : kPerRunDma;
+  const int how = offload_path(c, m);
+  int waves = c->cfg.copy_waves_out ? c->cfg.copy_waves_out : 4 * c->cfg.copy_blocks;
+  const bool balanced = !c->cfg.copy_waves_out && how == kCopyKernel &&
+                        (c->cfg.transfer_mode == CTN_XFER_DMA_IN_KERNEL_OUT ||
+                         (c->cfg.transfer_mode == CTN_XFER_AUTO && ev.waves == kBalancedOffload));
+  if (c->cfg.transfer_mode == CTN_XFER_AUTO && !c->cfg.copy_waves_out && ev.waves > 0) waves = ev.waves;
   uint64_t bytes = 0;
   // (a discarded device copy moves nothing; the stream waits above and the event below still
   // order the reuse of its blocks after the load and the inferences that were using them)
   for (int b = ev.b0; b < ev.b1 && !ev.discard; ++b) {
     bytes += L.block_bytes[b];
-    const int rc = copy_block(c, m, b, arena + ev.off[b - ev.b0], false, how, c->s_d2h);
+    // balanced: the blocks alternate between the two widths on either side of the point where the link's two
+    // directions trade places, so the offload as a whole keeps pace with the DMA load beside it
+    const int w = balanced ? ((b & 1) ? kBalancedWavesHigh : kBalancedWavesLow) : waves;
+    const int rc = copy_block(c, m, b, arena + ev.off[b - ev.b0], false, how, c->s_d2h, w);
     if (rc) return rc;
   }
   CTN_HIP(c, hipEventRecord(m->ev_out_done, c->s_d2h));
   m->out_recorded = true;
   m->pending_out = true;
   c->stats.bytes_d2h += bytes;
-  if (bytes) c->last_offload_s = host_seconds();
   c->stats.n_swap_out += 1;
   return CTN_OK;
 }
@@ -408,24 +435,16 @@ int ensure_resident(ctn_ctx* c, int mi) {
       ++i;
     }
   }
-  // An offload from an earlier call is still running: the link is already busy in both
-  // directions.  The observation is held for the next two misses as well, so that a
-  // back-to-back swap sequence does not flip between the two load paths.
-  // An offload enqueued less than two of this model's load times ago says the same even when it has just
-  // finished (a shard of a few GB swapped back and forth: its offload ends within milliseconds of the next
-  // miss, and polling alone made every fourth load fall back to the kernel, 67.7 against 58.1 ms per step
-  // for the 1.3B shard).
-  const bool offload_just_now = c->last_offload_s >= 0.0 &&
-                                host_seconds() - c->last_offload_s < 2.0 * static_cast<double>(L.param_bytes) / 50e9;
-  if (!c->pending.empty() || offload_just_now) c->contended_misses = 3;
-  const bool earlier_offload_running = c->contended_misses > 0;
-  if (c->contended_misses > 0) c->contended_misses -= 1;
-
   const uint64_t use = c->events.size();
   const int first = m->k;                       // blocks [first, n_blocks) are missing
   std::vector<Residency::Move> moves;           // what this use evicts, one entry per victim, in order
   while (c->res.over_budget_with(mi))
     if (c->res.evict_step(mi, moves) < 0) return CTN_E_BUSY;   // (cannot happen: the model fits the budget alone)
+  // CTN_XFER_AUTO reads the link's state from the context's own record and its events, never from the clock:
+  // the link is busy both ways during this load when the miss evicts (its victims' offloads run beside the
+  // load) or when an offload that an earlier use enqueued has not completed.
+  const bool two_way = !moves.empty() || !c->pending.empty();
+  c->evict_waves = kBalancedOffload;      // (CTN_XFER_AUTO) offloads that run beside this load keep pace with it
   for (const Residency::Move& mv : moves) evict_logical(c, mv);
   auto busy_ranges = [&]() {
     std::vector<RangeAllocator::Range> b;
@@ -503,18 +522,23 @@ int ensure_resident(ctn_ctx* c, int mi) {
   // The load reads the host tensors this model's own offload may still be writing.
   if (m->pending_out) CTN_HIP(c, hipStreamWaitEvent(c->s_h2d, m->ev_out_done, 0));
   char* arena = static_cast<char*>(c->cfg.arena_dev);
-  // AUTO: a host list in many pieces is gathered by one kernel launch per block
-  // (no per-piece cost, and the fastest load while only this call's victim is
-  // being offloaded: 53.6 GB/s against a 38.9 GB/s offload).  When earlier
-  // offloads still occupy the link, the per-piece DMA path shares it evenly
-  // (47 + 49 GB/s), which is what a back-to-back swap sequence needs.  A packed
-  // list always goes through the DMA engines, one copy per run.
-  const bool load_by_kernel = c->cfg.transfer_mode == CTN_XFER_KERNEL ||
-                              (c->cfg.transfer_mode == CTN_XFER_AUTO && m->fragmented && !earlier_offload_running);
+  // AUTO: with the link's other direction idle, a host list in many pieces is gathered by one kernel launch
+  // per block (no per-piece cost on the host or the device, 98.8 % of the link's peak).  Beside an offload
+  // the DMA engines load it, one copy per run: host reads that a kernel issues are many small requests that
+  // travel against the offload's data and slow both directions (kernel both ways at full width: 33 + 52 GB/s;
+  // DMA loads beside the balanced offload kernel: 47 + 47).  A packed list always takes one DMA copy per run.
+  int how = kPerRunDma;
+  switch (c->cfg.transfer_mode) {
+    case CTN_XFER_DMA: how = kPerTensorDma; break;
+    case CTN_XFER_KERNEL: case CTN_XFER_KERNEL_IN_DMA_OUT: how = kCopyKernel; break;
+    case CTN_XFER_DMA_IN_KERNEL_OUT: case CTN_XFER_DMA_RUNS: how = kPerRunDma; break;
+    default:   // CTN_XFER_AUTO
+      how = (m->fragmented && !two_way) ? kCopyKernel : kPerRunDma;
+      break;
+  }
   CTN_HIP(c, hipEventRecord(m->ev_in_start, c->s_h2d));
-  const int how = load_by_kernel ? kCopyKernel : c->cfg.transfer_mode == CTN_XFER_DMA ? kPerTensorDma : kPerRunDma;
   for (int b = first; b < L.n_blocks; ++b) {
-    rc = copy_block(c, m, b, arena + m->block_off[b], true, how, c->s_h2d);
+    rc = copy_block(c, m, b, arena + m->block_off[b], true, how, c->s_h2d, 4 * c->cfg.copy_blocks);
     if (rc) return rc;
     CTN_HIP(c, hipEventRecord(m->ev_block[b], c->s_h2d));
   }
@@ -565,7 +589,11 @@ int create_partitioned_streams(ctn_ctx* c, int copy_cus) {
   CTN_HIP(c, make(copy_cus, 2 * copy_cus, &c->s_d2h));
   CTN_HIP(c, make(2 * copy_cus, n_cu, &c->s_compute));
   CTN_HIP(c, make(2 * copy_cus, n_cu, &c->s_lane1));
-  CTN_HIP(c, hipStreamCreateWithFlags(&c->s_wide, hipStreamNonBlocking));
+  // The unmasked stream also gets an explicit mask, of every compute unit.  A plain stream may be handed a
+  // hardware queue that an earlier, destroyed masked stream of this process used, and then runs on that
+  // stream's compute units (measured: resident 1 x 64 requests at 7.1 ms instead of 3.0 ms in a process that
+  // had created and destroyed a context before).
+  CTN_HIP(c, make(0, n_cu, &c->s_wide));
   CTN_HIP(c, hipEventCreateWithFlags(&c->ev_compute_done, hipEventDisableTiming));
   c->own_streams = true;
   c->use_graphs = false;   // measured on ROCm 7.2 / MI355X: replay is no faster than direct launches (the
@@ -698,7 +726,8 @@ int ctn_create(const ctn_config* cfg, ctn_ctx** out) {
   if (reinterpret_cast<uintptr_t>(cfg->arena_dev) % kAlign || reinterpret_cast<uintptr_t>(cfg->workspace_dev) % kAlign)
     return CTN_E_INVAL;
   if (cfg->hbm_budget_bytes == 0 || cfg->arena_bytes == 0) return CTN_E_INVAL;
-  if (cfg->transfer_mode < CTN_XFER_DMA || cfg->transfer_mode > CTN_XFER_AUTO) return CTN_E_INVAL;
+  if (cfg->transfer_mode < CTN_XFER_DMA || cfg->transfer_mode > CTN_XFER_DMA_RUNS) return CTN_E_INVAL;
+  if (cfg->copy_blocks < 0 || cfg->copy_blocks > 4096 || cfg->copy_waves_out < 0 || cfg->copy_waves_out > 16384) return CTN_E_INVAL;
   if (cfg->block_residency != 0 && cfg->block_residency != 1) return CTN_E_INVAL;
   if (cfg->discard_on_evict != 0 && cfg->discard_on_evict != 1) return CTN_E_INVAL;
   if (!own_streams && (cfg->stream_h2d == cfg->stream_compute || cfg->stream_d2h == cfg->stream_compute ||
@@ -863,6 +892,7 @@ int ctn_swap_out(ctn_ctx* c, ctn_model mi) {
   if (m->k > 0) {
     victims.push_back(mi);
     const Residency::Move mv = c->res.evict_all(mi);
+    c->evict_waves = 0;                // nothing competes for the link on the caller's behalf: full width
     evict_logical(c, mv);
     log_blocks(c, 1, mv, c->events.size());
   }
@@ -1102,11 +1132,18 @@ int ctn_set_discard(ctn_ctx* c, int32_t enable) {
 
 int ctn_set_mode(ctn_ctx* c, int32_t transfer_mode, int32_t pipeline, int32_t copy_blocks) {
   if (!c) return CTN_E_INVAL;
-  if (transfer_mode < CTN_XFER_DMA || transfer_mode > CTN_XFER_AUTO) return CTN_E_INVAL;
+  if (transfer_mode < CTN_XFER_DMA || transfer_mode > CTN_XFER_DMA_RUNS) return CTN_E_INVAL;
   if (copy_blocks < 0 || copy_blocks > 4096) return CTN_E_INVAL;
   c->cfg.transfer_mode = transfer_mode;
   c->cfg.pipeline = pipeline ? 1 : 0;
   c->cfg.copy_blocks = copy_blocks;
+  return CTN_OK;
+}
+
+int ctn_set_copy_width(ctn_ctx* c, int32_t blocks_in, int32_t waves_out) {
+  if (!c || blocks_in < 0 || blocks_in > 4096 || waves_out < 0 || waves_out > 16384) return CTN_E_INVAL;
+  c->cfg.copy_blocks = blocks_in;
+  c->cfg.copy_waves_out = waves_out;
   return CTN_OK;
 }
 
@@ -1528,8 +1565,9 @@ int ctn_op_copy(void* dst, const void* src, uint64_t nbytes, int32_t blocks, voi
   CopyTable t{};
   t.n = 1;
   t.seg[0] = {src, dst, nbytes / 16};
-  if (!copy_table_finish(t)) return CTN_E_INVAL;
-  return op_rc(launch_copy_table(t, blocks, static_cast<hipStream_t>(stream), kCopyOther));
+  if (blocks < 0 || blocks > 16384) return CTN_E_INVAL;
+  if (!copy_table_finish(t, 256)) return CTN_E_INVAL;
+  return op_rc(launch_copy_table(t, 4 * blocks, static_cast<hipStream_t>(stream), kCopyOther));
 }
 
 int ctn_op_dma(void* dst, const void* src, uint64_t nbytes, void* stream) {

@@ -18,44 +18,62 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def serve_setup(host_layout="separate"):
+    """The eight shards of the serving workload in pinned host memory: (config, pool, tensor lists)."""
+    import paper_2306_13835_amd as P
+    from synth import CONFIGS, fill_shard, shard_bytes, param_list
+    c = CONFIGS["serve8x6.7b_tp2"]
+    desc, n_models = c["desc"], c["n_models"]
+    nbytes = shard_bytes(desc)
+    gap = 4096 if host_layout == "separate" else 0
+    n_t = len(param_list(desc))
+    pool = P.HostPool(n_models * (nbytes + n_t * (256 + gap)) + 8192)
+    t0 = time.time()
+    keep = [fill_shard(desc, c["wseed"] + k, alloc=lambda s: pool.take(s, gap=gap), threads=16) for k in range(n_models)]
+    log(f"[serve] {n_models} shards ({n_models * nbytes / 1e9:.1f} GB pinned) ready in {time.time() - t0:.1f}s")
+    return c, pool, keep
+
+
 def run_serve(args):
+    import torch
+    torch.cuda.set_device(0)
+    torch.zeros(1, device="cuda")
+    c, pool, keep = serve_setup(args.host_layout)
+    res = serve_once(c, keep, args.requests or c["n_requests"], args.transfer, args.host_layout,
+                     blocks=bool(getattr(args, "block_residency", False)), two_lanes=bool(getattr(args, "two_lane", False)),
+                     load_ahead=bool(getattr(args, "load_ahead", False)))
+    del keep
+    pool.close()
+    print(json.dumps(res), flush=True)
+
+
+TRANSFER_MODES = {"dma": 0, "kernel": 1, "auto": 2, "dma_in_kernel_out": 3, "kernel_in_dma_out": 4, "dma_runs": 5}
+
+
+def serve_once(c, keep, n_req, transfer="auto", host_layout="separate", blocks=False, two_lanes=False, load_ahead=False):
+    """One real-time replay of the first n_req requests of the serving trace over the registered shards;
+    returns the result record (latency percentiles, misses, whether every decision equals the policy replay)."""
     import torch
     import paper_2306_13835_amd as P
     from paper_2306_13835_amd.serving import serve_trace
-    from synth import CONFIGS, fill_shard, token_ids, shard_bytes, param_list, gamma_zipf_trace
+    from synth import token_ids, shard_bytes, param_list, gamma_zipf_trace
 
-    torch.cuda.set_device(0)
-    torch.zeros(1, device="cuda")
-    c = CONFIGS["serve8x6.7b_tp2"]
     desc, batch, seq, n_models = c["desc"], c["batch"], c["seq"], c["n_models"]
-    n_req = args.requests or c["n_requests"]
     nbytes = shard_bytes(desc)
     budget = c["budget"]
-    gap = 4096 if args.host_layout == "separate" else 0
     # The budget caps the bytes of models *marked resident* (at most two here).  The arena holds one
     # more range so that a victim can still be streaming out of its range while the requested model
     # streams into another one, as the paper's overlapped offload and load do (Sections 3.2, 5.1).
     resident_max = budget // nbytes
-    blocks = bool(getattr(args, "block_residency", False))
     # Block residency: every transfer block takes one slot; the slack of the budget below another whole
     # model holds a prefix of one more model, so the arena gets one more range than the whole-model case.
     one = P.slot_bytes(desc) * (desc.layers + 1) if blocks else P.arena_bytes(desc)
     arena = torch.empty((resident_max + (2 if blocks else 1)) * one, dtype=torch.uint8, device="cuda")
-    two_lanes = bool(getattr(args, "two_lane", False))
     ws = torch.empty(P.workspace_bytes(desc, batch * seq) * (2 if two_lanes else 1) + 512, dtype=torch.uint8, device="cuda")
     logits = torch.empty(batch, seq, desc.vocab // desc.tp, dtype=torch.float32, device="cuda")
     logits2 = torch.empty_like(logits)
-    ctx = P.Context(budget, arena, ws, transfer_mode={"dma": 0, "kernel": 1, "auto": 2}[args.transfer],
-                    pipeline=True, block_residency=blocks)
-    n_t = len(param_list(desc))
-    pool = P.HostPool(n_models * (nbytes + n_t * (256 + gap)) + 8192)
-    t0 = time.time()
-    models, keep = [], []
-    for k in range(n_models):
-        t = fill_shard(desc, c["wseed"] + k, alloc=lambda s: pool.take(s, gap=gap), threads=16)
-        keep.append(t)
-        models.append(ctx.register_model(desc, t))
-    log(f"[serve] {n_models} shards ({n_models * nbytes / 1e9:.1f} GB pinned) ready in {time.time() - t0:.1f}s")
+    ctx = P.Context(budget, arena, ws, transfer_mode=TRANSFER_MODES[transfer], pipeline=True, block_residency=blocks)
+    models = [ctx.register_model(desc, t) for t in keep]
     arr, mod = gamma_zipf_trace(n_models, c["rate"], c["cv"], c["zipf"], c["n_requests"], c["trace_seed"])
     arr, mod = arr[:n_req], mod[:n_req]
     ids = [token_ids(c["idseed"] + i, batch, seq, desc.vocab) for i in range(n_req)]
@@ -82,7 +100,7 @@ def run_serve(args):
         # the asynchronous engine of Section 3.2 (batch size 1 as in this workload): hits go on while a model loads
         from paper_2306_13835_amd.serving import serve_engine_async
         eng = P.Engine(ctx, batch, seq, two_lanes=True)
-        if getattr(args, "load_ahead", False):
+        if load_ahead:
             eng.set_prefetch(True, min_count=3, min_share_percent=60)
         miss = np.zeros(n_req, dtype=bool)
         count = [0]
@@ -140,9 +158,9 @@ def run_serve(args):
                                f"batch {batch} x seq {seq}, "
                                + ("two-lane engine (hits go on while a model loads)" if two_lanes else "serial oldest-first engine")
                                + ", LRU",
-                   "transfer": args.transfer, "host_layout": args.host_layout,
+                   "transfer": transfer, "host_layout": host_layout,
                    "residency": "per transfer block (prefix kept)" if blocks else "whole models (2 resident)",
-                   "load_ahead": bool(getattr(args, "load_ahead", False)),
+                   "load_ahead": bool(load_ahead),
                    "arena_bytes": int(arena.numel()), "arena_note": "budget + one transit range"},
         "latency_s": {"mean": round(float(lat.mean()), 4), "p50": round(float(np.percentile(lat, 50)), 4),
                       "p90": round(float(np.percentile(lat, 90)), 4), "p99": round(float(np.percentile(lat, 99)), 4),
@@ -163,9 +181,8 @@ def run_serve(args):
         "hit_tokens_per_s": round(batch * seq / float(np.median(svc[~miss])), 1) if (~miss).any() else None,
     }
     ctx.close()
-    del keep
-    pool.close()
-    print(json.dumps(res), flush=True)
+    del arena, ws
+    return res
 
 
 # Average end-to-end latencies the paper prints (Tables 1 and 2; 4 x A100, OPT-13B, TP=2 x PP=2,
@@ -213,7 +230,7 @@ def run_grid(args):
                          device="cuda")
         logits = torch.empty(max_batch, seq, desc.vocab // desc.tp, dtype=torch.float32, device="cuda")
         logits2 = torch.empty_like(logits)
-        ctx = P.Context(budget, arena, ws, transfer_mode={"dma": 0, "kernel": 1, "auto": 2}[args.transfer], pipeline=True)
+        ctx = P.Context(budget, arena, ws, transfer_mode=TRANSFER_MODES[args.transfer], pipeline=True)
         models = [ctx.register_model(desc, keep[k]) for k in range(n_models)]
         eng = P.Engine(ctx, max_batch, seq, two_lanes=two_lanes)
         table = {}
@@ -287,7 +304,7 @@ def run_cyclic(args):
         arena = torch.empty(3 * P.arena_bytes(desc), dtype=torch.uint8, device="cuda")
         ws = torch.empty(P.workspace_bytes(desc, seq), dtype=torch.uint8, device="cuda")
         logits = torch.empty(1, seq, desc.vocab // desc.tp, dtype=torch.float32, device="cuda")
-        ctx = P.Context(2 * nbytes, arena, ws, transfer_mode={"dma": 0, "kernel": 1, "auto": 2}[args.transfer], pipeline=True)
+        ctx = P.Context(2 * nbytes, arena, ws, transfer_mode=TRANSFER_MODES[args.transfer], pipeline=True)
         models = [ctx.register_model(desc, keep[k]) for k in range(n_models)]
         eng = P.Engine(ctx, 1, seq)
         eng.set_prefetch(ahead)
@@ -339,7 +356,7 @@ def run_mixed(args):
     arena = torch.empty(4 * P.arena_bytes(big), dtype=torch.uint8, device="cuda")
     ws = torch.empty(max(P.workspace_bytes(d, batch * seq) for d in (big, small)) + 512, dtype=torch.uint8, device="cuda")
     logits = torch.empty(batch * seq * max(d.vocab // d.tp for d in (big, small)), dtype=torch.float32, device="cuda")
-    ctx = P.Context(budget, arena, ws, transfer_mode={"dma": 0, "kernel": 1, "auto": 2}[args.transfer], pipeline=True)
+    ctx = P.Context(budget, arena, ws, transfer_mode=TRANSFER_MODES[args.transfer], pipeline=True)
     t0 = time.time()
     keep = [fill_shard(d, 70 + k, alloc=lambda sh: pool.take(sh, gap=gap), threads=16) for k, d in enumerate(kinds)]
     models = [ctx.register_model(d, t) for d, t in zip(kinds, keep)]
@@ -429,7 +446,7 @@ def run_scaling(args):
         arena = torch.empty(2 * P.arena_bytes(desc), dtype=torch.uint8, device="cuda")
         ws = torch.empty(P.workspace_bytes(desc, seq), dtype=torch.uint8, device="cuda")
         out = torch.empty(1, seq, desc.out_features, dtype=torch.float32, device="cuda")
-        ctx = P.Context(nbytes, arena, ws, transfer_mode={"dma": 0, "kernel": 1, "auto": 2}[args.transfer], pipeline=True)
+        ctx = P.Context(nbytes, arena, ws, transfer_mode=TRANSFER_MODES[args.transfer], pipeline=True)
         pool = P.HostPool(2 * (nbytes + n_t * (256 + gap)) + 8192)
         t0 = time.time()
         keep = [fill_shard(desc, 200 + 10 * tp + pp + k, alloc=lambda s: pool.take(s, gap=gap), threads=16) for k in range(2)]

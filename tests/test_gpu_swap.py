@@ -61,6 +61,66 @@ def test_round_trip_scribble_and_poison(mode, desc, gap):
         rig.close()
 
 
+@pytest.mark.parametrize("waves_out", [0, 1, 6, 10, 12])       # workgroups of 256, 64, 128, 128 and 256 threads
+@pytest.mark.parametrize("mode", [P.XFER_KERNEL, P.XFER_DMA_IN_KERNEL_OUT, P.XFER_KERNEL_IN_DMA_OUT, P.XFER_DMA_RUNS])
+def test_round_trip_every_path_and_offload_width(mode, waves_out):
+    """The copy kernel in one direction and the DMA engines in the other, and every workgroup size the
+    offload's kernel comes in: device copy equal to the oracle's image, host bytes restored after an overwrite,
+    nothing written between the tensors."""
+    desc = SMALL_TP
+    rig = Rig([desc], mode=mode, gap=48)
+    try:
+        rig.ctx.set_copy_width(0, waves_out)
+        m = rig.add(desc, seed=6)
+        orig = [t.copy() for t in rig.tensors[m]]
+        for cycle in range(2):
+            rig.arena.fill_(0x7E)
+            torch.cuda.synchronize()
+            rig.ctx.swap_in(m)
+            rig.ctx.wait(m)
+            check_device_copy(rig, m, desc)
+            for t in rig.tensors[m]:
+                as_bytes(t)[:] = 0x5A
+            rig.ctx.swap_out(m)
+            rig.ctx.wait(m)
+            for t, o in zip(rig.tensors[m], orig):
+                assert np.array_equal(as_bytes(t), as_bytes(o))
+        used = np.zeros(rig.pool.nbytes, dtype=bool)
+        for t in rig.tensors[m]:
+            off = t.ctypes.data - rig.pool.ptr
+            used[off:off + t.nbytes] = True
+        assert not rig.pool.bytes[~used].any()
+    finally:
+        rig.close()
+
+
+def test_auto_offloads_beside_a_load_restore_every_byte():
+    """Transfer mode AUTO with a host list in separate pieces: a miss that evicts loads through the DMA engines
+    while the victim's offload goes through the copy kernel, its blocks alternating between two widths.  Two
+    models, room for one, requests alternating: after every swap the evicted model's host bytes (overwritten
+    while it was on the device) are back and the loaded model's device copy equals the oracle's image."""
+    desc = SMALL
+    size = shard_bytes(desc)
+    rig = Rig([desc] * 2, budget=size, arena_bytes=2 * P.arena_bytes(desc), mode=P.XFER_AUTO, gap=4096)
+    try:
+        ms = [rig.add(desc, seed=70 + i) for i in range(2)]
+        orig = [[t.copy() for t in rig.tensors[m]] for m in ms]
+        rig.ctx.swap_in(ms[0]); rig.ctx.wait(ms[0])
+        for step in range(6):
+            cur, nxt = ms[step % 2], ms[(step + 1) % 2]
+            for t in rig.tensors[cur]:
+                as_bytes(t)[:] = 0xC3                      # the copy on the device is the only good one now
+            rig.ctx.swap_in(nxt)                           # evicts cur
+            rig.ctx.wait(nxt); rig.ctx.wait(cur)
+            assert rig.ctx.is_resident(nxt) and not rig.ctx.is_resident(cur)
+            for t, o in zip(rig.tensors[cur], orig[cur]):
+                assert np.array_equal(as_bytes(t), as_bytes(o))
+            check_device_copy(rig, nxt, desc)
+        assert rig.ctx.stats()["n_swap_out"] == 6
+    finally:
+        rig.close()
+
+
 def test_dma_and_kernel_paths_leave_identical_arenas():
     rig = Rig([SMALL])
     try:
