@@ -38,6 +38,10 @@ PCIE5_X16_NOMINAL_GBPS = 64.0
 # passes summarised in profiles/counters_opt6.7b_tp2_pmc.md: FETCH_SIZE 98,373 KiB x 2.0 (calibration
 # factor of that counter) of loads from the host mapping + WRITE_SIZE 196,684 KiB x 1.0 of HBM stores.
 COPY_KERNEL_TRAFFIC = {"opt6.7b_tp2": {"fetch_bytes": 98373 * 2 * 1024, "write_bytes": 196684 * 1024}}
+# The same for an offload launch of a layer block (HBM -> host), mean of the 8- and the 12-wavefront launches that the
+# blocks of an offload beside a load alternate between: FETCH_SIZE 98,350 KiB x 2.0 from HBM, WRITE_SIZE (196,735 +
+# 197,551) / 2 KiB towards the host.
+COPY_KERNEL_OUT_TRAFFIC = {"opt6.7b_tp2": {"fetch_bytes": 98350 * 2 * 1024, "write_bytes": (196735 + 197551) // 2 * 1024}}
 # Same two passes, the fc1 product of that shard inside its 4 x 256 forward (M=1024, N=8192, K=4096,
 # 128x128x64 tiles): FETCH_SIZE 65,614 KiB x 2.0 = W once (67.1 MB) + A once per XCD (8 x 8.4 MB);
 # WRITE_SIZE 16,488 KiB = the fp16 output once.
@@ -212,83 +216,86 @@ def run_swap(args):
 
     # ---- side measurements (outside the timed region) ---------------------------
     side = {}
-    ctx.sync()
-    # pure transfer, no forward, nothing else on the link: kernel path and per-tensor DMA path
-    for mode, key in ((P.XFER_KERNEL, "kernel"), (P.XFER_DMA, "dma")):
-        ctx.set_mode(mode, True, args.copy_blocks)
-        ins, outs = [], []
-        for _ in range(3):
-            ctx.swap_in(models[0]); ctx.wait(models[0])
-            ctx.swap_out(models[0]); ctx.wait(models[0])
-            i_ms, o_ms, blocks = ctx.last_swap_ms(models[0])
-            ins.append(i_ms); outs.append(o_ms)
-            side.setdefault(f"blocks_{key}", []).append(list(blocks))
-        side[f"swap_in_ms_{key}"] = median(ins)
-        side[f"swap_out_ms_{key}"] = median(outs)
-    ctx.set_mode(P.XFER_KERNEL, True, args.copy_blocks)
-    transfer_ms = side["swap_in_ms_kernel"]
-    # first-token latency from a swapped-out model, nothing else in flight
-    for pipe, key in ((True, "pipelined"), (False, "load_then_run")):
-        ctx.set_mode(P.XFER_KERNEL, pipe, args.copy_blocks)
-        ts = []
-        for _ in range(3):
-            ctx.sync()
-            t = time.perf_counter()
-            request(0)
-            ts.append((time.perf_counter() - t) * 1e3)
-            ctx.swap_out(models[0]); ctx.wait(models[0])
-        side[f"first_token_ms_{key}"] = median(ts)
-    ctx.set_mode(MODES[args.transfer], True, args.copy_blocks)
-    # resident forward (hit path)
-    request(0)
-    ts = []
-    for _ in range(5):
-        t = time.perf_counter(); request(0); ts.append((time.perf_counter() - t) * 1e3)
-    side["forward_resident_ms"] = median(ts)
-    # the hit path at the request sizes of the paper's workloads (8 tokens; 1 x 64 in the serving trace):
-    # every weight byte is read once, so the bound is shard bytes / HBM bandwidth
-    if desc.has_embed:
-        for tokens in (8, 64):
-            if tokens > M or tokens > desc.max_pos:
-                continue
-            small_ids = token_ids(cfg["idseed"] + 7, 1, tokens, desc.vocab)
-            small_out = torch.empty(1, tokens, desc.out_features, dtype=torch.float32, device="cuda")
+    if not args.only_timed:
+        ctx.sync()
+        # pure transfer, no forward, nothing else on the link: kernel path and per-tensor DMA path
+        for mode, key in ((P.XFER_KERNEL, "kernel"), (P.XFER_DMA, "dma")):
+            ctx.set_mode(mode, True, args.copy_blocks)
+            ins, outs = [], []
+            for _ in range(3):
+                ctx.swap_in(models[0]); ctx.wait(models[0])
+                ctx.swap_out(models[0]); ctx.wait(models[0])
+                i_ms, o_ms, blocks = ctx.last_swap_ms(models[0])
+                ins.append(i_ms); outs.append(o_ms)
+                side.setdefault(f"blocks_{key}", []).append(list(blocks))
+            side[f"swap_in_ms_{key}"] = median(ins)
+            side[f"swap_out_ms_{key}"] = median(outs)
+        ctx.set_mode(P.XFER_KERNEL, True, args.copy_blocks)
+        transfer_ms = side["swap_in_ms_kernel"]
+        # first-token latency from a swapped-out model, nothing else in flight
+        for pipe, key in ((True, "pipelined"), (False, "load_then_run")):
+            ctx.set_mode(P.XFER_KERNEL, pipe, args.copy_blocks)
             ts = []
-            for _ in range(8):
+            for _ in range(3):
+                ctx.sync()
                 t = time.perf_counter()
-                ctx.infer(models[0], small_ids, out=small_out)
-                s_c.synchronize()
+                request(0)
                 ts.append((time.perf_counter() - t) * 1e3)
-            side[f"forward_resident_1x{tokens}_ms"] = median(ts[3:])
-    ctx.swap_out(models[0]); ctx.wait(models[0])
-    ctx.sync()
+                ctx.swap_out(models[0]); ctx.wait(models[0])
+            side[f"first_token_ms_{key}"] = median(ts)
+        ctx.set_mode(MODES[args.transfer], True, args.copy_blocks)
+        # resident forward (hit path)
+        request(0)
+        ts = []
+        for _ in range(5):
+            t = time.perf_counter(); request(0); ts.append((time.perf_counter() - t) * 1e3)
+        side["forward_resident_ms"] = median(ts)
+        # the hit path at the request sizes of the paper's workloads (8 tokens; 1 x 64 in the serving trace):
+        # every weight byte is read once, so the bound is shard bytes / HBM bandwidth
+        if desc.has_embed:
+            for tokens in (8, 64):
+                if tokens > M or tokens > desc.max_pos:
+                    continue
+                small_ids = token_ids(cfg["idseed"] + 7, 1, tokens, desc.vocab)
+                small_out = torch.empty(1, tokens, desc.out_features, dtype=torch.float32, device="cuda")
+                ts = []
+                for _ in range(8):
+                    t = time.perf_counter()
+                    ctx.infer(models[0], small_ids, out=small_out)
+                    s_c.synchronize()
+                    ts.append((time.perf_counter() - t) * 1e3)
+                side[f"forward_resident_1x{tokens}_ms"] = median(ts[3:])
+        ctx.swap_out(models[0]); ctx.wait(models[0])
+        ctx.sync()
 
-    # the same alternation on the other transfer paths, for the comparison of the copy kernel with the DMA engines:
-    # one hipMemcpyAsync per run of adjacent tensors, one per tensor (the paper's per-tensor messages), and the
-    # copy kernel at full width in both directions (AUTO narrows the offload's kernel)
-    side["paths"] = {}
-    for alt, mode, waves_out in (("dma_runs", "dma_runs", 0), ("dma_per_tensor", "dma", 0),
-                                 ("kernel_both_ways_full_width", "kernel", 0), ("kernel_both_ways_offload_8_waves", "kernel", 8)):
-        ctx.set_mode(MODES[mode], True, args.copy_blocks)
-        ctx.set_copy_width(args.copy_blocks, waves_out)
-        w_alt, lat_alt = alternate(models, 4, 2)
-        side["paths"][alt] = {"ms_per_step": round(w_alt / 4 * 1e3, 3), "value_gbps": round(4 * nbytes / w_alt / 1e9, 3),
-                              "step_latencies_ms": [round(x, 1) for x in lat_alt]}
+        # the same alternation on the other transfer paths, for the comparison of the copy kernel with the DMA engines:
+        # one hipMemcpyAsync per run of adjacent tensors, one per tensor (the paper's per-tensor messages), and the
+        # copy kernel at full width in both directions (AUTO narrows the offload's kernel)
+        side["paths"] = {}
+        for alt, mode, waves_out in (("dma_runs", "dma_runs", 0), ("dma_per_tensor", "dma", 0),
+                                     ("kernel_both_ways_full_width", "kernel", 0), ("kernel_both_ways_offload_8_waves", "kernel", 8)):
+            ctx.set_mode(MODES[mode], True, args.copy_blocks)
+            ctx.set_copy_width(args.copy_blocks, waves_out)
+            w_alt, lat_alt = alternate(models, 4, 2)
+            side["paths"][alt] = {"ms_per_step": round(w_alt / 4 * 1e3, 3), "value_gbps": round(4 * nbytes / w_alt / 1e9, 3),
+                                  "step_latencies_ms": [round(x, 1) for x in lat_alt]}
+        ctx.set_copy_width(args.copy_blocks, args.copy_waves_out)
+
+        # the same alternation if evictions only freed the device copy (parameters are read-only on the device);
+        # an option, off by default: the paper's swap-out is a real copy and so is the timed region's
+        ctx.set_mode(MODES[args.transfer], True, args.copy_blocks)
+        ctx.set_discard(True)
+        w_disc, _ = alternate(models, 4, 2)
+        ctx.set_discard(False)
+        side["discard_ms_per_step"] = w_disc / 4 * 1e3
+
+        # the same alternation on the other host layout, for the report
+        ctx.set_mode(MODES[args.transfer], True, args.copy_blocks)
+        w_other, lat_other = alternate(models_other, 4, 2)
+        side["other_layout_ms_per_step"] = w_other / 4 * 1e3
+
+    ctx.set_mode(MODES[args.transfer], True, args.copy_blocks)
     ctx.set_copy_width(args.copy_blocks, args.copy_waves_out)
-
-    # the same alternation if evictions only freed the device copy (parameters are read-only on the device);
-    # an option, off by default: the paper's swap-out is a real copy and so is the timed region's
-    ctx.set_mode(MODES[args.transfer], True, args.copy_blocks)
-    ctx.set_discard(True)
-    w_disc, _ = alternate(models, 4, 2)
-    ctx.set_discard(False)
-    side["discard_ms_per_step"] = w_disc / 4 * 1e3
-
-    # the same alternation on the other host layout, for the report
-    ctx.set_mode(MODES[args.transfer], True, args.copy_blocks)
-    w_other, lat_other = alternate(models_other, 4, 2)
-    side["other_layout_ms_per_step"] = w_other / 4 * 1e3
-
     # ---- timed region -------------------------------------------------------------
     in_ms, out_ms = [], []
     wall, lat = alternate(models, args.steps, args.warmup)
@@ -316,6 +323,27 @@ def run_swap(args):
     avg_launch_ms = float(np.mean(launch_ms))
     avg_launch_bytes = float(np.mean(block_bytes))
     achieved = avg_launch_bytes / avg_launch_ms / 1e6
+
+    if args.only_timed:
+        n_launch = len(block_bytes)
+        out_launch_ms = float(np.mean(out_ms)) / n_launch
+        result = {"metric": "host->HBM swap-in GB/s (demand-paged requests, swap-out overlapped, forward pipelined)",
+                  "value": round(args.steps * nbytes / wall / 1e9, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+                  "warmup": args.warmup, "ms_per_step": round(wall / args.steps * 1e3, 3), "higher_is_better": True,
+                  "dtype": "f16", "data": "synthetic",
+                  "config": {"workload": f"{args.config} shard x2 models, budget 1 resident, alternating blocking requests, "
+                                         f"batch {batch} x seq {seq}; timed region only (for profilers)",
+                             "transfer": args.transfer, "host_layout": args.host_layout},
+                  "step_latencies_ms": [round(x, 1) for x in lat],
+                  "load_avg_block_ms": round(avg_launch_ms, 4), "load_gbps": round(achieved, 3),
+                  "offload_avg_launch_ms": round(out_launch_ms, 4),
+                  "offload_gbps": round(avg_launch_bytes / out_launch_ms / 1e6, 3), "bytes_per_launch": avg_launch_bytes,
+                  "launches_per_swap": n_launch}
+        ctx.close()
+        del tensors
+        pool.close()
+        print(json.dumps(result), flush=True)
+        return
 
     # the largest product of a layer (fc1: [M, h] x [f/t, h]^T) alone, for the MFMA roofline
     gM, gN, gK = M, desc.local_ffn, desc.hidden
@@ -376,7 +404,12 @@ def run_swap(args):
         "kernel": ("copy_table_kernel<1, 256> (HBM -> host, one launch per transfer block)" if offloads_by_kernel
                    else "hipMemcpyAsync HBM -> host, not a kernel of this library"),
         "bound": "host_link", "achieved": round(avg_launch_bytes / out_launch_ms / 1e6, 3), "peak": round(link["d2h"], 3),
-        "unit": "GB/s", "frac": round(avg_launch_bytes / out_launch_ms / 1e6 / link["d2h"], 4), "traffic": None,
+        "unit": "GB/s", "frac": round(avg_launch_bytes / out_launch_ms / 1e6 / link["d2h"], 4),
+        "traffic": (sum(COPY_KERNEL_OUT_TRAFFIC[args.config].values())
+                    if offloads_by_kernel and args.config in COPY_KERNEL_OUT_TRAFFIC else None),
+        "traffic_detail": (dict(COPY_KERNEL_OUT_TRAFFIC[args.config], note="per layer-block launch: bytes fetched from HBM + bytes "
+                                "written over the host link; algorithmic = 201,404,416 each")
+                           if offloads_by_kernel and args.config in COPY_KERNEL_OUT_TRAFFIC else None),
         "bytes_per_launch": avg_launch_bytes, "avg_launch_ms": round(out_launch_ms, 4), "launches_timed": 2 * n_launch,
         "measured_over": "timed region: the last offload of each of the two models, start event to end event over its "
                          f"{n_launch} back-to-back launches",
@@ -542,7 +575,11 @@ def run_counters(args):
     for _ in range(max(1, args.repeat)):
         ctx.infer(m, token_ids(cfg["idseed"], batch, seq, desc.vocab), out=logits)
     ctx.sync()
-    ctx.swap_out(m); ctx.wait(m)                             # copy_table_kernel<1> x (layers + 1)
+    ctx.swap_out(m); ctx.wait(m)                             # copy_table_kernel<1, 256> x (layers + 1), 128 wavefronts wide
+    for waves in (8, 12):                                    # the two widths of an offload that runs beside a load
+        ctx.set_copy_width(0, waves)
+        ctx.swap_in(m); ctx.wait(m)
+        ctx.swap_out(m); ctx.wait(m)
     ctx.close()
     del tensors
     pool.close()
@@ -589,6 +626,8 @@ def main():
     ap.add_argument("--workload", choices=["swap", "serve", "grid", "cyclic", "scaling", "mixed", "counters"], default="swap")
     ap.add_argument("--config", default="opt6.7b_tp2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-timed", action="store_true",
+                    help="swap workload: warm-up and timed steps only, none of the side measurements (for profiler runs)")
     ap.add_argument("--duration", type=float, default=30.0, help="grid workload: seconds of arrivals per trial")
     ap.add_argument("--requests", type=int, default=0, help="serve workload: number of requests (0: all 2000)")
     ap.add_argument("--transfer", choices=sorted(MODES), default="auto",

@@ -32,6 +32,8 @@ def test_roofline_constants_are_the_published_peaks():
     # traffic constants taken from the committed counter summaries stay within a few percent of the algorithmic bytes
     copy = bench.COPY_KERNEL_TRAFFIC["opt6.7b_tp2"]
     assert abs(copy["fetch_bytes"] / 201404416 - 1) < 0.01 and abs(copy["write_bytes"] / 201404416 - 1) < 0.01
+    out = bench.COPY_KERNEL_OUT_TRAFFIC["opt6.7b_tp2"]
+    assert abs(out["fetch_bytes"] / 201404416 - 1) < 0.01 and abs(out["write_bytes"] / 201404416 - 1) < 0.01
     assert abs(bench.LAYERNORM_TRAFFIC["opt6.7b_tp2"] / (6 * 1024 * 4096) - 1) < 0.02
     for tokens, fetched in bench.SMALL_REQUEST_FETCH["opt6.7b_tp2"].items():
         assert 1.0 <= fetched / 6667665408 < 1.25, tokens
