@@ -19,7 +19,8 @@
  *     HIP device addresses.  Each argument says which it is.
  *   - The library never allocates or frees device memory: the arena, the
  *     workspace and the streams belong to the caller and must outlive the
- *     context.  It owns only host-side descriptors and its events.
+ *     context.  It owns only host-side descriptors, its events and a few KB
+ *     of pinned host memory in which it stages token ids.
  *   - A context is not thread safe; use one host thread per context.
  *   - An engine borrows its context: destroy engines before their context.
  *     "streams ... belong to the caller" applies when the caller passes
@@ -60,7 +61,7 @@ enum { CTN_XFER_DMA = 0, CTN_XFER_KERNEL = 1, CTN_XFER_AUTO = 2,
  * the layers [stage*layers/pp, (stage+1)*layers/pp); stage 0 also holds the
  * embeddings, the last stage the final LayerNorm and its own copy of the tied
  * head matrix.  pp of 0 or 1: all layers.  Requirements: hidden % heads == 0,
- * head size 64 or 128, heads % tp == 0, ffn % tp == 0, vocab % tp == 0,
+ * hidden <= 8192, head size 64 or 128, heads % tp == 0, ffn % tp == 0, vocab % tp == 0,
  * (hidden/tp) % 8 == 0, (ffn/tp) % 8 == 0, 0 <= rank < tp, max_pos >= 1,
  * layers % pp == 0, 0 <= stage < pp. */
 typedef struct {
@@ -216,7 +217,9 @@ int ctn_sync(ctn_ctx* ctx);
  * values in [0, vocab)): logits fp32 [batch, seq, vocab/tp].  Row-parallel
  * products are this rank's partial sums (the cross-rank reduction is the
  * identity on one GPU).  Counts as a use; a non-resident model is swapped in
- * first (demand paging, Section 3).  logits_out is a device pointer when
+ * first (demand paging, Section 3).  token_ids_host (ordinary host memory) is
+ * copied into a pinned staging buffer of the context before the call returns,
+ * in every case, so the caller may reuse it at once.  logits_out is a device pointer when
  * out_is_device != 0 (the call returns with the work enqueued on the compute
  * stream), else pinned or ordinary host memory (the call returns after the
  * logits have arrived).  Errors: CTN_E_SHAPE when seq > max_pos or the
@@ -262,9 +265,6 @@ int ctn_get_block_events(ctn_ctx* ctx, uint64_t first, ctn_block_event* out, uin
  * embeddings with the final LayerNorm, then each layer).  Blocks until they have finished. */
 int ctn_last_swap_ms(ctn_ctx* ctx, ctn_model m, float* in_ms, float* out_ms, float* block_ms,
                      int32_t cap, int32_t* n_blocks);
-/* Reads the device copy of tensor `index` of a resident model into dst (host,
- * at least that tensor's nbytes); waits for the model's load first.  Tests. */
-int ctn_debug_read_param(ctn_ctx* ctx, ctn_model m, int32_t index, void* dst_host, uint64_t cap);
 /* The three streams in use (hipStream_t), the library's own or the caller's. */
 int ctn_get_streams(ctn_ctx* ctx, void** compute, void** h2d, void** d2h);
 /* Library-owned streams only: replay captured HIP graphs for inferences on completely resident
@@ -281,22 +281,6 @@ int ctn_set_copy_width(ctn_ctx* ctx, int32_t blocks_in, int32_t waves_out);
 /* HIP status behind the last CTN_E_HIP of this context (ctx == NULL: of calls that take no context). */
 int ctn_last_hip_error(ctn_ctx* ctx);
 const char* ctn_strerror(int code);
-
-/* Host only, no device needed: replays a sequence of uses (trace, host array
- * of n model indices below n_models) through the same replacement policy the
- * context uses (Section 3 demand paging with Section 4's LRU, byte budget)
- * and writes one event per use to out (host, n entries). */
-int ctn_residency_replay(uint64_t budget_bytes, const uint64_t* sizes, int32_t n_models,
-                         const int32_t* trace, uint64_t n, ctn_event* out);
-
-/* The same for block residency: model i has n_blocks[i] blocks whose parameter
- * bytes follow each other in block_bytes (host, sum of n_blocks entries).
- * out receives one event per use (victims: models that lost blocks, least
- * recently used first), blocks_out up to cap block-level records (*n_blocks_out
- * = number produced; CTN_E_INVAL when cap is too small). */
-int ctn_block_residency_replay(uint64_t budget_bytes, const int32_t* n_blocks, const uint64_t* block_bytes,
-                               int32_t n_models, const int32_t* trace, uint64_t n, ctn_event* out,
-                               ctn_block_event* blocks_out, uint64_t cap, uint64_t* n_blocks_out);
 
 /* ---- serving engine (Section 3.1: per-model request queues, oldest first;
  *      Section 5.2: maximum batch size) ----------------------------------------- */
@@ -335,7 +319,8 @@ int ctn_engine_pending(ctn_engine* eng, int64_t* n);
  * followed, block by block, by its batch; a model whose miss is in flight is
  * not dispatched again until that batch has completed.  Needs a context with
  * library-owned streams and twice the workspace of ctn_workspace_bytes() (each
- * lane works in its own half).  ctn_engine_step is not available on it. */
+ * lane works in its own half; destroying the engine gives the context its whole
+ * workspace back).  ctn_engine_step is not available on it. */
 int ctn_engine_create_async(ctn_ctx* ctx, int32_t max_batch, int32_t seq, ctn_engine** out);
 /* Dispatches at most one batch: the non-empty queues are scanned oldest head
  * first and the first whose lane is free and whose model is not loading goes.
@@ -363,27 +348,6 @@ int ctn_engine_set_prefetch(ctn_engine* eng, int32_t enable, int32_t min_count, 
  * for the replacement policy, victims evicted as needed).  *loaded receives
  * that model's handle, -1 when nothing was done. */
 int ctn_engine_idle(ctn_engine* eng, ctn_model* loaded);
-/* Host only: the prediction after each of n dispatches (host arrays; -1 = none). */
-int ctn_predictor_replay(int32_t n_models, int32_t min_count, int32_t min_share_percent,
-                         const int32_t* dispatches, uint64_t n, int32_t* predictions);
-/* Host only, simulated clock: replays a trace (arrival times ascending, host
- * arrays of n entries) through the same queues, batch selection and
- * replacement policy; a batch of b requests takes t_base + b * t_per_request
- * (+ t_miss when its model was not resident) and the next one is dispatched
- * when it has finished.  batches (cap entries) and requests (n entries) are
- * host arrays. */
-int ctn_engine_replay(int32_t n_models, int32_t max_batch, uint64_t budget_bytes, const uint64_t* sizes,
-                      const double* arrival, const int32_t* model_of, uint64_t n, double t_base,
-                      double t_per_request, double t_miss, ctn_batch_record* batches, uint64_t cap,
-                      uint64_t* n_batches, uint64_t* requests);
-/* The same for the two-lane engine (ctn_engine_dispatch's rule on a simulated
- * clock: each lane runs one batch at a time, a miss occupies lane 1 for
- * t_base + b * t_per_request + t_miss); batches[i].reserved holds the lane. */
-int ctn_engine_replay_async(int32_t n_models, int32_t max_batch, uint64_t budget_bytes, const uint64_t* sizes,
-                            const double* arrival, const int32_t* model_of, uint64_t n, double t_base,
-                            double t_per_request, double t_miss, ctn_batch_record* batches, uint64_t cap,
-                            uint64_t* n_batches, uint64_t* requests);
-
 /* ---- single operations (each enqueues on `stream`, a hipStream_t; all data
  *      pointers are device pointers unless stated) --------------------------- */
 
@@ -430,27 +394,6 @@ int ctn_op_gemm_ws(const void* A_f16, const void* W_f16, const void* bias_f16, v
 int ctn_op_gemm_static(const void* A_f16, const void* W_f16, const void* bias_f16, void* out, int32_t M,
                        int32_t N, int32_t K, int32_t epilogue, void* stream);
 uint64_t ctn_static_scratch_bytes(void);
-/* Test and tuning hook, process wide: forces tile configuration cfg on every product of ctn_op_gemm and
- * ctn_infer; -1 restores the library's choice.
- *   0        128x128x64 tiles, filled straight from global memory into LDS when K is a multiple of 64
- *   1..8, 11..13  the other register-staged tile shapes
- *   9, 10    the streaming kernels for M <= 64 (ignored for larger M)
- *   14, 15   split-K over 64x64 / 32x128 tiles where a workspace is given
- *   16       the row-contiguous streaming kernel for M <= 16 (ignored for larger M)
- *   17       128x128x64 tiles always staged through registers
- * Switches that force no tile (all default on; 100..107 change no result):
- *   100 / 101  direct global -> LDS fills off / on
- *   102 / 103  the register-staged tiles' second stage of loads in flight off / on (where K is a multiple
- *              of the tile's K step)
- *   104 / 105  off / on: a K-sliced row-parallel product inside ctn_infer leaves the sum of its slices to the
- *              LayerNorm that follows
- *   106 / 107  off / on: the second pass of a K-sliced product reads four columns per thread with every
- *              slice in flight
- *   108 / 109  off / on: where the last round of 128x128 tiles would fill at most half of the chip, its columns
- *              are computed in K slices by a second launch (a workspace is needed; the order of the fp32
- *              additions in those columns differs from the one-launch product, nothing else)
- * CTN_E_INVAL for any other value. */
-int ctn_debug_gemm_tile(int32_t cfg);
 /* Causal self-attention of every (batch, head): qkv fp16 [batch*seq, 3*heads*d]
  * holds q | k | v side by side; out fp16 [batch*seq, heads*d]
  * = softmax_causal((q d^-1/2) k^T) v.  d is 64 or 128. */

@@ -23,7 +23,7 @@ DECLARED_SYMBOLS = [
     "ctn_slot_bytes", "ctn_resident_blocks", "ctn_get_block_events", "ctn_block_residency_replay",
     "ctn_engine_set_prefetch", "ctn_engine_idle", "ctn_predictor_replay", "ctn_infer_stage",
     "ctn_engine_create_async", "ctn_engine_dispatch", "ctn_engine_lanes", "ctn_engine_replay_async",
-    "ctn_set_discard", "ctn_op_gemm_static", "ctn_static_scratch_bytes", "ctn_set_copy_width",
+    "ctn_set_discard", "ctn_op_gemm_static", "ctn_static_scratch_bytes", "ctn_set_copy_width", "ctn_test_op_gemm",
 ]
 
 
@@ -132,7 +132,8 @@ def lib() -> C.CDLL:
         "ctn_op_attention": (C.c_int, [vp, vp, i32, i32, i32, i32, vp]),
         "ctn_op_gemm_static": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, vp]),
         "ctn_static_scratch_bytes": (u64, []),
-        "ctn_debug_gemm_tile": (C.c_int, [i32]),
+        "ctn_debug_gemm_tile": (C.c_int, [vp, i32]),
+        "ctn_test_op_gemm": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, vp, u64, P(i32), i32, vp]),
         "ctn_engine_create": (C.c_int, [vp, i32, i32, P(vp)]),
         "ctn_engine_destroy": (C.c_int, [vp]),
         "ctn_engine_submit": (C.c_int, [vp, i32, vp, C.c_double, P(i64)]),
@@ -515,6 +516,10 @@ class Context:
                     "ctn_debug_read_param")
         return dst
 
+    def debug_gemm_tile(self, cfg: int):
+        """Test / tuning switch for this context's products (ctn_debug_gemm_tile)."""
+        self._check(lib().ctn_debug_gemm_tile(self.h, cfg), "ctn_debug_gemm_tile")
+
     def set_graphs(self, enable: bool):
         self._check(lib().ctn_set_graphs(self.h, int(bool(enable))), "ctn_set_graphs")
 
@@ -581,5 +586,13 @@ def op_attention(qkv, out, batch, seq, heads, head_dim, stream):
         "ctn_op_attention")
 
 
-def debug_gemm_tile(cfg: int):
-    _op(lib().ctn_debug_gemm_tile(cfg), "ctn_debug_gemm_tile")
+def test_op_gemm(A, W, bias, out, M, N, K, epilogue, workspace, hooks, stream):
+    """ctn_op_gemm_ws under an explicit list of test switches (see ctn_debug_gemm_tile); workspace may be None."""
+    nbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    hooks = [int(h) for h in hooks]
+    arr = (C.c_int32 * max(len(hooks), 1))(*hooks)
+    _op(lib().ctn_test_op_gemm(_addr(A), _addr(W), _addr(bias), _addr(out), M, N, K, epilogue, _addr(workspace), nbytes,
+                               arr, len(hooks), stream.cuda_stream), "ctn_test_op_gemm")
+
+
+test_op_gemm.__test__ = False      # (not a pytest test, whatever module imports it)

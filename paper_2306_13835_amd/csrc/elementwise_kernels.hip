@@ -5,6 +5,7 @@
 // bandwidth: embed reads 2*hidden*2 B and writes 4*hidden B per token,
 // LayerNorm reads 4*hidden B and writes 2*hidden B per row.
 #include "kernels.h"
+#include "layout.hpp"
 
 namespace ctn {
 
@@ -236,7 +237,8 @@ hipError_t launch_embed(const int32_t* ids, const _Float16* tok, const _Float16*
 hipError_t launch_layernorm(float* x, const _Float16* g, const _Float16* b, _Float16* out, int rows, int hidden,
                             hipStream_t s, const PendingSum* pending) {
   if (rows <= 0) return hipSuccess;
-  if (hidden % 4 || hidden <= 0 || hidden > 256 * 4 * 8) return hipErrorInvalidValue;
+  static_assert(kMaxHidden == 256 * 4 * 8, "registration admits exactly the widths these kernels cover");
+  if (hidden % 4 || hidden <= 0 || hidden > kMaxHidden) return hipErrorInvalidValue;
   const bool fuse = pending && pending->splits > 0;
   const PendingSum pend = fuse ? *pending : PendingSum{};
   const dim3 grid(rows);

@@ -30,6 +30,17 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// The switches a launch runs under: the caller's (a context's, or a test's) or the defaults.  They are
+// scoped to the host thread for the duration of one launch_gemm call, never process wide.
+thread_local const GemmTuning* t_tuning = nullptr;
+const GemmTuning kDefaultTuning{};
+inline const GemmTuning& tuning() { return t_tuning ? *t_tuning : kDefaultTuning; }
+struct TuningScope {
+  const GemmTuning* prev;
+  explicit TuningScope(const GemmTuning* t) : prev(t_tuning) { t_tuning = t; }
+  ~TuningScope() { t_tuning = prev; }
+};
+
 constexpr int LDS_PAD = 8;      // halves of padding per LDS row (16 bytes)
 constexpr int kXcds = 8;
 
@@ -351,7 +362,6 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, 2) void gemm_nt_deep_ke
   gemm_nt_deep_body<BM, BN, BK, WM, WN, EPI>(g);
 }
 
-bool g_deep_loads = true;   // tuning hook: loads two steps ahead where K is a multiple of the tile's K step
 
 template <int BM, int BN, int BK, int WM, int WN>
 hipError_t launch_tiles(const GemmArgs& g, int epi, hipStream_t s) {
@@ -364,7 +374,7 @@ hipError_t launch_tiles(const GemmArgs& g, int epi, hipStream_t s) {
                          ((kWaves == 4 && 4 * (BM + BN) * (BK + 8) <= 80 * 1024) || kWaves == 8);
   // (128x128 per wavefront already fills the register file with accumulators: no room for a second set;
   // the 8-wave tiles sit at their 128-register limit and measured 7 % slower with it)
-  const bool deep = g_deep_loads && g.K % BK == 0 && WM * WN < 128 * 128 && kWaves <= 4;
+  const bool deep = tuning().deep_loads && g.K % BK == 0 && WM * WN < 128 * 128 && kWaves <= 4;
 #define CTN_GEMM(E)                                                                                  \
   do {                                                                                               \
     if constexpr (kOcc2) {                                                                           \
@@ -526,7 +536,6 @@ __global__ __launch_bounds__(256, 2) void gemm_dma_kernel(const GemmArgs g) {
   store_tile<TM, TN, EPI>(g, acc, bias, g.out, m0 + wm0, n0 + wn0, col0, ldc, split, lane);
 }
 
-bool g_direct_fill = true;   // tuning hook: direct-to-LDS fills for the 128x128x64 tiles where K allows
 
 hipError_t launch_dma_tiles(const GemmArgs& g, int epi, hipStream_t s) {
   const int tiles = ((g.M + 127) / 128) * ((g.N + 127) / 128) * g.parts * g.splits;
@@ -857,10 +866,9 @@ void launch_reduce4(const GemmArgs& g, hipStream_t s) {
   else hipLaunchKernelGGL((splitk_reduce4_kernel<EPI, 16>), grid, block, 0, s, g);
 }
 
-bool g_reduce4 = true;   // test hook: the four-column reduction where the shape allows it
 
 hipError_t launch_splitk_reduce(const GemmArgs& g, int epi, hipStream_t s) {
-  if (g_reduce4 && g.N % 4 == 0 && g.ldc % 4 == 0 && g.splits <= 16 &&
+  if (tuning().reduce4 && g.N % 4 == 0 && g.ldc % 4 == 0 && g.splits <= 16 &&
       reinterpret_cast<uintptr_t>(g.out) % 16 == 0 && reinterpret_cast<uintptr_t>(g.partial) % 16 == 0 &&
       (epi == CTN_EPI_F32 || (reinterpret_cast<uintptr_t>(g.bias[0]) % 8 == 0 &&
                               (g.parts < 2 || reinterpret_cast<uintptr_t>(g.bias[1]) % 8 == 0) &&
@@ -888,13 +896,11 @@ hipError_t launch_splitk_reduce(const GemmArgs& g, int epi, hipStream_t s) {
   return hipGetLastError();
 }
 
-int g_force_tile = -1;   // test / tuning hook: tile configuration forced for every product
-bool g_defer_sums = true; // test hook: a split residual product may leave its summation to the caller's LayerNorm
 
 hipError_t launch_config(int cfg, const GemmArgs& g, int epi, hipStream_t s) {
   switch (cfg) {
     case 0:
-      if (g_direct_fill && g.K % 64 == 0) return launch_dma_tiles(g, epi, s);
+      if (tuning().direct_fill && g.K % 64 == 0) return launch_dma_tiles(g, epi, s);
       return launch_tiles<128, 128, 64, 64, 64>(g, epi, s);
     case 17: return launch_tiles<128, 128, 64, 64, 64>(g, epi, s);   // the register-staged loop, whatever K
     case 1: return launch_tiles<128, 64, 64, 64, 32>(g, epi, s);
@@ -936,7 +942,7 @@ hipError_t launch_splitk(GemmArgs g, int cfg, int splits, int epi, hipStream_t s
   g.splits = splits;
   hipError_t e = launch_config(cfg, g, EPI_PARTIAL, s);
   if (e != hipSuccess) return e;
-  if (g_defer_sums && defer && epi == CTN_EPI_BIAS_RESID_F32 && g.parts == 1 && g.ldc == g.N) {
+  if (tuning().defer_sums && defer && epi == CTN_EPI_BIAS_RESID_F32 && g.parts == 1 && g.ldc == g.N) {
     // the caller's next kernel, a LayerNorm, reads x anyway and finishes the update there (with
     // few rows its variant that keeps every slice's load in flight at once: one kernel and one
     // memory round trip in place of two kernels)
@@ -948,7 +954,6 @@ hipError_t launch_splitk(GemmArgs g, int cfg, int splits, int epi, hipStream_t s
   return launch_splitk_reduce(g, epi, s);
 }
 
-bool g_tail_split = true;   // test hook: columns of a thinly filled last round computed in K slices
 
 hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_floats, PendingSum* defer = nullptr,
                     bool allow_tail = true) {
@@ -957,13 +962,13 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
   if (g.K <= 0 || g.K % 8 || g.parts < 1 || g.parts > 3) return hipErrorInvalidValue;
   for (int p = 0; p < g.parts; ++p)
     if (!g.W[p] || (epi != CTN_EPI_F32 && !g.bias[p])) return hipErrorInvalidValue;
-  if (g_force_tile == 14 || g_force_tile == 15) {       // tuning hook: split-K over 64x64 / 32x128 tiles
-    const int cfg = g_force_tile == 14 ? 6 : 7;
+  if (tuning().force_tile == 14 || tuning().force_tile == 15) {       // tuning hook: split-K over 64x64 / 32x128 tiles
+    const int cfg = tuning().force_tile == 14 ? 6 : 7;
     const int splits = g.partial ? choose_splits(g, cfg == 6 ? 64 : 32, cfg == 6 ? 64 : 128, partial_floats) : 1;
     return splits > 1 ? launch_splitk(g, cfg, splits, epi, s, defer) : launch_config(cfg, g, epi, s);
   }
-  if (g_force_tile >= 0 && !(g_force_tile >= 9 && g_force_tile <= 10 && g.M > 64) && !(g_force_tile == 16 && g.M > 16))
-    return launch_config(g_force_tile, g, epi, s);
+  if (tuning().force_tile >= 0 && !(tuning().force_tile >= 9 && tuning().force_tile <= 10 && g.M > 64) && !(tuning().force_tile == 16 && g.M > 16))
+    return launch_config(tuning().force_tile, g, epi, s);
   if (g.M <= 64) {
     // measured on MI355X: very wide outputs (the vocabulary head) re-read A too often in the
     // streaming kernel; mid-size outputs take 32 features per workgroup to halve A's L2 traffic
@@ -1008,7 +1013,7 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
   // vocabulary head) costs nearly a whole round.  The columns of the full rounds go out as one product and
   // the remaining columns as a second one whose tiles are cut along K, so that its workgroups fill the
   // chip too and each takes a fraction of a tile's time; a third, small kernel adds the slices in order.
-  if (g_tail_split && allow_tail && g.partial && g.parts == 1 && t0 > 512 && t0 % 512 && t0 % 512 <= 256 &&
+  if (tuning().tail_split && allow_tail && g.partial && g.parts == 1 && t0 > 512 && t0 % 512 && t0 % 512 <= 256 &&
       g.K >= 2048 && g.K % 64 == 0) {
     const int tiles_m = (g.M + 127) / 128, tiles_n = (g.N + 127) / 128;
     const int n_main = (t0 / 512) * 512 / tiles_m;                  // column tiles of the full rounds
@@ -1049,41 +1054,43 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
     // a short K (the out-projection of a finely split shard: K = hidden / TP) has few steps per tile to hide
     // a stage's latency behind; half-size steps do better (13B / TP4 forward 22.4 -> 21.9 ms)
     if (g.K <= 2560) return launch_config(5, g, epi, s);
-    return launch_config(g_deep_loads && g.K % 64 == 0 ? 17 : 13, g, epi, s);
+    return launch_config(tuning().deep_loads && g.K % 64 == 0 ? 17 : 13, g, epi, s);
   }
   return launch_config(0, g, epi, s);
 }
 
 }  // namespace
 
-int gemm_force_tile(int cfg) {
-  if (cfg == 100 || cfg == 101) {      // tuning hook: direct-to-LDS stage fills off / on
-    g_direct_fill = cfg == 101;
+int gemm_tuning_set(GemmTuning& t, int cfg) {
+  if (cfg == 100 || cfg == 101) {      // direct-to-LDS stage fills off / on
+    t.direct_fill = cfg == 101;
     return 0;
   }
-  if (cfg == 102 || cfg == 103) {      // tuning hook: global loads two steps ahead off / on
-    g_deep_loads = cfg == 103;
+  if (cfg == 102 || cfg == 103) {      // global loads two steps ahead off / on
+    t.deep_loads = cfg == 103;
     return 0;
   }
-  if (cfg == 108 || cfg == 109) {      // test hook: K-sliced tail columns off / on
-    g_tail_split = cfg == 109;
+  if (cfg == 108 || cfg == 109) {      // K-sliced tail columns off / on
+    t.tail_split = cfg == 109;
     return 0;
   }
-  if (cfg == 106 || cfg == 107) {      // test hook: four-column split-K reduction off / on
-    g_reduce4 = cfg == 107;
+  if (cfg == 106 || cfg == 107) {      // four-column split-K reduction off / on
+    t.reduce4 = cfg == 107;
     return 0;
   }
-  if (cfg == 104 || cfg == 105) {      // test hook: summation of split residual products left to LayerNorm off / on
-    g_defer_sums = cfg == 105;
+  if (cfg == 104 || cfg == 105) {      // summation of split residual products left to LayerNorm off / on
+    t.defer_sums = cfg == 105;
     return 0;
   }
   if (cfg < -1 || cfg > 17) return -1;
-  g_force_tile = cfg;
+  t.force_tile = cfg;
   return 0;
 }
 
 hipError_t launch_gemm(const _Float16* A, const _Float16* W, const _Float16* bias, void* out, int M, int N,
-                       int K, int epi, hipStream_t s, float* partial, size_t partial_floats, PendingSum* defer) {
+                       int K, int epi, hipStream_t s, float* partial, size_t partial_floats, PendingSum* defer,
+                       const GemmTuning* tune) {
+  const TuningScope scope(tune);
   GemmArgs g{};
   g.A = A; g.W[0] = W; g.bias[0] = bias; g.out = out;
   g.M = M; g.N = N; g.K = K; g.ldc = N; g.parts = 1; g.splits = 1; g.partial = partial;
@@ -1091,7 +1098,9 @@ hipError_t launch_gemm(const _Float16* A, const _Float16* W, const _Float16* bia
 }
 
 hipError_t launch_gemm3(const _Float16* A, const _Float16* const W[3], const _Float16* const bias[3], void* out,
-                        int M, int N, int K, int epi, hipStream_t s, float* partial, size_t partial_floats) {
+                        int M, int N, int K, int epi, hipStream_t s, float* partial, size_t partial_floats,
+                        const GemmTuning* tune) {
+  const TuningScope scope(tune);
   GemmArgs g{};
   g.A = A; g.out = out;
   for (int p = 0; p < 3; ++p) { g.W[p] = W[p]; g.bias[p] = bias[p]; }

@@ -45,20 +45,29 @@ hipError_t launch_layernorm(float* x, const _Float16* g, const _Float16* b, _Flo
                             hipStream_t s, const PendingSum* pending = nullptr);
 
 // ---- dense products ------------------------------------------------------------
+// Switches for tests and tuning runs; the defaults are what the library uses.  The values of
+// gemm_tuning_set are listed at ctn_debug_gemm_tile in the test header.
+struct GemmTuning {
+  int force_tile = -1;        // >= 0: one tile configuration for every product
+  bool deep_loads = true;     // register-staged tiles keep a second stage of loads in flight
+  bool direct_fill = true;    // 128x128x64 tiles filled straight from global memory into LDS
+  bool reduce4 = true;        // the second pass of a K-sliced product reads four columns per thread
+  bool defer_sums = true;     // a K-sliced row-parallel product may leave its sum to the next LayerNorm
+  bool tail_split = true;     // columns of a thinly filled last round of tiles computed in K slices
+};
+int gemm_tuning_set(GemmTuning& t, int cfg);   // 0, or -1 for a value that means nothing
 // partial / partial_floats: optional fp32 scratch (device) that allows small-M products to split K
 // across workgroups; nullptr keeps every product in one pass.
 // defer (optional, residual epilogue only): when the product is split, leave the summation of the
 // slices and the residual update to the caller (*defer describes it) instead of running the reduce kernel.
+// tune (optional): switches for this call; nullptr = defaults.
 hipError_t launch_gemm(const _Float16* A, const _Float16* W, const _Float16* bias, void* out, int M, int N,
                        int K, int epilogue, hipStream_t s, float* partial = nullptr, size_t partial_floats = 0,
-                       PendingSum* defer = nullptr);
-// Test / tuning hook: force one tile configuration (0..17) for every product, -1 restores the heuristic;
-// 100..107 switch single mechanisms off / on (the values are listed at ctn_debug_gemm_tile in the C header).
-int gemm_force_tile(int cfg);
+                       PendingSum* defer = nullptr, const GemmTuning* tune = nullptr);
 // Three products sharing A in one launch: out[M, 3N] = [A W0^T + b0 | A W1^T + b1 | A W2^T + b2].
 hipError_t launch_gemm3(const _Float16* A, const _Float16* const W[3], const _Float16* const bias[3], void* out,
                         int M, int N, int K, int epilogue, hipStream_t s, float* partial = nullptr,
-                        size_t partial_floats = 0);
+                        size_t partial_floats = 0, const GemmTuning* tune = nullptr);
 hipError_t launch_attention(const _Float16* qkv, _Float16* out, int batch, int seq, int heads, int head_dim,
                             hipStream_t s);
 

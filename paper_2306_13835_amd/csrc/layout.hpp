@@ -27,6 +27,7 @@ namespace ctn {
 constexpr uint64_t kAlign = 256;
 constexpr int kLayerTensors = 16;
 constexpr int kPosOffset = 2;  // OPT keeps position rows shifted by two
+constexpr int kMaxHidden = 8192;
 
 inline uint64_t align_up(uint64_t x, uint64_t a = kAlign) { return (x + a - 1) / a * a; }
 
@@ -84,6 +85,7 @@ inline bool desc_valid(const ctn_model_desc& d) {
   int hd = d.hidden / d.heads;
   if (hd != 64 && hd != 128) return false;
   if ((d.hidden / d.tp) % 8 || (d.ffn / d.tp) % 8 || d.hidden % 8) return false;
+  if (d.hidden > kMaxHidden) return false;      // widest row the LayerNorm kernels hold in registers
   return true;
 }
 

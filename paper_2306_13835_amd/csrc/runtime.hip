@@ -18,6 +18,7 @@
 #include <vector>
 
 #include "computron.h"
+#include "computron_test.h"
 #include "engine.hpp"
 #include "kernels.h"
 #include "layout.hpp"
@@ -120,6 +121,18 @@ struct RetiredGraphs {   // captured forward passes of an evicted placement; des
   hipEvent_t done;
 };
 
+// Token ids of one inference, staged in pinned, device-mapped host memory that the context owns: the
+// caller's buffer is free again when ctn_infer returns, and the embedding kernel reads the few KB
+// straight over the link instead of waiting for a separate copy.
+struct IdSlot {
+  int32_t* host = nullptr;
+  int32_t* dev = nullptr;          // the same memory as the device sees it
+  size_t cap = 0;                  // ids
+  hipEvent_t done = nullptr;       // recorded after the last kernel that reads the slot
+  bool used = false;
+};
+constexpr int kIdSlots = 8;
+
 struct Activations {   // carved from the workspace for one inference of M tokens
   int32_t* ids;
   float* x;
@@ -158,6 +171,9 @@ struct ctn_ctx {
   std::vector<ctn_event> events;
   ctn_stats stats{};
   int last_hip = 0;
+  GemmTuning tuning;                 // test / tuning switches of this context's products (defaults: none)
+  IdSlot id_slots[kIdSlots];
+  int next_id_slot = 0;
 };
 
 namespace {
@@ -628,8 +644,8 @@ T* dev_tensor(ctn_ctx* c, Model* m, int ti) {
 // The launch sequence of one forward pass on stream s.  with_waits: wait for the
 // transfer blocks' events (not needed, and not capturable across loads, when the
 // model is known to be completely resident).
-int forward_launches(ctn_ctx* c, Model* m, const Activations& act, int batch, int seq, float* logits, hipStream_t s,
-                     bool with_waits) {
+int forward_launches(ctn_ctx* c, Model* m, const Activations& act, const int32_t* ids_dev, int batch, int seq,
+                     float* logits, hipStream_t s, bool with_waits) {
   const ShardLayout& L = m->lay;
   const ctn_model_desc& d = L.d;
   const int M = batch * seq;
@@ -641,11 +657,12 @@ int forward_launches(ctn_ctx* c, Model* m, const Activations& act, int batch, in
     else CTN_HIP(c, hipStreamWaitEvent(s, m->ev_block[0], 0));
   }
 
+  const GemmTuning* tune = &c->tuning;
   // A split-K row-parallel product leaves its residual update to the LayerNorm that follows it.
   PendingSum pend;
   // Stage 0 builds the residual stream from the token ids; later pipeline stages were handed it.
   if (L.has_embed())
-    CTN_HIP(c, launch_embed(act.ids, dev_tensor<_Float16>(c, m, L.idx_tok()), dev_tensor<_Float16>(c, m, L.idx_pos()),
+    CTN_HIP(c, launch_embed(ids_dev, dev_tensor<_Float16>(c, m, L.idx_tok()), dev_tensor<_Float16>(c, m, L.idx_pos()),
                             act.x, M, seq, h, vl, d.rank, s));
   const int n_layers = L.local_layers();
   for (int l = 0; l < n_layers; ++l) {
@@ -655,22 +672,22 @@ int forward_launches(ctn_ctx* c, Model* m, const Activations& act, int batch, in
     // q | k | v: three column-parallel projections of the same input in one launch
     const _Float16* const wqkv[3] = {T(Q_W), T(K_W), T(V_W)};
     const _Float16* const bqkv[3] = {T(Q_B), T(K_B), T(V_B)};
-    CTN_HIP(c, launch_gemm3(act.a, wqkv, bqkv, act.qkv, M, hl, h, CTN_EPI_BIAS_F16, s, act.partial, act.partial_floats));
+    CTN_HIP(c, launch_gemm3(act.a, wqkv, bqkv, act.qkv, M, hl, h, CTN_EPI_BIAS_F16, s, act.partial, act.partial_floats, tune));
     CTN_HIP(c, launch_attention(act.qkv, act.attn, batch, seq, L.local_heads(), L.head_dim(), s));
     // row parallel: this rank's partial sum joins the residual stream (the
     // cross-rank reduction is the identity on one GPU), bias added once
-    CTN_HIP(c, launch_gemm(act.attn, T(O_W), T(O_B), act.x, M, h, hl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats, &pend));
+    CTN_HIP(c, launch_gemm(act.attn, T(O_W), T(O_B), act.x, M, h, hl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats, &pend, tune));
     CTN_HIP(c, launch_layernorm(act.x, T(LN2_W), T(LN2_B), act.a, M, h, s, &pend));
-    CTN_HIP(c, launch_gemm(act.a, T(FC1_W), T(FC1_B), act.u, M, fl, h, CTN_EPI_BIAS_RELU_F16, s, act.partial, act.partial_floats));
+    CTN_HIP(c, launch_gemm(act.a, T(FC1_W), T(FC1_B), act.u, M, fl, h, CTN_EPI_BIAS_RELU_F16, s, act.partial, act.partial_floats, nullptr, tune));
     // (a stage that ends without a final LayerNorm has nobody to finish a deferred update for it)
     PendingSum* after_fc2 = (l + 1 < n_layers || L.has_head()) ? &pend : nullptr;
-    CTN_HIP(c, launch_gemm(act.u, T(FC2_W), T(FC2_B), act.x, M, h, fl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats, after_fc2));
+    CTN_HIP(c, launch_gemm(act.u, T(FC2_W), T(FC2_B), act.x, M, h, fl, CTN_EPI_BIAS_RESID_F32, s, act.partial, act.partial_floats, after_fc2, tune));
   }
   if (!L.has_head()) return CTN_OK;            // the stage emits the residual stream act.x
   CTN_HIP(c, launch_layernorm(act.x, dev_tensor<_Float16>(c, m, L.idx_final_w()),
                               dev_tensor<_Float16>(c, m, L.idx_final_b()), act.a, M, h, s, &pend));
   // head: the token matrix (tied), or the last pipeline stage's own copy of it; vocabulary slice
-  CTN_HIP(c, launch_gemm(act.a, dev_tensor<_Float16>(c, m, L.idx_head()), nullptr, logits, M, vl, h, CTN_EPI_F32, s));
+  CTN_HIP(c, launch_gemm(act.a, dev_tensor<_Float16>(c, m, L.idx_head()), nullptr, logits, M, vl, h, CTN_EPI_F32, s, nullptr, 0, nullptr, tune));
   return CTN_OK;
 }
 
@@ -686,23 +703,23 @@ int forward_graph(ctn_ctx* c, Model* m, const Activations& act, int batch, int s
   if (hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal) != hipSuccess) {
     (void)hipGetLastError();
     c->use_graphs = false;   // this runtime cannot capture here: keep launching directly
-    return forward_launches(c, m, act, batch, seq, logits, s, true);
+    return forward_launches(c, m, act, act.ids, batch, seq, logits, s, true);
   }
-  const int rc = forward_launches(c, m, act, batch, seq, logits, s, false);
+  const int rc = forward_launches(c, m, act, act.ids, batch, seq, logits, s, false);
   const hipError_t e_end = hipStreamEndCapture(s, &graph);
   if (rc || e_end != hipSuccess || !graph) {
     if (graph) (void)hipGraphDestroy(graph);
     (void)hipGetLastError();
     if (rc) return rc;
     c->use_graphs = false;
-    return forward_launches(c, m, act, batch, seq, logits, s, true);
+    return forward_launches(c, m, act, act.ids, batch, seq, logits, s, true);
   }
   const hipError_t e_inst = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
   (void)hipGraphDestroy(graph);
   if (e_inst != hipSuccess || !exec) {
     (void)hipGetLastError();
     c->use_graphs = false;
-    return forward_launches(c, m, act, batch, seq, logits, s, true);
+    return forward_launches(c, m, act, act.ids, batch, seq, logits, s, true);
   }
   if (m->graphs.size() >= 8) {           // bounded cache: drop the oldest capture
     (void)hipGraphExecDestroy(m->graphs.front().exec);
@@ -785,6 +802,10 @@ int ctn_destroy(ctn_ctx* c) {
   if (!c) return CTN_E_INVAL;
   int rc = ctn_sync(c);
   c->models.clear();   // destroys every model's events
+  for (IdSlot& sl : c->id_slots) {
+    if (sl.host) (void)hipHostFree(sl.host);
+    if (sl.done) (void)hipEventDestroy(sl.done);
+  }
   if (c->own_streams) {
     for (hipStream_t st : {c->s_compute, c->s_h2d, c->s_d2h, c->s_wide, c->s_lane1})
       if (st) (void)hipStreamDestroy(st);
@@ -933,6 +954,37 @@ uint64_t ctn_slot_bytes(const ctn_model_desc* desc) {
   return make_layout(*desc).slot_bytes;
 }
 
+// Copies n token ids into the next staging slot (waiting, on the host, for the slot's previous reader
+// if that is still running, which takes kIdSlots inferences in flight).
+static int stage_ids(ctn_ctx* c, const int32_t* ids_host, size_t n, IdSlot** out) {
+  IdSlot& sl = c->id_slots[c->next_id_slot];
+  c->next_id_slot = (c->next_id_slot + 1) % kIdSlots;
+  if (sl.used) CTN_HIP(c, hipEventSynchronize(sl.done));
+  if (sl.cap < n) {
+    if (sl.host) CTN_HIP(c, hipHostFree(sl.host));
+    sl.host = nullptr;
+    sl.cap = 0;
+    size_t cap = 256;
+    while (cap < n) cap *= 2;
+    void* p = nullptr;
+    hipError_t e = hipHostMalloc(&p, 4 * cap, hipHostMallocMapped | hipHostMallocPortable);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      c->last_hip = (int)e;
+      return e == hipErrorOutOfMemory ? CTN_E_NOMEM : CTN_E_HIP;
+    }
+    void* dp = nullptr;
+    CTN_HIP(c, hipHostGetDevicePointer(&dp, p, 0));
+    sl.host = static_cast<int32_t*>(p);
+    sl.dev = static_cast<int32_t*>(dp);
+    sl.cap = cap;
+    if (!sl.done) CTN_HIP(c, hipEventCreateWithFlags(&sl.done, hipEventDisableTiming));
+  }
+  std::memcpy(sl.host, ids_host, 4 * n);
+  *out = &sl;
+  return CTN_OK;
+}
+
 // Enqueues one inference.  *result_dev / *result_bytes describe where the result stands on the
 // device when the caller asked for it in host memory (the caller copies it down).
 static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, const void* hidden_in, int32_t in_is_device,
@@ -974,8 +1026,13 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, cons
     if (c->last_compute && c->last_compute != s) CTN_HIP(c, hipStreamWaitEvent(s, c->ev_compute_done, 0));
   }
   const uint64_t x_bytes = 4ull * M * d.hidden;
+  const bool replayable = c->use_graphs && lane == 0 && s == c->s_wide && !m->pending_in;
+  IdSlot* slot = nullptr;
   if (L.has_embed()) {
-    CTN_HIP(c, hipMemcpyAsync(act.ids, ids_host, 4ull * M, hipMemcpyHostToDevice, s));
+    rc = stage_ids(c, ids_host, M, &slot);
+    if (rc) return rc;
+    // a captured graph reads its ids from the workspace address it was captured with
+    if (replayable) CTN_HIP(c, hipMemcpyAsync(act.ids, slot->host, 4ull * M, hipMemcpyHostToDevice, s));
   } else {
     CTN_HIP(c, hipMemcpyAsync(act.x, hidden_in, x_bytes, in_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, s));
   }
@@ -984,13 +1041,16 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, cons
   // A resident model on an idle link needs no event waits: the whole launch
   // sequence is captured once per (model placement, shape, output) as a HIP
   // graph and replayed, which removes the per-launch host cost of ~400 small kernels.
-  const bool replayable = c->use_graphs && lane == 0 && s == c->s_wide && !m->pending_in;
   if (replayable) {
     rc = forward_graph(c, m, act, batch, seq, logits, s);
   } else {
-    rc = forward_launches(c, m, act, batch, seq, logits, s, true);
+    rc = forward_launches(c, m, act, slot ? slot->dev : nullptr, batch, seq, logits, s, true);
   }
   if (rc) return rc;
+  if (slot) {
+    CTN_HIP(c, hipEventRecord(slot->done, s));
+    slot->used = true;
+  }
   if (!L.has_head()) {       // the stage's result is the residual stream
     if (out_is_device) CTN_HIP(c, hipMemcpyAsync(logits_out, act.x, x_bytes, hipMemcpyDeviceToDevice, s));
     logits = act.x;
@@ -1284,6 +1344,11 @@ int ctn_engine_create_async(ctn_ctx* c, int32_t max_batch, int32_t seq, ctn_engi
 
 int ctn_engine_destroy(ctn_engine* e) {
   if (!e) return CTN_OK;
+  if (e->two_lanes) {
+    // the context goes back to one lane over the whole workspace once nothing runs in the halves
+    (void)ctn_sync(e->ctx);
+    e->ctx->two_lanes = false;
+  }
   for (hipEvent_t ev : e->lane_done)
     if (ev) (void)hipEventDestroy(ev);
   delete e;
@@ -1626,7 +1691,24 @@ int ctn_op_gemm_static(const void* A, const void* W, const void* bias, void* out
 
 uint64_t ctn_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
-int ctn_debug_gemm_tile(int32_t cfg) { return gemm_force_tile(cfg) == 0 ? CTN_OK : CTN_E_INVAL; }
+int ctn_debug_gemm_tile(ctn_ctx* c, int32_t cfg) {
+  if (!c) return CTN_E_INVAL;
+  return gemm_tuning_set(c->tuning, cfg) == 0 ? CTN_OK : CTN_E_INVAL;
+}
+
+int ctn_test_op_gemm(const void* A, const void* W, const void* bias, void* out, int32_t M, int32_t N, int32_t K,
+                     int32_t epilogue, void* workspace, uint64_t workspace_bytes, const int32_t* hooks, int32_t n_hooks,
+                     void* stream) {
+  if (!A || !W || !out || M < 0 || N < 0 || n_hooks < 0 || (n_hooks && !hooks)) return CTN_E_INVAL;
+  if (workspace && reinterpret_cast<uintptr_t>(workspace) % 16) return CTN_E_INVAL;
+  GemmTuning t;
+  for (int i = 0; i < n_hooks; ++i)
+    if (gemm_tuning_set(t, hooks[i]) != 0) return CTN_E_INVAL;
+  return op_rc(launch_gemm(static_cast<const _Float16*>(A), static_cast<const _Float16*>(W),
+                           static_cast<const _Float16*>(bias), out, M, N, K, epilogue,
+                           static_cast<hipStream_t>(stream), static_cast<float*>(workspace), workspace_bytes / 4,
+                           nullptr, &t));
+}
 
 int ctn_op_attention(const void* qkv, void* out, int32_t batch, int32_t seq, int32_t heads, int32_t head_dim,
                      void* stream) {

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "engine.hpp"
+#include "layout.hpp"
 #include "residency.hpp"
 
 using ctn::RangeAllocator;
@@ -175,5 +176,22 @@ int main() {
     assert(q.pick() == 1);                        // equal timestamps: the lower model index wins
   }
   std::puts("host logic ok");
+  {   // shard descriptions: what the kernels cannot run is refused at registration, not at the first inference
+    ctn_model_desc d{};
+    d.layers = 2; d.hidden = 8192; d.ffn = 32768; d.heads = 64; d.vocab = 1024; d.max_pos = 64; d.tp = 2; d.rank = 1;
+    assert(ctn::desc_valid(d));                       // the widest row the LayerNorm kernels hold
+    ctn_model_desc wide = d;
+    wide.hidden = 9216; wide.heads = 72;              // head size 128, divisible by everything, but too wide
+    assert(!ctn::desc_valid(wide));
+    wide.hidden = 12288; wide.heads = 96;
+    assert(!ctn::desc_valid(wide));
+    ctn_model_desc odd = d;
+    odd.hidden = 96 * 64; odd.heads = 64;             // head size 96
+    assert(!ctn::desc_valid(odd));
+    // every layer block fits one copy table whatever the shape
+    const ctn::ShardLayout L = ctn::make_layout(d);
+    for (int b = 1; b < L.n_blocks; ++b) assert((int)L.block_tensors[b].size() == ctn::kLayerTensors);
+    assert((int)L.block_tensors[0].size() <= 5);
+  }
   return 0;
 }

@@ -378,11 +378,9 @@ def test_layernorm_finishing_split_products_changes_no_bit(hidden, heads):
         m = rig.add(desc, seed=240)
         for b, s_ in ((1, 64), (3, 8), (4, 64), (1, 17)):
             ids = token_ids(241 + b, b, s_, desc.vocab)
-            try:
-                B.debug_gemm_tile(104)
-                apart = rig.ctx.infer(m, ids)
-            finally:
-                B.debug_gemm_tile(105)
+            rig.ctx.debug_gemm_tile(104)          # (a switch of this context only)
+            apart = rig.ctx.infer(m, ids)
+            rig.ctx.debug_gemm_tile(105)
             fused = rig.ctx.infer(m, ids)
             assert np.array_equal(fused, apart), (hidden, b, s_)
             if (b, s_) == (1, 64) and hidden <= 5120:      # (the bar is stated for the configs' widths, up to 5120)

@@ -11,6 +11,20 @@ from gpu_util import dev
 pytestmark = pytest.mark.gpu
 
 
+class Hooks:
+    """An explicit list of switch values (see ctn_debug_gemm_tile) for ctn_test_op_gemm: the product runs under
+    exactly these, applied in order to the library's defaults; nothing outlives the call."""
+
+    def __init__(self):
+        self.values = []
+
+    def set(self, cfg):
+        self.values.append(int(cfg))
+
+    def gemm(self, A, W, bias, out, M, N, K, epi, stream, ws=None):
+        B.test_op_gemm(A, W, bias, out, M, N, K, epi, ws, self.values, stream)
+
+
 @pytest.fixture(scope="module")
 def stream():
     torch.cuda.set_device(0)
@@ -145,6 +159,7 @@ def test_attention(stream, batch, seq, heads, d):
                                        (300, 520, 320, P.EPI_BIAS_F16)])
 def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
     """Each tile shape the library can pick, forced through the tuning hook, on ragged sizes."""
+    hooks = Hooks()
     rng = np.random.default_rng(cfg * 1000 + M)
     A, W, bias = f16(rng, (M, K)), f16(rng, (N, K), 0.05), f16(rng, N, 0.5)
     res = rng.standard_normal((M, N)).astype(np.float32)
@@ -157,20 +172,19 @@ def test_gemm_every_tile_configuration(stream, cfg, M, N, K, epi):
         want, out = acc, torch.empty(M, N, dtype=torch.float16, device="cuda")
     else:
         want, out = acc - bias.astype(np.float64), torch.empty(M, N, dtype=torch.float32, device="cuda")
-    B.debug_gemm_tile(cfg)
+    hooks.set(cfg)
     try:
-        B.op_gemm(dev(A), dev(W), dev(bias), out, M, N, K, epi, stream)
+        hooks.gemm(dev(A), dev(W), dev(bias), out, M, N, K, epi, stream)
         stream.synchronize()
     finally:
-        B.debug_gemm_tile(-1)
+        hooks.set(-1)
     got = out.cpu().numpy().astype(np.float64)
     tol = 2.0 ** -10 * np.abs(want) + 1e-4 if out.dtype == torch.float16 else 1e-4
     assert np.all(np.abs(got - want) <= tol)
-    with pytest.raises(P.CtnError):
-        B.debug_gemm_tile(18)
-    for bad in (-2, 99, 110):          # 100..109 are the fill / load-depth / hand-over / reduction / tail switches, nothing else is accepted
-        with pytest.raises(P.CtnError):
-            B.debug_gemm_tile(bad)
+    for bad in (18, -2, 99, 110):      # 100..109 are the fill / load-depth / hand-over / reduction / tail switches, nothing else is accepted
+        with pytest.raises(P.CtnError) as e:
+            B.test_op_gemm(dev(A), dev(W), dev(bias), out, M, N, K, epi, None, [cfg, bad], stream)
+        assert e.value.code == -1
 
 
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5, 6, 7, 11, 12, 13, 14, 15, 17])
@@ -180,6 +194,7 @@ def test_gemm_loads_two_steps_ahead_change_nothing(stream, cfg, M, N, K, epi):
     """The register-staged tiles with a second stage of global loads in flight (K a multiple of the tile's
     K step: one, two, five, seventeen steps; ragged edges; K slices with the workspace) against the plain loop:
     same K order, so the same bits."""
+    hooks = Hooks()
     rng = np.random.default_rng(cfg * 77 + M + K)
     A, W, bias = f16(rng, (M, K)), f16(rng, (N, K), 0.05), f16(rng, N, 0.5)
     res = rng.standard_normal((M, N)).astype(np.float32)
@@ -187,20 +202,20 @@ def test_gemm_loads_two_steps_ahead_change_nothing(stream, cfg, M, N, K, epi):
     ws = torch.full((16 * M * N + 64,), float("nan"), dtype=torch.float32, device="cuda")
     outs = {}
     try:
-        B.debug_gemm_tile(100)                       # (direct fills off, so that configuration 0 is register staged too)
-        B.debug_gemm_tile(cfg)
+        hooks.set(100)                       # (direct fills off, so that configuration 0 is register staged too)
+        hooks.set(cfg)
         for hook in (103, 102):
-            B.debug_gemm_tile(hook)
+            hooks.set(hook)
             out = dev(res) if epi in (P.EPI_BIAS_RESID_F32, P.EPI_F32) else torch.empty(M, N, dtype=torch.float16, device="cuda")
             guard = torch.full((4096,), 7.0, dtype=torch.float32, device="cuda")
-            B.op_gemm_ws(dA, dW, db, out, M, N, K, epi, ws, stream)
+            hooks.gemm(dA, dW, db, out, M, N, K, epi, stream, ws)
             stream.synchronize()
             assert (guard == 7.0).all()
             outs[hook] = out.cpu().numpy()
     finally:
-        B.debug_gemm_tile(103)
-        B.debug_gemm_tile(101)
-        B.debug_gemm_tile(-1)
+        hooks.set(103)
+        hooks.set(101)
+        hooks.set(-1)
     assert np.array_equal(outs[103], outs[102])
     acc = A.astype(np.float64) @ W.astype(np.float64).T
     want = {P.EPI_BIAS_F16: acc + bias.astype(np.float64), P.EPI_BIAS_RELU_F16: np.maximum(acc + bias.astype(np.float64), 0),
@@ -218,6 +233,7 @@ def test_gemm_direct_lds_fill_equals_register_staged(stream, M, N, K, epi):
     """128x128x64 tiles filled straight from global memory into LDS (K a multiple of 64) against the same
     tiles staged through registers: same K order, so the same bits; ragged edges, an odd number of K steps,
     one-step products and (with the workspace, last shape) K slices included."""
+    hooks = Hooks()
     rng = np.random.default_rng(M + 5 * N + K + epi)
     A, W, bias = f16(rng, (M, K)), f16(rng, (N, K), 0.05), f16(rng, N, 0.5)
     res = rng.standard_normal((M, N)).astype(np.float32)
@@ -226,23 +242,23 @@ def test_gemm_direct_lds_fill_equals_register_staged(stream, M, N, K, epi):
     outs = {}
     try:
         for cfg in (0, 17):
-            B.debug_gemm_tile(cfg)
+            hooks.set(cfg)
             out = dev(res) if epi in (P.EPI_BIAS_RESID_F32, P.EPI_F32) else torch.empty(M, N, dtype=torch.float16, device="cuda")
             guard = torch.full((4096,), 7.0, dtype=torch.float32, device="cuda")
-            B.op_gemm(dA, dW, db, out, M, N, K, epi, stream)
+            hooks.gemm(dA, dW, db, out, M, N, K, epi, stream)
             stream.synchronize()
             assert (guard == 7.0).all()
             outs[cfg] = out.cpu().numpy()
-        B.debug_gemm_tile(-1)          # the library's own choice with a workspace (K slices at M = 1024, K = 8192)
+        hooks.set(-1)          # the library's own choice with a workspace (K slices at M = 1024, K = 8192)
         for hook in (101, 100):
-            B.debug_gemm_tile(hook)
+            hooks.set(hook)
             out = dev(res) if epi in (P.EPI_BIAS_RESID_F32, P.EPI_F32) else torch.empty(M, N, dtype=torch.float16, device="cuda")
-            B.op_gemm_ws(dA, dW, db, out, M, N, K, epi, ws, stream)
+            hooks.gemm(dA, dW, db, out, M, N, K, epi, stream, ws)
             stream.synchronize()
             outs[hook] = out.cpu().numpy()
     finally:
-        B.debug_gemm_tile(101)
-        B.debug_gemm_tile(-1)
+        hooks.set(101)
+        hooks.set(-1)
     assert np.array_equal(outs[0], outs[17])
     assert np.array_equal(outs[101], outs[100])
     acc = A.astype(np.float64) @ W.astype(np.float64).T
@@ -262,6 +278,7 @@ def test_gemm_tail_columns_in_k_slices(stream, M, N, K, epi):
     columns of that round are computed in K slices by a second launch and added in a fixed order.  Same bar as
     any other product, the same bits when repeated, nothing written past the output, and close to the
     one-launch result (only the order of the fp32 additions differs in the tail columns)."""
+    hooks = Hooks()
     rng = np.random.default_rng(M + 3 * N + K + epi)
     A, W, bias = f16(rng, (M, K)), f16(rng, (N, K), 0.05), f16(rng, N, 0.5)
     res = rng.standard_normal((M, N)).astype(np.float32)
@@ -270,15 +287,15 @@ def test_gemm_tail_columns_in_k_slices(stream, M, N, K, epi):
     outs = []
     try:
         for hook in (109, 109, 108):
-            B.debug_gemm_tile(hook)
+            hooks.set(hook)
             out = dev(res) if epi in (P.EPI_BIAS_RESID_F32, P.EPI_F32) else torch.empty(M, N, dtype=torch.float16, device="cuda")
             guard = torch.full((4096,), 7.0, dtype=torch.float32, device="cuda")
-            B.op_gemm_ws(dA, dW, db, out, M, N, K, epi, ws, stream)
+            hooks.gemm(dA, dW, db, out, M, N, K, epi, stream, ws)
             stream.synchronize()
             assert (guard == 7.0).all()
             outs.append(out.cpu().numpy())
     finally:
-        B.debug_gemm_tile(109)
+        hooks.set(109)
     assert np.array_equal(outs[0], outs[1])
     acc = A.astype(np.float64) @ W.astype(np.float64).T
     want = {P.EPI_BIAS_F16: acc + bias.astype(np.float64), P.EPI_BIAS_RELU_F16: np.maximum(acc + bias.astype(np.float64), 0),
@@ -299,6 +316,7 @@ def test_gemm_tail_columns_in_k_slices(stream, M, N, K, epi):
 def test_gemm_split_k_with_workspace(stream, M, N, K, epi, force):
     """Small-M products with a scratch buffer: K split across workgroups, partials added in order;
     same bar as the one-pass product, and bit-identical when repeated."""
+    hooks = Hooks()
     rng = np.random.default_rng(M + N + K + epi)
     A, W, bias = f16(rng, (M, K)), f16(rng, (N, K), 0.05), f16(rng, N, 0.5)
     res = rng.standard_normal((M, N)).astype(np.float32)
@@ -313,17 +331,17 @@ def test_gemm_split_k_with_workspace(stream, M, N, K, epi, force):
         want, mk = acc, lambda: torch.empty(M, N, dtype=torch.float32, device="cuda")
     ws = torch.full((16 * M * N + 64,), float("nan"), dtype=torch.float32, device="cuda")
     outs = []
-    B.debug_gemm_tile(force)
+    hooks.set(force)
     try:
         for hook in (107, 107, 106):       # the reduction four columns at a time, again, then one column at a time
-            B.debug_gemm_tile(hook)
+            hooks.set(hook)
             out = mk()
-            B.op_gemm_ws(dev(A), dev(W), dev(bias), out, M, N, K, epi, ws, stream)
+            hooks.gemm(dev(A), dev(W), dev(bias), out, M, N, K, epi, stream, ws)
             stream.synchronize()
             outs.append(out.cpu().numpy())
     finally:
-        B.debug_gemm_tile(107)
-        B.debug_gemm_tile(-1)
+        hooks.set(107)
+        hooks.set(-1)
     assert np.array_equal(outs[0], outs[1])
     assert np.array_equal(outs[0], outs[2])       # both reductions add the slices in the same order
     got = outs[0].astype(np.float64)
