@@ -312,8 +312,9 @@ def run_swap(args):
         in_ms.append(i_ms)
         out_ms.append(o_ms)
         timed_blocks.append(list(blocks))
-    # AUTO on a host list in separate pieces: a miss that evicts loads through the DMA engines (one copy per run)
-    # while its victim's offload goes through the copy kernel; a packed list takes DMA copies both ways
+    # AUTO on a host list in separate pieces: a miss that evicts loads its matrices through the DMA engines (one
+    # copy each) and gathers the small tensors of a block with one narrow copy-kernel launch, while its victim's
+    # offload goes through the copy kernel; a packed list takes DMA copies both ways
     loads_by_kernel = args.transfer in ("kernel", "kernel_in_dma_out")
     offloads_by_kernel = args.transfer in ("kernel", "dma_in_kernel_out") or \
         (args.transfer == "auto" and args.host_layout == "separate")
@@ -393,7 +394,10 @@ def run_swap(args):
         }
     else:
         roofline = {
-            "kernel": "hipMemcpyAsync host -> HBM (DMA engines / the runtime's copy shader), not a kernel of this library",
+            "kernel": ("hipMemcpyAsync host -> HBM for the matrices (DMA engines, not a kernel of this library) + one "
+                       "copy_table_kernel<0, 256> launch per transfer block that gathers its small tensors"
+                       if args.transfer == "auto" and args.host_layout == "separate" else
+                       "hipMemcpyAsync host -> HBM (DMA engines / the runtime's copy shader), not a kernel of this library"),
             "bound": "host_link", "achieved": round(achieved, 3), "peak": round(link["h2d"], 3), "unit": "GB/s",
             "frac": round(achieved / link["h2d"], 4), "traffic": None, "peak_source": link_note,
             "bytes_per_launch": avg_launch_bytes, "avg_launch_ms": round(avg_launch_ms, 4),

@@ -283,7 +283,11 @@ uint64_t block_footprint(const ctn_ctx* c, const ShardLayout& L, int b) {
 // or will sit, in the arena) on stream s.  how: 0 = one hipMemcpyAsync per tensor (the paper's
 // per-tensor messages, Section 5.1), 1 = one copy-kernel launch over the block's runs, 2 = one
 // hipMemcpyAsync per run of adjacent tensors.
-enum { kPerTensorDma = 0, kCopyKernel = 1, kPerRunDma = 2 };
+enum { kPerTensorDma = 0, kCopyKernel = 1, kPerRunDma = 2, kGatherSmallDmaLarge = 3 };
+// kGatherSmallDmaLarge: runs of up to kSmallRunBytes travel together in one narrow copy-kernel launch per block
+// (the per-message cost of Section 5.1 is paid once for all of them), the larger runs by one DMA copy each.
+constexpr uint64_t kSmallRunBytes = 256 << 10;
+constexpr int kSmallRunWaves = 8;
 // Offloads by the copy kernel beside loads by the DMA engines (CTN_XFER_DMA_IN_KERNEL_OUT, and CTN_XFER_AUTO
 // in a run of back-to-back swaps): writes to the host that a kernel issues take link capacity from the loads
 // running beside them, the more the wider the kernel is.  Measured on the alternating two-model workload
@@ -307,10 +311,13 @@ int offload_path(const ctn_ctx* c, const Model* m) {
 int copy_block(ctn_ctx* c, Model* m, int b, char* base, bool to_device, int how, hipStream_t s, int waves) {
   const ShardLayout& L = m->lay;
   if (m->runs[b].empty()) return CTN_OK;        // a stage without tensors outside its layers
-  if (how == kCopyKernel) {
+  if (how == kCopyKernel || how == kGatherSmallDmaLarge) {
+    const bool only_small = how == kGatherSmallDmaLarge;
+    if (only_small) waves = kSmallRunWaves;
     CopyTable t{};
     static_assert(kLayerTensors <= kCopyMaxSegs, "a layer block's tensors must fit one copy table");
     for (const Model::Run& r : m->runs[b]) {
+      if (only_small && r.bytes > kSmallRunBytes) continue;
       if (t.n >= kCopyMaxSegs) {                 // a block 0 with more runs than one table holds: flush and go on
         if (!copy_table_finish(t, copy_workgroup_threads(waves))) return CTN_E_INVAL;
         CTN_HIP(c, launch_copy_table(t, waves, s, to_device ? kCopyH2D : kCopyD2H));
@@ -324,7 +331,7 @@ int copy_block(ctn_ctx* c, Model* m, int b, char* base, bool to_device, int how,
     }
     if (!copy_table_finish(t, copy_workgroup_threads(waves))) return CTN_E_INVAL;
     CTN_HIP(c, launch_copy_table(t, waves, s, to_device ? kCopyH2D : kCopyD2H));
-    return CTN_OK;
+    if (!only_small) return CTN_OK;
   }
   auto one = [&](int ti, uint64_t bytes) {
     char* dev = base + L.offset_in_block(ti);
@@ -334,7 +341,10 @@ int copy_block(ctn_ctx* c, Model* m, int b, char* base, bool to_device, int how,
   if (how == kPerTensorDma) {
     for (int ti : L.block_tensors[b]) CTN_HIP(c, one(ti, L.nbytes[ti]));
   } else {
-    for (const Model::Run& r : m->runs[b]) CTN_HIP(c, one(r.first, r.bytes));
+    for (const Model::Run& r : m->runs[b]) {
+      if (how == kGatherSmallDmaLarge && r.bytes <= kSmallRunBytes) continue;   // went with the gather launch
+      CTN_HIP(c, one(r.first, r.bytes));
+    }
   }
   return CTN_OK;
 }
@@ -549,7 +559,7 @@ int ensure_resident(ctn_ctx* c, int mi) {
     case CTN_XFER_KERNEL: case CTN_XFER_KERNEL_IN_DMA_OUT: how = kCopyKernel; break;
     case CTN_XFER_DMA_IN_KERNEL_OUT: case CTN_XFER_DMA_RUNS: how = kPerRunDma; break;
     default:   // CTN_XFER_AUTO
-      how = (m->fragmented && !two_way) ? kCopyKernel : kPerRunDma;
+      how = !m->fragmented ? kPerRunDma : (two_way ? kGatherSmallDmaLarge : kCopyKernel);
       break;
   }
   CTN_HIP(c, hipEventRecord(m->ev_in_start, c->s_h2d));
