@@ -663,8 +663,14 @@ constexpr int RS_WIN = 512, RS_ROW = RS_WIN + 8, RS_AHEAD = 2;
 static_assert(RS_AHEAD % 2 == 0, "the LDS stage alternates with the position inside a trip");
 template <int EPI>
 __global__ __launch_bounds__(SK_WAVES * 64) void gemm_rowstream_kernel(const GemmArgs g) {
-  __shared__ __attribute__((aligned(16))) _Float16 wt[2][16][RS_ROW];
-  __shared__ float part[SK_WAVES][16][17];
+  // Two stages each of the weight window and of the activation window, [16 rows][RS_ROW]; the 16 partial tiles
+  // of the end reuse the weight stages (two workgroups of 66.6 KB fit a CU's LDS, three arrays side by side would not).
+  constexpr int kStage = 16 * RS_ROW;                  // halves per stage
+  __shared__ __attribute__((aligned(16))) _Float16 smem[4 * kStage];
+  _Float16 (*wt)[16][RS_ROW] = reinterpret_cast<_Float16 (*)[16][RS_ROW]>(smem);
+  _Float16 (*at)[16][RS_ROW] = reinterpret_cast<_Float16 (*)[16][RS_ROW]>(smem + 2 * kStage);
+  float (*part)[16][17] = reinterpret_cast<float (*)[16][17]>(smem);
+  static_assert(sizeof(float) * SK_WAVES * 16 * 17 <= sizeof(_Float16) * 2 * kStage, "partial tiles fit the weight stages");
   const int M = g.M, N = g.N, K = g.K;
   const int tiles_n = (N + 15) / 16;
   const int part_id = blockIdx.x / tiles_n;
@@ -675,8 +681,9 @@ __global__ __launch_bounds__(SK_WAVES * 64) void gemm_rowstream_kernel(const Gem
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
   const bool row_ok = n0 + wave < N;
+  const bool tok_ok = wave < M;                        // wavefront w also fetches token w's activations
   const _Float16* wrow = W + static_cast<int64_t>(row_ok ? n0 + wave : 0) * K;
-  const _Float16* arow = A + static_cast<int64_t>(r16 < M ? r16 : 0) * K;
+  const _Float16* arow = A + static_cast<int64_t>(tok_ok ? wave : 0) * K;
   const int steps = (K + RS_WIN - 1) / RS_WIN;
   // Loads are branch free (an address that is always valid, zeros selected afterwards where the window or the
   // row does not exist) and the barrier is a raw one: a fenced barrier, or a branch around a load, makes the
@@ -684,46 +691,48 @@ __global__ __launch_bounds__(SK_WAVES * 64) void gemm_rowstream_kernel(const Gem
   // (the zeros are selected where a value is consumed, not where it is loaded: a select right behind the load
   // would wait for it)
   const half8 zero8 = half8{0, 0, 0, 0, 0, 0, 0, 0};
-  auto w_ok = [&](int p) { return row_ok && p * RS_WIN + lane * 8 < K; };   // (p >= steps implies false)
-  auto load_w = [&](int p) {                            // this lane's 16 bytes of window p of its wave's row
-    return *reinterpret_cast<const half8*>(wrow + (w_ok(p) ? p * RS_WIN + lane * 8 : 0));
+  auto in_k = [&](int p) { return p * RS_WIN + lane * 8 < K; };             // (p >= steps implies false)
+  auto load_w = [&](int p) {                            // this lane's 16 bytes of window p of its wave's weight row
+    return *reinterpret_cast<const half8*>(wrow + (row_ok && in_k(p) ? p * RS_WIN + lane * 8 : 0));
   };
-  auto a_ok = [&](int p) { return r16 < M && p * RS_WIN + wave * 32 + kg * 8 < K; };
-  auto load_a = [&](int p) {                            // this lane's 8 activations of chunk `wave` of window p
-    return *reinterpret_cast<const half8*>(arow + (a_ok(p) ? p * RS_WIN + wave * 32 + kg * 8 : 0));
+  // The activations take the same road as the weights: wavefront w reads 1 KiB of token w's row per window
+  // (M of the 16 wavefronts; the others store zeros) and the 16 x 512 window is transposed through LDS.  Loading
+  // the operand fragments straight from global memory instead (16 rows x 64 bytes per wave instruction, by all
+  // 16 wavefronts, half of each cache line unused) cost the load path of a CU twice what the weights cost it.
+  auto load_a = [&](int p) {
+    return *reinterpret_cast<const half8*>(arow + (tok_ok && in_k(p) ? p * RS_WIN + lane * 8 : 0));
   };
   // Issue order matters: vector memory returns in order, so a load waited for takes everything older with it.
-  // Per window p the order is  A(p + 1), W(p + RS_AHEAD):  waiting for W(p) and then A(p) leaves the newer
-  // windows in flight.
-  // (the prologue issues in the order the loop leaves behind, W(0) .. W(RS_AHEAD - 2), A(0), W(RS_AHEAD - 1), so
-  // that the wait counts the compiler derives for the loop's entry and for its back edge agree)
-  half8 wr[RS_AHEAD];
+  // Window p + RS_AHEAD of both operands is asked for while window p is being stored and multiplied.
+  half8 wr[RS_AHEAD], ar[RS_AHEAD];
 #pragma unroll
-  for (int u = 0; u + 1 < RS_AHEAD; ++u) wr[u] = load_w(u);
-  __builtin_amdgcn_sched_barrier(0);
-  half8 a_cur = load_a(0);
-  __builtin_amdgcn_sched_barrier(0);
-  wr[RS_AHEAD - 1] = load_w(RS_AHEAD - 1);
-  __builtin_amdgcn_sched_barrier(0);
+  for (int u = 0; u < RS_AHEAD; ++u) {
+    ar[u] = load_a(u);
+    __builtin_amdgcn_sched_barrier(0);
+    wr[u] = load_w(u);
+    __builtin_amdgcn_sched_barrier(0);
+  }
   float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
   for (int p0 = 0; p0 < steps; p0 += RS_AHEAD) {
 #pragma unroll
     for (int u = 0; u < RS_AHEAD; ++u) {
       const int p = p0 + u, buf = u & 1;               // (RS_AHEAD is even: the stage alternates with u)
       // past the last window the same code runs on zeros: no branch, and zeros add nothing
-      *reinterpret_cast<half8*>(&wt[buf][wave][lane * 8]) = w_ok(p) ? wr[u] : zero8;
+      *reinterpret_cast<half8*>(&at[buf][wave][lane * 8]) = (tok_ok && in_k(p)) ? ar[u] : zero8;
+      *reinterpret_cast<half8*>(&wt[buf][wave][lane * 8]) = (row_ok && in_k(p)) ? wr[u] : zero8;
       __builtin_amdgcn_sched_barrier(0);
-      const half8 a_next = load_a(p + 1);
+      ar[u] = load_a(p + RS_AHEAD);
       __builtin_amdgcn_sched_barrier(0);
       wr[u] = load_w(p + RS_AHEAD);
       __builtin_amdgcn_sched_barrier(0);
       stage_stores_done_barrier();                      // one per window: the other stage was last read before the previous one
       const half8 bf = *reinterpret_cast<const half8*>(&wt[buf][r16][wave * 32 + kg * 8]);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_ok(p) ? a_cur : zero8, bf, acc, 0, 0, 0);
+      const half8 af = *reinterpret_cast<const half8*>(&at[buf][r16][wave * 32 + kg * 8]);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, bf, acc, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      a_cur = a_next;
     }
   }
+  __syncthreads();                                      // the stages have been read for the last time: they become `part`
   // accumulator layout of a 16x16 tile: lane holds column (lane % 16), rows 4*(lane/16) + e
 #pragma unroll
   for (int e = 0; e < 4; ++e) part[wave][4 * kg + e][r16] = acc[e];
