@@ -965,10 +965,19 @@ uint64_t ctn_slot_bytes(const ctn_model_desc* desc) {
 }
 
 // Copies n token ids into the next staging slot (waiting, on the host, for the slot's previous reader
-// if that is still running, which takes kIdSlots inferences in flight).
+// only when every slot's reader is still running, i.e. with kIdSlots inferences in flight).
 static int stage_ids(ctn_ctx* c, const int32_t* ids_host, size_t n, IdSlot** out) {
-  IdSlot& sl = c->id_slots[c->next_id_slot];
-  c->next_id_slot = (c->next_id_slot + 1) % kIdSlots;
+  // the first slot, from the one after the last used, whose reader has finished: a batch that waits for its
+  // model's load keeps its slot for a long time while batches of loaded models come and go
+  int pick = -1;
+  for (int i = 0; i < kIdSlots && pick < 0; ++i) {
+    const int k = (c->next_id_slot + i) % kIdSlots;
+    if (!c->id_slots[k].used || hipEventQuery(c->id_slots[k].done) == hipSuccess) pick = k;
+  }
+  (void)hipGetLastError();                  // "not ready" is an answer
+  if (pick < 0) pick = c->next_id_slot;     // every slot busy: wait for this one
+  IdSlot& sl = c->id_slots[pick];
+  c->next_id_slot = (pick + 1) % kIdSlots;
   if (sl.used) CTN_HIP(c, hipEventSynchronize(sl.done));
   if (sl.cap < n) {
     if (sl.host) CTN_HIP(c, hipHostFree(sl.host));

@@ -192,3 +192,45 @@ def test_model_that_is_loading_ahead_takes_the_load_lane():
     finally:
         eng.close()
         rig.close()
+
+
+def test_many_hits_complete_while_one_miss_is_loading():
+    """A batch that waits for its model's load keeps everything it was given (its token ids among them) for the
+    whole load; the batches of loaded models that are dispatched meanwhile must not wait for it.  One large model
+    (2.6 GB: tens of milliseconds of load) misses on the load lane; twenty hits on a small resident model are then
+    dispatched one after the other, each awaited, and all of them must be done while the load lane is still busy."""
+    from synth import CONFIGS
+    big = CONFIGS["opt1.3b_tp1"]["desc"]
+    small = DESC
+    rig = Rig([small, big], max_tokens=MAXB * SEQ, mode=P.XFER_KERNEL, two_lanes=True, gap=4096)
+    eng = None
+    try:
+        eng = P.Engine(rig.ctx, MAXB, SEQ, two_lanes=True)
+        m_small = rig.add(small, seed=300)
+        m_big = rig.add(big, seed=301)
+        bufs = [torch.empty(MAXB, SEQ, max(small.vocab, big.vocab), dtype=torch.float32, device="cuda") for _ in range(2)]
+        ids = token_ids(700, 1, SEQ, small.vocab)
+        eng.submit(m_small, ids, 0.0)
+        assert eng.dispatch(*bufs)[1:] == (m_small, True, 1)
+        rig.ctx.sync()
+        eng.submit(m_big, ids, 1.0)
+        t0 = time.perf_counter()
+        assert eng.dispatch(*bufs)[1:] == (m_big, True, 1)     # the load lane is busy from here on
+        done = 0
+        for i in range(20):
+            eng.submit(m_small, ids, 2.0 + i)
+            r = eng.dispatch(*bufs)
+            assert r is not None and r[1:] == (m_small, False, 0), (i, r)
+            while eng.lanes_busy()[0]:
+                pass
+            done += 1
+        t_hits = time.perf_counter() - t0
+        still_loading = eng.lanes_busy()[1]
+        rig.ctx.sync()
+        t_all = time.perf_counter() - t0
+        print(f"20 hits in {t_hits * 1e3:.1f} ms, the miss took {t_all * 1e3:.1f} ms", flush=True)
+        assert done == 20 and still_loading, (t_hits, t_all)
+    finally:
+        if eng is not None:
+            eng.close()
+        rig.close()
