@@ -507,32 +507,58 @@ __global__ __launch_bounds__(256, 2) void gemm_dma_kernel(const GemmArgs g) {
   const int kt_end = static_cast<int>(static_cast<int64_t>(ksteps_all) * (split + 1) / g.splits);
   const int ksteps = kt_end - kt_begin;
   const int kbase = kt_begin * BK;
-  if (ksteps > 0) fill_stage(0, kbase);
-  fills_landed_barrier();
-  for (int kt = 0; kt < ksteps; ++kt) {
-    const int buf = kt & 1;
-    // the other stage was last read before the barrier that ended the previous step
-    if (kt + 1 < ksteps) fill_stage(buf ^ 1, kbase + (kt + 1) * BK);
+  // Two register sets for the fragments: the reads of sub-step ks + 1 are in flight while the products of
+  // sub-step ks run, and the barrier that ends a stage sits in front of the last sub-step's products, with the
+  // first fragment reads of the next stage issued right behind it, so that no product waits for an LDS read
+  // that has not had a block of products to arrive in (4 x 256 forward of the 6.7B/TP2 shard 10.35 -> 10.18 ms).
+  half8 af0[TM], bf0[TN], af1[TM], bf1[TN];
+  auto read_frags = [&](half8 (&af)[TM], half8 (&bf)[TN], int buf, int ks) {
     const unsigned a0 = as_base + buf * STAGE, b0 = bs_base + buf * STAGE;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      half8 af[TM], bf[TN];
+    for (int i = 0; i < TM; ++i) af[i] = frag16(a0 + fa[i][ks]);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = frag16(a0 + fa[i][ks]);
+    for (int j = 0; j < TN; ++j) bf[j] = frag16(b0 + fb[j][ks]);
+  };
+  auto products = [&](const half8 (&af)[TM], const half8 (&bf)[TN]) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bf[j] = frag16(b0 + fb[j][ks]);
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
+  };
 #if defined(__HIP_DEVICE_COMPILE__)
-      // the products below depend on this statement's outputs, so they cannot be scheduled above the wait
-      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[0]), "+v"(af[1]), "+v"(bf[0]), "+v"(bf[1]));
+#define CTN_FRAGS_READY(AF, BF) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(AF[0]), "+v"(AF[1]), "+v"(BF[0]), "+v"(BF[1]))
+#else
+#define CTN_FRAGS_READY(AF, BF)
 #endif
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
+
+  if (ksteps > 0) {
+    fill_stage(0, kbase);
+    fills_landed_barrier();
+    if (ksteps > 1) fill_stage(1, kbase + BK);
+    read_frags(af0, bf0, 0, 0);
+    for (int kt = 0; kt < ksteps; ++kt) {
+      const int buf = kt & 1;
+      CTN_FRAGS_READY(af0, bf0);
+      read_frags(af1, bf1, buf, 1);
+      products(af0, bf0);
+      CTN_FRAGS_READY(af1, bf1);
+      read_frags(af0, bf0, buf, 2);
+      products(af1, bf1);
+      CTN_FRAGS_READY(af0, bf0);
+      read_frags(af1, bf1, buf, 3);
+      products(af0, bf0);
+      CTN_FRAGS_READY(af1, bf1);
+      // this wavefront has read stage kt for the last time; the fill of stage kt + 1 was issued a step ago
+      if (kt + 1 < ksteps) {
+        fills_landed_barrier();                        // stage kt + 1 complete everywhere, stage kt free everywhere
+        if (kt + 2 < ksteps) fill_stage(buf, kbase + (kt + 2) * BK);
+        read_frags(af0, bf0, buf ^ 1, 0);
+      }
+      products(af1, bf1);
     }
-    fills_landed_barrier();      // next stage complete for everybody, this stage free to be overwritten
   }
+#undef CTN_FRAGS_READY
   store_tile<TM, TN, EPI>(g, acc, bias, g.out, m0 + wm0, n0 + wn0, col0, ldc, split, lane);
 }
 
