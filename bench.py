@@ -270,7 +270,7 @@ def run_swap(args):
 
         # the same alternation on the other transfer paths, for the comparison of the copy kernel with the DMA engines:
         # one hipMemcpyAsync per run of adjacent tensors, one per tensor (the paper's per-tensor messages), and the
-        # copy kernel at full width in both directions (AUTO narrows the offload's kernel)
+        # copy kernel at full width in both directions (AUTO narrows the kernel of an offload that runs beside a load: a wide one takes the link from the load)
         side["paths"] = {}
         for alt, mode, waves_out in (("dma_runs", "dma_runs", 0), ("dma_per_tensor", "dma", 0),
                                      ("kernel_both_ways_full_width", "kernel", 0), ("kernel_both_ways_offload_8_waves", "kernel", 8)):
