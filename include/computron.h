@@ -100,7 +100,9 @@ typedef struct {
                                 block, both directions; CTN_XFER_DMA_RUNS: one hipMemcpyAsync per run of
                                 tensors that lie back to back on the host, both directions;
                                 CTN_XFER_DMA_IN_KERNEL_OUT / CTN_XFER_KERNEL_IN_DMA_OUT: the copy kernel
-                                in one direction, one DMA copy per run in the other.
+                                in one direction, one DMA copy per run in the other (with
+                                copy_waves_out == 0 the offloads that a miss causes take the width that
+                                keeps pace with the load beside them, as under CTN_XFER_AUTO).
                                 CTN_XFER_AUTO, decided per miss from the context's own record and its
                                 events (never the clock): a host list in many separate pieces is loaded
                                 by the copy kernel when the link's other direction is idle (the miss

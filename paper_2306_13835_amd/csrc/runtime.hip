@@ -398,9 +398,9 @@ int enqueue_offload(ctn_ctx* c, const Eviction& ev) {
   const ShardLayout& L = m->lay;
   const int how = offload_path(c, m);
   int waves = c->cfg.copy_waves_out ? c->cfg.copy_waves_out : 4 * c->cfg.copy_blocks;
-  const bool balanced = !c->cfg.copy_waves_out && how == kCopyKernel &&
-                        (c->cfg.transfer_mode == CTN_XFER_DMA_IN_KERNEL_OUT ||
-                         (c->cfg.transfer_mode == CTN_XFER_AUTO && ev.waves == kBalancedOffload));
+  // (an eviction that a miss decided runs beside that miss's load; an explicit swap-out has the link to itself)
+  const bool balanced = !c->cfg.copy_waves_out && how == kCopyKernel && ev.waves == kBalancedOffload &&
+                        (c->cfg.transfer_mode == CTN_XFER_DMA_IN_KERNEL_OUT || c->cfg.transfer_mode == CTN_XFER_AUTO);
   if (c->cfg.transfer_mode == CTN_XFER_AUTO && !c->cfg.copy_waves_out && ev.waves > 0) waves = ev.waves;
   uint64_t bytes = 0;
   // (a discarded device copy moves nothing; the stream waits above and the event below still
