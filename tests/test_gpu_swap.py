@@ -153,7 +153,7 @@ def test_many_cycles_any_order_keeps_host_bits(gap):
             if rng.random() < 0.3:
                 rig.ctx.swap_out(m)
             else:
-                rig.ctx.set_mode(int(rng.integers(0, 3)), True)
+                rig.ctx.set_mode(int(rng.integers(0, 6)), True)          # any of the six transfer modes
                 rig.ctx.swap_in(m)
                 if rng.random() < 0.5:
                     rig.ctx.wait(m)
