@@ -109,7 +109,8 @@ typedef struct {
                                 evicts nothing and no earlier offload is still running), else by one DMA
                                 copy per large run plus one narrow copy-kernel launch per block that
                                 gathers its small tensors, with the victims' offloads going through the copy
-                                kernel at a width that keeps the two directions at the same pace; an explicit
+                                kernel at a width that keeps the two directions at the same pace (library-
+                                owned streams; on the caller's streams those offloads are DMA copies); an explicit
                                 ctn_swap_out uses the copy kernel at full width; a list whose tensors
                                 lie back to back on the host takes one DMA copy per run both ways */
   int32_t pipeline;          /* 0: inference waits for the whole shard (the paper's rule, Section 3.2);

@@ -396,7 +396,12 @@ int enqueue_offload(ctn_ctx* c, const Eviction& ev) {
     if (m->used[lane]) CTN_HIP(c, hipStreamWaitEvent(c->s_d2h, m->ev_last_use[lane], 0));
   CTN_HIP(c, hipEventRecord(m->ev_out_start, c->s_d2h));
   const ShardLayout& L = m->lay;
-  const int how = offload_path(c, m);
+  int how = offload_path(c, m);
+  // The widths that balance an offload kernel against the load beside it were measured with the kernel confined
+  // to the offload stream's own compute units; on a caller's streams, where it shares the chip with the forward
+  // pass, it falls behind (160 against 142 ms per alternating step), so there AUTO offloads by DMA copies.
+  if (c->cfg.transfer_mode == CTN_XFER_AUTO && how == kCopyKernel && ev.waves == kBalancedOffload && !c->own_streams)
+    how = kPerRunDma;
   int waves = c->cfg.copy_waves_out ? c->cfg.copy_waves_out : 4 * c->cfg.copy_blocks;
   // (an eviction that a miss decided runs beside that miss's load; an explicit swap-out has the link to itself)
   const bool balanced = !c->cfg.copy_waves_out && how == kCopyKernel && ev.waves == kBalancedOffload &&
