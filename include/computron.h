@@ -61,7 +61,7 @@ enum { CTN_XFER_DMA = 0, CTN_XFER_KERNEL = 1, CTN_XFER_AUTO = 2,
  * the layers [stage*layers/pp, (stage+1)*layers/pp); stage 0 also holds the
  * embeddings, the last stage the final LayerNorm and its own copy of the tied
  * head matrix.  pp of 0 or 1: all layers.  Requirements: hidden % heads == 0,
- * hidden <= 8192, head size 64 or 128, heads % tp == 0, ffn % tp == 0, vocab % tp == 0,
+ * hidden <= 16384, head size 64 or 128, heads % tp == 0, ffn % tp == 0, vocab % tp == 0,
  * (hidden/tp) % 8 == 0, (ffn/tp) % 8 == 0, 0 <= rank < tp, max_pos >= 1,
  * layers % pp == 0, 0 <= stage < pp. */
 typedef struct {

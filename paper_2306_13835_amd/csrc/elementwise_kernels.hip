@@ -237,7 +237,7 @@ hipError_t launch_embed(const int32_t* ids, const _Float16* tok, const _Float16*
 hipError_t launch_layernorm(float* x, const _Float16* g, const _Float16* b, _Float16* out, int rows, int hidden,
                             hipStream_t s, const PendingSum* pending) {
   if (rows <= 0) return hipSuccess;
-  static_assert(kMaxHidden == 256 * 4 * 8, "registration admits exactly the widths these kernels cover");
+  static_assert(kMaxHidden == 256 * 4 * 16, "registration admits exactly the widths these kernels cover");
   if (hidden % 4 || hidden <= 0 || hidden > kMaxHidden) return hipErrorInvalidValue;
   const bool fuse = pending && pending->splits > 0;
   const PendingSum pend = fuse ? *pending : PendingSum{};
@@ -249,7 +249,9 @@ hipError_t launch_layernorm(float* x, const _Float16* g, const _Float16* b, _Flo
     else if (nvec <= 512) launch_fewrows<1, 8>(x, g, b, out, rows, hidden, s, pend);     // 2048
     else if (nvec <= 1024) launch_fewrows<1, 16>(x, g, b, out, rows, hidden, s, pend);   // 4096
     else if (nvec <= 1280) launch_fewrows<2, 10>(x, g, b, out, rows, hidden, s, pend);   // 5120
-    else launch_fewrows<2, 16>(x, g, b, out, rows, hidden, s, pend);                     // up to 8192
+    else if (nvec <= 2048) launch_fewrows<2, 16>(x, g, b, out, rows, hidden, s, pend);   // up to 8192
+    else if (nvec <= 3072) launch_fewrows<3, 16>(x, g, b, out, rows, hidden, s, pend);   // 9216, 12288
+    else launch_fewrows<4, 16>(x, g, b, out, rows, hidden, s, pend);                     // up to 16384
     return hipGetLastError();
   }
 #define CTN_LN(NV, WAVES)                                                                                     \
@@ -262,7 +264,9 @@ hipError_t launch_layernorm(float* x, const _Float16* g, const _Float16* b, _Flo
   else if (nvec <= 512) CTN_LN(2, 4);      // 2048
   else if (nvec <= 1024) CTN_LN(4, 4);     // 4096
   else if (nvec <= 1536) CTN_LN(6, 4);     // 5120, 6144
-  else CTN_LN(8, 4);                       // up to 8192
+  else if (nvec <= 2048) CTN_LN(8, 4);     // up to 8192
+  else if (nvec <= 3072) CTN_LN(12, 4);    // 9216, 12288
+  else CTN_LN(16, 4);                      // up to 16384
 #undef CTN_LN
   return hipGetLastError();
 }

@@ -27,7 +27,7 @@ namespace ctn {
 constexpr uint64_t kAlign = 256;
 constexpr int kLayerTensors = 16;
 constexpr int kPosOffset = 2;  // OPT keeps position rows shifted by two
-constexpr int kMaxHidden = 8192;
+constexpr int kMaxHidden = 16384;
 
 inline uint64_t align_up(uint64_t x, uint64_t a = kAlign) { return (x + a - 1) / a * a; }
 

@@ -178,12 +178,14 @@ int main() {
   std::puts("host logic ok");
   {   // shard descriptions: what the kernels cannot run is refused at registration, not at the first inference
     ctn_model_desc d{};
-    d.layers = 2; d.hidden = 8192; d.ffn = 32768; d.heads = 64; d.vocab = 1024; d.max_pos = 64; d.tp = 2; d.rank = 1;
+    d.layers = 2; d.hidden = 16384; d.ffn = 65536; d.heads = 128; d.vocab = 1024; d.max_pos = 64; d.tp = 2; d.rank = 1;
     assert(ctn::desc_valid(d));                       // the widest row the LayerNorm kernels hold
     ctn_model_desc wide = d;
-    wide.hidden = 9216; wide.heads = 72;              // head size 128, divisible by everything, but too wide
-    assert(!ctn::desc_valid(wide));
-    wide.hidden = 12288; wide.heads = 96;
+    wide.hidden = 9216; wide.heads = 72; wide.ffn = 36864;    // the 66B and 175B members of the OPT family fit
+    assert(ctn::desc_valid(wide));
+    wide.hidden = 12288; wide.heads = 96; wide.ffn = 49152;
+    assert(ctn::desc_valid(wide));
+    wide.hidden = 16384 + 128; wide.heads = 129;      // head size 128, divisible by everything, but too wide
     assert(!ctn::desc_valid(wide));
     ctn_model_desc odd = d;
     odd.hidden = 96 * 64; odd.heads = 64;             // head size 96

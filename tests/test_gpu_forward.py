@@ -365,7 +365,8 @@ def test_batches_of_short_requests_in_a_workspace_sized_for_the_largest(tokens):
         rig.close()
 
 
-@pytest.mark.parametrize("hidden,heads", [(512, 4), (2048, 16), (4096, 32), (5120, 40), (8192, 64)])
+@pytest.mark.parametrize("hidden,heads", [(512, 4), (2048, 16), (4096, 32), (5120, 40), (8192, 64), (9216, 72), (12288, 96),
+                                          (16384, 128)])
 def test_layernorm_finishing_split_products_changes_no_bit(hidden, heads):
     """Between 17 and 256 tokens the row-parallel products are cut along K and leave the sum of their slices to
     the LayerNorm that follows (one workgroup per row, every slice's load in flight at once).  That kernel adds in
@@ -385,6 +386,23 @@ def test_layernorm_finishing_split_products_changes_no_bit(hidden, heads):
             assert np.array_equal(fused, apart), (hidden, b, s_)
             if (b, s_) == (1, 64) and hidden <= 5120:      # (the bar is stated for the configs' widths, up to 5120)
                 assert_close(fused, oracle_logits(rig, m, desc, ids), f"hidden {hidden}, {b} x {s_}")
+    finally:
+        rig.close()
+
+
+@pytest.mark.parametrize("hidden,heads,tp,tokens", [(9216, 72, 8, (1, 8)), (12288, 96, 8, (2, 32)), (12288, 96, 8, (3, 100))])
+def test_rows_wider_than_8192(hidden, heads, tp, tokens):
+    """One layer of the widest members of the model family (hidden 9216 and 12288, one rank of eight): rows of
+    three vectors per thread in both LayerNorm kernels, every product shape of such a shard, within the bar."""
+    desc = ShardDesc(1, hidden, 4 * hidden, heads, vocab=1024, max_pos=128, tp=tp, rank=5)
+    b, s_ = tokens
+    rig = Rig([desc], max_tokens=b * s_)
+    try:
+        m = rig.add(desc, seed=260)
+        ids = token_ids(261 + b * s_, b, s_, desc.vocab)
+        got = rig.ctx.infer(m, ids)
+        assert_close(got, oracle_logits(rig, m, desc, ids), f"hidden {hidden}, {b} x {s_}")
+        assert np.array_equal(got, rig.ctx.infer(m, ids))
     finally:
         rig.close()
 

@@ -82,7 +82,9 @@ def test_embed(stream, hidden, rank, tp):
 
 
 @pytest.mark.parametrize("rows,hidden", [(1, 768), (8, 768), (5, 2048), (133, 4096), (64, 5120), (3, 128), (9, 8192),
-                                         (300, 4096), (257, 5120), (256, 2048), (700, 768)])   # (more than 256 rows: the four-wavefront kernel)
+                                         (300, 4096), (257, 5120), (256, 2048), (700, 768),    # (more than 256 rows: the four-wavefront kernel)
+                                         (7, 9216), (260, 9216), (64, 12288), (300, 12288), (5, 16384), (258, 16384),
+                                         (3, 10240), (270, 14336)])    # (rows wider than 8192: three or four vectors per thread)
 def test_layernorm(stream, rows, hidden):
     rng = np.random.default_rng(rows * hidden)
     x = (rng.standard_normal((rows, hidden)) * 3 + 0.5).astype(np.float32)
