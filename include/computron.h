@@ -226,8 +226,11 @@ int ctn_sync(ctn_ctx* ctx);
  * in every case, so the caller may reuse it at once.  logits_out is a device pointer when
  * out_is_device != 0 (the call returns with the work enqueued on the compute
  * stream), else pinned or ordinary host memory (the call returns after the
- * logits have arrived).  Errors: CTN_E_SHAPE when seq > max_pos or the
- * workspace cannot hold batch*seq tokens (see ctn_workspace_bytes). */
+ * logits have arrived).  Errors: CTN_E_SHAPE when batch or seq is not positive,
+ * seq > max_pos, batch > 65535, batch*seq > 2^24 or the workspace cannot hold
+ * batch*seq tokens (see ctn_workspace_bytes); CTN_E_INVAL for a token id outside
+ * [0, vocab).  Nothing is enqueued and no residency decision is taken when
+ * either is returned. */
 int ctn_infer(ctn_ctx* ctx, ctn_model m, const int32_t* token_ids_host, int32_t batch, int32_t seq,
               void* logits_out, int32_t out_is_device);
 /* The same for any pipeline stage.  Stage 0 starts from token_ids_host
@@ -353,7 +356,11 @@ int ctn_engine_set_prefetch(ctn_engine* eng, int32_t enable, int32_t min_count, 
  * that model's handle, -1 when nothing was done. */
 int ctn_engine_idle(ctn_engine* eng, ctn_model* loaded);
 /* ---- single operations (each enqueues on `stream`, a hipStream_t; all data
- *      pointers are device pointers unless stated) --------------------------- */
+ *      pointers are device pointers unless stated).  The kernels read and write
+ *      rows in 16-byte pieces: matrices and activations must start on a 16-byte
+ *      boundary (vectors of gains and biases on an 8-byte one, the bias of a
+ *      product on a 2-byte one, ids and fp32 outputs of a product on a 4-byte
+ *      one); CTN_E_INVAL otherwise, and for shapes a kernel does not cover. ---- */
 
 enum { CTN_EPI_BIAS_F16 = 0,       /* out fp16 [M,N]  = A W^T + bias            */
        CTN_EPI_BIAS_RELU_F16 = 1,  /* out fp16 [M,N]  = max(0, A W^T + bias)    */
@@ -367,10 +374,12 @@ int ctn_op_copy(void* dst, const void* src, uint64_t nbytes, int32_t blocks, voi
 /* hipMemcpyAsync of one range (the DMA engine path), for link-peak measurements. */
 int ctn_op_dma(void* dst, const void* src, uint64_t nbytes, void* stream);
 /* x fp32 [M,hidden] = token row (zero if id outside [rank*vocab_local,
- * (rank+1)*vocab_local)) + position row (m mod seq) + 2.  ids int32 [M]. */
+ * (rank+1)*vocab_local)) + position row (m mod seq) + 2.  ids int32 [M].
+ * hidden % 8 == 0. */
 int ctn_op_embed(const int32_t* ids, const void* tok_f16, const void* pos_f16, float* x, int32_t M,
                  int32_t seq, int32_t hidden, int32_t vocab_local, int32_t rank, void* stream);
-/* out fp16 [rows,hidden] = LayerNorm(x fp32; gain, bias fp16), biased variance, eps 1e-5. */
+/* out fp16 [rows,hidden] = LayerNorm(x fp32; gain, bias fp16), biased variance, eps 1e-5.
+ * hidden % 4 == 0, hidden <= 16384. */
 int ctn_op_layernorm(const float* x, const void* gain_f16, const void* bias_f16, void* out_f16,
                      int32_t rows, int32_t hidden, void* stream);
 /* C = A[M,K] (fp16) times W[N,K]^T (fp16), fp32 accumulation on the matrix
@@ -400,7 +409,7 @@ int ctn_op_gemm_static(const void* A_f16, const void* W_f16, const void* bias_f1
 uint64_t ctn_static_scratch_bytes(void);
 /* Causal self-attention of every (batch, head): qkv fp16 [batch*seq, 3*heads*d]
  * holds q | k | v side by side; out fp16 [batch*seq, heads*d]
- * = softmax_causal((q d^-1/2) k^T) v.  d is 64 or 128. */
+ * = softmax_causal((q d^-1/2) k^T) v.  d is 64 or 128; batch and heads at most 65535 each. */
 int ctn_op_attention(const void* qkv_f16, void* out_f16, int32_t batch, int32_t seq, int32_t heads,
                      int32_t head_dim, void* stream);
 

@@ -997,6 +997,10 @@ hipError_t dispatch(const GemmArgs& g, int epi, hipStream_t s, size_t partial_fl
   if (g.K <= 0 || g.K % 8 || g.parts < 1 || g.parts > 3) return hipErrorInvalidValue;
   for (int p = 0; p < g.parts; ++p)
     if (!g.W[p] || (epi != CTN_EPI_F32 && !g.bias[p])) return hipErrorInvalidValue;
+  // operands are read in 16-byte pieces (K is a multiple of 8, so every row then starts on such a boundary)
+  if (reinterpret_cast<uintptr_t>(g.A) % 16 || reinterpret_cast<uintptr_t>(g.out) % 4) return hipErrorInvalidValue;
+  for (int p = 0; p < g.parts; ++p)
+    if (reinterpret_cast<uintptr_t>(g.W[p]) % 16 || reinterpret_cast<uintptr_t>(g.bias[p]) % 2) return hipErrorInvalidValue;
   if (tuning().force_tile == 14 || tuning().force_tile == 15) {       // tuning hook: split-K over 64x64 / 32x128 tiles
     const int cfg = tuning().force_tile == 14 ? 6 : 7;
     const int splits = g.partial ? choose_splits(g, cfg == 6 ? 64 : 32, cfg == 6 ? 64 : 128, partial_floats) : 1;

@@ -1021,7 +1021,8 @@ static int infer_enqueue(ctn_ctx* c, ctn_model mi, const int32_t* ids_host, cons
   const ctn_model_desc& d = L.d;
   // stage 0 starts from token ids, every later pipeline stage from the residual stream
   if (L.has_embed() ? (!ids_host || hidden_in) : !hidden_in) return CTN_E_INVAL;
-  if (batch <= 0 || seq <= 0 || seq > d.max_pos || (int64_t)batch * seq > (1 << 24)) return CTN_E_SHAPE;
+  // (the attention launch puts the batch entries on a grid dimension of at most 65535)
+  if (batch <= 0 || batch > 65535 || seq <= 0 || seq > d.max_pos || (int64_t)batch * seq > (1 << 24)) return CTN_E_SHAPE;
   const int M = batch * seq;
   const bool own_logits = !out_is_device && L.has_head();
   Activations act{};
@@ -1646,6 +1647,7 @@ int ctn_engine_replay_async(int32_t n_models, int32_t max_batch, uint64_t budget
 
 // ---- single operations -------------------------------------------------------
 
+static bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 static int op_rc(hipError_t e) { return e == hipSuccess ? CTN_OK : (e == hipErrorInvalidValue ? CTN_E_INVAL : CTN_E_HIP); }
 
 int ctn_op_copy(void* dst, const void* src, uint64_t nbytes, int32_t blocks, void* stream) {
@@ -1667,6 +1669,7 @@ int ctn_op_dma(void* dst, const void* src, uint64_t nbytes, void* stream) {
 int ctn_op_embed(const int32_t* ids, const void* tok, const void* pos, float* x, int32_t M, int32_t seq,
                  int32_t hidden, int32_t vocab_local, int32_t rank, void* stream) {
   if (!ids || !tok || !pos || !x || M < 0) return CTN_E_INVAL;
+  if (!aligned16(tok) || !aligned16(pos) || !aligned16(x) || reinterpret_cast<uintptr_t>(ids) % 4) return CTN_E_INVAL;
   return op_rc(launch_embed(ids, static_cast<const _Float16*>(tok), static_cast<const _Float16*>(pos), x, M, seq,
                             hidden, vocab_local, rank, static_cast<hipStream_t>(stream)));
 }
@@ -1674,6 +1677,9 @@ int ctn_op_embed(const int32_t* ids, const void* tok, const void* pos, float* x,
 int ctn_op_layernorm(const float* x, const void* g, const void* b, void* out, int32_t rows, int32_t hidden,
                      void* stream) {
   if (!x || !g || !b || !out || rows < 0) return CTN_E_INVAL;
+  if (!aligned16(x) || reinterpret_cast<uintptr_t>(g) % 8 || reinterpret_cast<uintptr_t>(b) % 8 ||
+      reinterpret_cast<uintptr_t>(out) % 8)
+    return CTN_E_INVAL;
   return op_rc(launch_layernorm(const_cast<float*>(x), static_cast<const _Float16*>(g), static_cast<const _Float16*>(b),
                                 static_cast<_Float16*>(out), rows, hidden, static_cast<hipStream_t>(stream)));
 }
@@ -1737,6 +1743,7 @@ int ctn_test_op_gemm(const void* A, const void* W, const void* bias, void* out, 
 int ctn_op_attention(const void* qkv, void* out, int32_t batch, int32_t seq, int32_t heads, int32_t head_dim,
                      void* stream) {
   if (!qkv || !out || batch < 0 || seq < 0 || heads < 0) return CTN_E_INVAL;
+  if (!aligned16(qkv) || !aligned16(out)) return CTN_E_INVAL;
   return op_rc(launch_attention(static_cast<const _Float16*>(qkv), static_cast<_Float16*>(out), batch, seq, heads,
                                 head_dim, static_cast<hipStream_t>(stream)));
 }

@@ -442,6 +442,7 @@ def test_degenerate_shapes_no_layers_single_token():
                 assert_close(got, want, f"layers={desc.layers} {batch}x{seq}")
                 rows.append(got.shape)
             assert P.lib().ctn_infer(rig.ctx.h, m, ids.ctypes.data, 0, 3, got.ctypes.data, 0) == -6   # empty batch
+            assert P.lib().ctn_infer(rig.ctx.h, m, ids.ctypes.data, 70000, 1, got.ctypes.data, 0) == -6   # more entries than a launch takes
             rig.ctx.swap_out(m); rig.ctx.wait(m)
             assert rig.ctx.resident_blocks(m) == (0, desc.layers + 1)
         finally:

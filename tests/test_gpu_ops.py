@@ -135,6 +135,29 @@ def test_gemm_rejects_bad_k(stream):
         B.op_gemm(a, a, a, a, 2, 2, 12, P.EPI_BIAS_F16, stream)
 
 
+def test_ops_reject_misaligned_operands(stream):
+    """The kernels read rows in 16-byte pieces; an operand that starts elsewhere is refused on the host,
+    before any launch."""
+    buf = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    base = buf.data_ptr()
+    assert base % 256 == 0
+    ok = base + 4096
+    for a, w, out in ((ok + 2, ok + 8192, ok + 16384), (ok, ok + 8192 + 8, ok + 16384), (ok, ok + 8192, ok + 16384 + 2)):
+        with pytest.raises(P.CtnError) as e:
+            B.op_gemm(a, w, base, out, 8, 16, 64, P.EPI_F32, stream)
+        assert e.value.code == -1
+    with pytest.raises(P.CtnError):
+        B.op_layernorm(ok + 4, base, base, ok + 8192, 2, 128, stream)          # x off a 16-byte boundary
+    with pytest.raises(P.CtnError):
+        B.op_layernorm(ok, base + 2, base, ok + 8192, 2, 128, stream)          # gain off an 8-byte boundary
+    with pytest.raises(P.CtnError):
+        B.op_attention(ok + 8, ok + 32768, 1, 4, 1, 64, stream)
+    with pytest.raises(P.CtnError):
+        B.op_embed(base, ok + 2, ok + 8192, ok + 16384, 2, 2, 64, 8, 0, stream)
+    stream.synchronize()
+    assert int(buf.max()) == 0                                                 # nothing ran
+
+
 @pytest.mark.parametrize("batch,seq,heads,d", [(1, 8, 12, 64), (2, 33, 3, 64), (4, 256, 16, 128), (1, 64, 16, 128),
                                                (2, 129, 2, 128), (16, 128, 10, 128), (1, 300, 2, 64),
                                                (1, 2048, 1, 64), (1, 1, 1, 128), (3, 127, 5, 64),
