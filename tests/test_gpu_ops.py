@@ -98,6 +98,46 @@ def test_layernorm(stream, rows, hidden):
     assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.maximum(np.abs(want), 2.0 ** -14) + 1e-6)
 
 
+@pytest.mark.parametrize("rows,hidden", [(4, 4096), (300, 5120)])
+def test_layernorm_rows_with_outliers(stream, rows, hidden):
+    """Rows shaped like a trained decoder's residual stream: a few channels hundreds of times larger than the
+    rest and a large common offset.  The two-pass variance (mean first, then centred squares) must hold the
+    same bar as on well-behaved rows; a one-pass E[x^2] - E[x]^2 in fp32 would not."""
+    rng = np.random.default_rng(rows + hidden)
+    x = rng.standard_normal((rows, hidden)).astype(np.float32) + 40.0
+    cols = rng.choice(hidden, 6, replace=False)
+    x[:, cols] += (rng.standard_normal((rows, 6)) * 800.0).astype(np.float32)
+    g, b = (1 + 0.1 * rng.standard_normal(hidden)).astype(np.float16), f16(rng, hidden, 0.1)
+    want = O.layer_norm(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64))
+    out = torch.empty(rows, hidden, dtype=torch.float16, device="cuda")
+    B.op_layernorm(dev(x), dev(g), dev(b), out, rows, hidden, stream)
+    stream.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    # the subtraction x - mean loses up to ulp_fp32(|x|) / std of relative accuracy on the small channels
+    slack = 2.0 ** -23 * np.abs(x).max() / x.std(axis=1).min() * 4
+    assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.maximum(np.abs(want), 2.0 ** -14) + 1e-6 + slack)
+
+
+def test_attention_peaked_scores(stream):
+    """Scores tens of units apart (one key dominates every row, as in a trained model's sharp heads): the
+    running maximum keeps every exponent at or below zero and the result stays within the bar."""
+    rng = np.random.default_rng(77)
+    batch, seq, heads, d = 2, 200, 4, 128
+    hl = heads * d
+    qkv = f16(rng, (batch * seq, 3 * hl), 1.0)
+    qkv[:, :hl] *= np.float16(6.0)                       # q: scores ~ N(0, 6^2 * 128) / sqrt(128) -> spread of about 6, tails past 25
+    q, k, v = (qkv[:, i * hl:(i + 1) * hl].astype(np.float64).reshape(batch, seq, hl) for i in range(3))
+    want = O.attention(q, k, v, heads).reshape(batch * seq, hl)
+    out = torch.full((batch * seq, hl), float("nan"), dtype=torch.float16, device="cuda")
+    B.op_attention(dev(qkv), out, batch, seq, heads, d, stream)
+    stream.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= 4e-3 * max(1.0, np.abs(want).max())
+    assert np.abs(got - want).mean() <= 4e-4 * np.abs(want).mean() + 1e-5
+
+
 GEMM_SHAPES = [(8, 520, 4104), (16, 77, 5120), (3, 4096, 8192), (1, 33, 4096), (8, 2304, 768), (1, 128, 64), (33, 200, 72), (16, 50, 40), (17, 4096, 2048), (48, 33, 8192), (49, 640, 264), (64, 6144, 4096), (130, 257, 136),
                (1024, 4096, 2048), (300, 50272 // 4, 512), (2048, 1280, 5120)]
 
