@@ -163,6 +163,8 @@ CONFIGS: Dict[str, dict] = {
     # the paper's hybrid split of OPT-13B (Section 5.1: TP = 2 x PP = 2 on four GPUs): one GPU's share
     "opt13b_tp2_pp2": dict(desc=ShardDesc(40, 5120, 20480, 40, tp=2, rank=0, pp=2, stage=0), batch=16, seq=128,
                            wseed=6, idseed=106),
+    # beyond the paper's sizes: one GPU's share of the 66B member of the family split eight ways (16.5 GB)
+    "opt66b_tp8": dict(desc=ShardDesc(64, 9216, 36864, 72, tp=8, rank=0), batch=4, seq=256, wseed=7, idseed=107),
     "serve8x6.7b_tp2": dict(desc=ShardDesc(32, 4096, 16384, 32, tp=2, rank=0), batch=1, seq=64,
                             n_models=8, wseed=50, budget=20_000_000_000, n_requests=2000,
                             rate=20.0, cv=4.0, zipf=1.5, trace_seed=500, idseed=1000),
